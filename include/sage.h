@@ -1,0 +1,120 @@
+/*
+ * libsage -- SageAttention forward pass (SAGEAttn-B) for AMD gfx950, C ABI.
+ *
+ * The three calls are the three stages of Algorithm 1 of the SageAttention paper:
+ *   sage_smooth_quant_k : "Preprocessing" K = K - mean(K) (Section 4.2) followed by the per-block
+ *                         INT8 quantizer psi_K (Section 3.2);
+ *   sage_quant_q        : psi_Q(Q / sqrt(d)) -- the softmax scale is folded into Q before
+ *                         quantizing (Section 4.6, "Fusion Tricks");
+ *   sage_attn_fwd       : the tiled loop of Algorithm 1: S = Q^ K^^T * dQ * dK, online softmax
+ *                         (Section 3.1), O += P~.to(FP16) V (Section 4.4), O = diag(l)^-1 O.
+ *
+ * Conventions shared by every call
+ *   - All pointers are DEVICE pointers (HIP global memory) unless stated; the library never
+ *     allocates, frees or synchronizes.  Work is enqueued on `stream` (a hipStream_t passed as
+ *     void*; NULL is the default stream) and the call returns immediately.
+ *   - Tensors are contiguous row-major [B, H, N, D] with D innermost; fp16 is IEEE binary16.
+ *     Scales are fp32 [B, H, ceil(N/block)], the K mean is fp32 [B, H, D].
+ *   - The caller owns every buffer.  Outputs are fully overwritten, inputs are never written.
+ *   - Tensor pointers must be 16-byte aligned, scale/mean pointers 4-byte aligned.
+ *   - Inputs must be finite.  N is any positive value up to 2^23 (it need not be a multiple of a
+ *     block size: the last block is short).  D is 64 or 128.
+ *   - Return value: SAGE_OK or an error code below.  Arguments are validated on the host before
+ *     anything is launched, so a failing call has no device side effects.  Nothing throws or aborts.
+ *
+ * Arithmetic (fixed so that an independent implementation can reproduce the INT8 tensors, the
+ * scales, the mean and the int32 scores bit for bit):
+ *   mean[c]  = fp32( (exact sum over the N tokens of K[t,c]) / N ), the division done in fp64;
+ *   Ks       = fp32(K) - mean                         (fp32, not re-rounded to fp16);
+ *   Qs       = fp32(Q) * sm_scale                     (fp32);
+ *   per block of `block` consecutive tokens (all D channels): amax = max |X|,
+ *   delta    = amax / 127   (fp32 division),  r = amax > 0 ? 127 / amax : 0  (fp32 division),
+ *   X^       = clamp(round_half_even(X * r), -127, 127);  an all-zero block has delta = 0, X^ = 0.
+ *   S^       = Q^ K^^T in int32, exact.
+ * The softmax/output stage is specified up to floating-point tolerance only.
+ */
+#ifndef SAGE_H_
+#define SAGE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    SAGE_OK = 0,
+    SAGE_ERR_NULL = 1,        /* a required pointer is NULL                                    */
+    SAGE_ERR_SHAPE = 2,       /* B, H, N or D <= 0, N > 2^23, or B*H*N*D overflows             */
+    SAGE_ERR_UNSUPPORTED = 3, /* D not in {64,128} or a block size the kernels do not cover    */
+    SAGE_ERR_WORKSPACE = 4,   /* workspace_bytes smaller than sage_smooth_quant_k_workspace()  */
+    SAGE_ERR_ALIGN = 5,       /* a pointer is not aligned as required                          */
+    SAGE_ERR_LAUNCH = 6,      /* the HIP runtime reported an error at launch                   */
+    SAGE_ERR_VALUE = 7        /* sm_scale not finite or not positive                           */
+};
+
+/* Human-readable name of a status code (host pointer to a static string; never NULL). */
+const char* sage_status_string(int status);
+
+/*
+ * psi_Q(Q * sm_scale): Section 3.2 (per-block quantizer), Section 4.6 (scale folded into Q),
+ * Algorithm 1 "Quantization".
+ *   q_f16   in  [B,H,N,D] fp16
+ *   q_i8    out [B,H,N,D] int8, values in [-127,127]
+ *   q_scale out [B,H,ceil(N/block_q)] fp32 (delta_Q)
+ *   sm_scale    the softmax scale, normally 1/sqrt(D); finite and > 0
+ *   block_q     tokens per scale: 32, 64 or 128
+ */
+int sage_quant_q(const void* q_f16, int8_t* q_i8, float* q_scale,
+                 int B, int H, int N, int D, float sm_scale, int block_q, void* stream);
+
+/* Bytes of device scratch sage_smooth_quant_k needs for this shape (exact column sums). */
+size_t sage_smooth_quant_k_workspace(int B, int H, int N, int D);
+
+/*
+ * phi_K = psi_K o gamma: Section 4.2 (gamma(K) = K - mean(K), mean over all N tokens of one
+ * (batch, head), also when the attention is causal), then Section 3.2's per-block quantizer.
+ *   k_f16   in  [B,H,N,D] fp16
+ *   k_i8    out [B,H,N,D] int8
+ *   k_scale out [B,H,ceil(N/block_k)] fp32 (delta_K)
+ *   k_mean  out [B,H,D] fp32 (required)
+ *   workspace   device scratch of at least sage_smooth_quant_k_workspace() bytes, 8-byte aligned;
+ *               contents on entry are ignored, contents on return are unspecified.  Two calls
+ *               that share a workspace must be ordered on the same stream.
+ *   block_k     tokens per scale: 32, 64 or 128
+ */
+int sage_smooth_quant_k(const void* k_f16, int8_t* k_i8, float* k_scale, float* k_mean,
+                        void* workspace, size_t workspace_bytes,
+                        int B, int H, int N, int D, int block_k, void* stream);
+
+/*
+ * The loop of Algorithm 1 (with Section 3.1's online softmax and Section 4.4's FP16 P~ V, here
+ * accumulated in fp32 because gfx950's FP16 matrix instructions accumulate in fp32).
+ *   q_i8, q_scale   from sage_quant_q (same block_q)
+ *   k_i8, k_scale   from sage_smooth_quant_k (same block_k)
+ *   v_f16   in  [B,H,N,D] fp16
+ *   o_f16   out [B,H,N,D] fp16
+ *   causal      0: every key is visible; non-zero: key j is visible to query t iff j <= t
+ *   sm_scale    the value that was given to sage_quant_q; it is already inside q_i8/q_scale and is
+ *               NOT applied again here -- it is only validated (finite, > 0)
+ *   block_q     32, 64 or 128;  block_k  64 or 128
+ */
+int sage_attn_fwd(const int8_t* q_i8, const float* q_scale,
+                  const int8_t* k_i8, const float* k_scale,
+                  const void* v_f16, void* o_f16,
+                  int B, int H, int N, int D, int causal, float sm_scale,
+                  int block_q, int block_k, void* stream);
+
+/*
+ * Test hook: the raw int32 scores S^ = Q^ K^^T (Algorithm 1, the Matmul inside the S update)
+ * produced by the same matrix-instruction code path as sage_attn_fwd, without mask.
+ *   s_i32   out [B,H,N,N] int32 -- O(N^2) memory: meant for small N or for sub-problems.
+ */
+int sage_attn_qk_i32_debug(const int8_t* q_i8, const int8_t* k_i8, int32_t* s_i32,
+                           int B, int H, int N, int D, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SAGE_H_ */

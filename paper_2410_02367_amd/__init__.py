@@ -1,0 +1,18 @@
+"""MI355X-native SageAttention forward pass: thin Python binding over the libsage C ABI.
+
+The binding only marshals arguments (torch is used for device memory and streams); every step of
+the path runs in the hand-written gfx950 kernels behind ``include/sage.h``.  There is no CPU
+fallback: if the library is missing the import of :mod:`binding` raises.
+"""
+from .binding import (  # noqa: F401
+    SageError,
+    lib_path,
+    load,
+    sage_attn_fwd,
+    sage_attn_qk_i32_debug,
+    sage_quant_q,
+    sage_smooth_quant_k,
+    sage_smooth_quant_k_workspace,
+    sage_status_string,
+    sageattn,
+)

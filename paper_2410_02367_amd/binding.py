@@ -1,0 +1,151 @@
+"""ctypes binding of libsage.so (declared in include/sage.h).  Argument marshalling only."""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libsage.so")
+_lib = None
+
+EXPORTS = ("sage_status_string", "sage_quant_q", "sage_smooth_quant_k_workspace",
+           "sage_smooth_quant_k", "sage_attn_fwd", "sage_attn_qk_i32_debug")
+
+
+class SageError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {sage_status_string(status)} (status {status})")
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load() -> ctypes.CDLL:
+    """Load the built library; builds it first only if no built library exists."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        from . import build as _build
+        _build.build()
+    lib = ctypes.CDLL(_LIB_PATH)
+    c_int, c_float, c_void_p, c_size_t = ctypes.c_int, ctypes.c_float, ctypes.c_void_p, ctypes.c_size_t
+    lib.sage_status_string.restype = ctypes.c_char_p
+    lib.sage_status_string.argtypes = [c_int]
+    lib.sage_quant_q.restype = c_int
+    lib.sage_quant_q.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_float, c_int, c_void_p]
+    lib.sage_smooth_quant_k_workspace.restype = c_size_t
+    lib.sage_smooth_quant_k_workspace.argtypes = [c_int, c_int, c_int, c_int]
+    lib.sage_smooth_quant_k.restype = c_int
+    lib.sage_smooth_quant_k.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t,
+                                        c_int, c_int, c_int, c_int, c_int, c_void_p]
+    lib.sage_attn_fwd.restype = c_int
+    lib.sage_attn_fwd.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                  c_int, c_int, c_int, c_int, c_int, c_float, c_int, c_int, c_void_p]
+    lib.sage_attn_qk_i32_debug.restype = c_int
+    lib.sage_attn_qk_i32_debug.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_void_p]
+    _lib = lib
+    return lib
+
+
+def sage_status_string(status: int) -> str:
+    return load().sage_status_string(int(status)).decode()
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _dev(t: torch.Tensor, dtype, name: str) -> int:
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise TypeError(f"{name}: expected a contiguous {dtype} tensor in device memory")
+    return t.data_ptr()
+
+
+def _nblk(N: int, block: int) -> int:
+    return (N + block - 1) // block
+
+
+def sage_quant_q(q: torch.Tensor, sm_scale: float, block_q: int = 128, q_i8=None, q_scale=None, stream=None):
+    """psi_Q(Q * sm_scale) -> (q_i8 [B,H,N,D] int8, q_scale [B,H,ceil(N/block_q)] fp32)."""
+    B, H, N, D = q.shape
+    if q_i8 is None:
+        q_i8 = torch.empty((B, H, N, D), dtype=torch.int8, device=q.device)
+    if q_scale is None:
+        q_scale = torch.empty((B, H, _nblk(N, block_q)), dtype=torch.float32, device=q.device)
+    st = load().sage_quant_q(_dev(q, torch.float16, "q"), _dev(q_i8, torch.int8, "q_i8"),
+                             _dev(q_scale, torch.float32, "q_scale"), B, H, N, D, float(sm_scale),
+                             int(block_q), _stream(stream))
+    if st != 0:
+        raise SageError(st, "sage_quant_q")
+    return q_i8, q_scale
+
+
+def sage_smooth_quant_k_workspace(B: int, H: int, N: int, D: int) -> int:
+    return int(load().sage_smooth_quant_k_workspace(B, H, N, D))
+
+
+def sage_smooth_quant_k(k: torch.Tensor, block_k: int = 64, k_i8=None, k_scale=None, k_mean=None,
+                        workspace=None, stream=None):
+    """phi_K(K) -> (k_i8 int8, k_scale [B,H,ceil(N/block_k)] fp32, k_mean [B,H,D] fp32)."""
+    B, H, N, D = k.shape
+    if k_i8 is None:
+        k_i8 = torch.empty((B, H, N, D), dtype=torch.int8, device=k.device)
+    if k_scale is None:
+        k_scale = torch.empty((B, H, _nblk(N, block_k)), dtype=torch.float32, device=k.device)
+    if k_mean is None:
+        k_mean = torch.empty((B, H, D), dtype=torch.float32, device=k.device)
+    need = sage_smooth_quant_k_workspace(B, H, N, D)
+    if workspace is None:
+        workspace = torch.empty((max(need, 8) + 7) // 8, dtype=torch.int64, device=k.device)
+    ws_bytes = workspace.numel() * workspace.element_size()
+    st = load().sage_smooth_quant_k(_dev(k, torch.float16, "k"), _dev(k_i8, torch.int8, "k_i8"),
+                                    _dev(k_scale, torch.float32, "k_scale"), _dev(k_mean, torch.float32, "k_mean"),
+                                    workspace.data_ptr(), ws_bytes, B, H, N, D, int(block_k), _stream(stream))
+    if st != 0:
+        raise SageError(st, "sage_smooth_quant_k")
+    return k_i8, k_scale, k_mean
+
+
+def sage_attn_fwd(q_i8, q_scale, k_i8, k_scale, v, causal: bool, sm_scale: float,
+                  block_q: int = 128, block_k: int = 64, out=None, stream=None):
+    """Algorithm 1's loop on pre-quantized Q^, K^ and fp16 V -> O [B,H,N,D] fp16."""
+    B, H, N, D = v.shape
+    if out is None:
+        out = torch.empty((B, H, N, D), dtype=torch.float16, device=v.device)
+    st = load().sage_attn_fwd(_dev(q_i8, torch.int8, "q_i8"), _dev(q_scale, torch.float32, "q_scale"),
+                              _dev(k_i8, torch.int8, "k_i8"), _dev(k_scale, torch.float32, "k_scale"),
+                              _dev(v, torch.float16, "v"), _dev(out, torch.float16, "out"),
+                              B, H, N, D, int(bool(causal)), float(sm_scale), int(block_q), int(block_k),
+                              _stream(stream))
+    if st != 0:
+        raise SageError(st, "sage_attn_fwd")
+    return out
+
+
+def sage_attn_qk_i32_debug(q_i8, k_i8, s_i32=None, stream=None):
+    """Raw int32 scores Q^ K^^T [B,H,N,N] through the attention kernel's MFMA path (test hook)."""
+    B, H, N, D = q_i8.shape
+    if s_i32 is None:
+        s_i32 = torch.empty((B, H, N, N), dtype=torch.int32, device=q_i8.device)
+    st = load().sage_attn_qk_i32_debug(_dev(q_i8, torch.int8, "q_i8"), _dev(k_i8, torch.int8, "k_i8"),
+                                       _dev(s_i32, torch.int32, "s_i32"), B, H, N, D, _stream(stream))
+    if st != 0:
+        raise SageError(st, "sage_attn_qk_i32_debug")
+    return s_i32
+
+
+def sageattn(q, k, v, causal: bool = False, sm_scale: float | None = None, block_q: int = 128, block_k: int = 64):
+    """Convenience: the three library calls in order (pre-pass on K, pre-pass on Q, attention)."""
+    D = q.shape[-1]
+    if sm_scale is None:
+        sm_scale = float(torch.tensor(1.0, dtype=torch.float32) / torch.sqrt(torch.tensor(float(D), dtype=torch.float32)))
+    k_i8, k_scale, _ = sage_smooth_quant_k(k, block_k)
+    q_i8, q_scale = sage_quant_q(q, sm_scale, block_q)
+    return sage_attn_fwd(q_i8, q_scale, k_i8, k_scale, v, causal, sm_scale, block_q, block_k)

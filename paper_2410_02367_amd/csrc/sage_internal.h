@@ -1,0 +1,19 @@
+// Internal launch interface between the C-ABI entry points and the gfx950 kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sage {
+
+// Pre-pass (HBM-bound).  All return the hipError_t of the launch.
+hipError_t launch_quant_q(const void* q, int8_t* qq, float* qscale, int BH, int N, int D,
+                          float sm_scale, int block, hipStream_t st);
+hipError_t launch_smooth_quant_k(const void* k, int8_t* kq, float* kscale, float* kmean,
+                                 long long* sums, int BH, int N, int D, int block, hipStream_t st);
+
+// Fused attention (MFMA-bound).  sdump != nullptr selects the int32 score dump.
+hipError_t launch_attn(const int8_t* qq, const float* qscale, const int8_t* kq, const float* kscale,
+                       const void* v, void* o, int32_t* sdump, int BH, int N, int D, int causal,
+                       int block_q, int block_k, hipStream_t st);
+
+}  // namespace sage

@@ -1,0 +1,99 @@
+"""GPU parity: libsage (through its C ABI) against the CPU oracle on the same seeded inputs.
+
+Bit-exact: INT8 tensors, scales, K mean, int32 scores.  Output: max-abs <= 2e-3 and cosine >= 0.9999
+against the oracle's Algorithm-1 level (which emulates the same quantization)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2410_02367_amd as sage
+import sage_inputs as si
+from gpu_util import ABS_TOL, assert_output_close, assert_prepass_bit_exact, bits, to_dev
+
+pytestmark = pytest.mark.gpu
+
+SMALL = [
+    si.WORKLOADS["cfg1_tiny"],
+    si.custom("ragged_d128", 1, 3, 333, 128, False, 128, 64, seed=si.BASE_SEED + 11),
+    si.custom("ragged_d64_causal", 2, 2, 457, 64, True, 128, 64, seed=si.BASE_SEED + 12),
+    si.custom("causal_d128", 1, 2, 640, 128, True, 128, 64, k_noise=1.0, k_bias=4.0, outlier_frac=0.01,
+              outlier_gain=8.0, seed=si.BASE_SEED + 13),
+    si.custom("blocks_64_128", 1, 2, 300, 64, True, 64, 128, seed=si.BASE_SEED + 14),
+    si.custom("blocks_32_64", 1, 1, 200, 128, False, 32, 64, seed=si.BASE_SEED + 15),
+    si.custom("one_token", 1, 1, 1, 64, True, 128, 64, seed=si.BASE_SEED + 16),
+    si.custom("short", 2, 1, 31, 128, False, 128, 64, seed=si.BASE_SEED + 17),
+]
+
+
+@pytest.mark.parametrize("w", SMALL, ids=lambda w: w.name)
+def test_small_workloads_full_parity(w):
+    print(f"[case] {w.name} B{w.B} H{w.H} N{w.N} D{w.D} causal={w.causal} blocks {w.block_q}x{w.block_k}", flush=True)
+    q, k, v = si.full(w)
+    (q_i8, q_scale, k_i8, k_scale, k_mean), (qq, qs, kq, ks, km) = assert_prepass_bit_exact(
+        q, k, w.sm_scale, w.block_q, w.block_k)
+    # int32 scores through the attention kernel's MFMA path
+    s_gpu = sage.sage_attn_qk_i32_debug(q_i8, k_i8)
+    torch.cuda.synchronize()
+    s_gpu = s_gpu.cpu().numpy()
+    for b in range(w.B):
+        for h in range(w.H):
+            assert np.array_equal(s_gpu[b, h], oracle.qk_i32(qq[b, h], kq[b, h])), "int32 scores differ"
+    # output
+    o_gpu = sage.sage_attn_fwd(q_i8, q_scale, k_i8, k_scale, to_dev(v), w.causal, w.sm_scale, w.block_q, w.block_k)
+    torch.cuda.synchronize()
+    o_ref = oracle.attn_l2(qq, qs, kq, ks, v, w.causal, w.block_q, w.block_k)
+    assert_output_close(o_gpu.cpu().numpy(), o_ref, w.name)
+
+
+def test_causal_first_row_is_v0_bit_exact_and_constant_k_gives_prefix_means():
+    print("[case] causal row 0 / constant K", flush=True)
+    N, D = 300, 64
+    g = np.random.default_rng(5)
+    q = g.standard_normal((1, 1, N, D)).astype(np.float16)
+    v = g.standard_normal((1, 1, N, D)).astype(np.float16)
+    k = np.tile(g.standard_normal((1, 1, 1, D)).astype(np.float16), (1, 1, N, 1))
+    (q_i8, q_scale, k_i8, k_scale, k_mean), _ = assert_prepass_bit_exact(q, k, 0.125, 128, 64)
+    assert int(k_i8.abs().max()) == 0 and float(k_scale.abs().max()) == 0.0     # all-zero blocks
+    o = sage.sage_attn_fwd(q_i8, q_scale, k_i8, k_scale, to_dev(v), True, 0.125, 128, 64).cpu().numpy()
+    assert np.array_equal(bits(o[0, 0, 0]), bits(v[0, 0, 0]))
+    prefix = np.cumsum(v[0, 0].astype(np.float64), 0) / np.arange(1, N + 1)[:, None]
+    assert np.abs(o[0, 0].astype(np.float64) - prefix).max() <= ABS_TOL
+    o_nc = sage.sage_attn_fwd(q_i8, q_scale, k_i8, k_scale, to_dev(v), False, 0.125, 128, 64).cpu().numpy()
+    assert np.abs(o_nc[0, 0].astype(np.float64) - v[0, 0].astype(np.float64).mean(0)[None]).max() <= ABS_TOL
+
+
+def test_results_are_deterministic_run_to_run():
+    print("[case] determinism", flush=True)
+    w = si.custom("det", 1, 4, 1000, 128, True, 128, 64, seed=si.BASE_SEED + 20)
+    q, k, v = si.full(w)
+    qd, kd, vd = to_dev(q), to_dev(k), to_dev(v)
+    outs = []
+    for _ in range(3):
+        k_i8, k_scale, k_mean = sage.sage_smooth_quant_k(kd, w.block_k)
+        q_i8, q_scale = sage.sage_quant_q(qd, w.sm_scale, w.block_q)
+        o = sage.sage_attn_fwd(q_i8, q_scale, k_i8, k_scale, vd, True, w.sm_scale, w.block_q, w.block_k)
+        outs.append([x.cpu().numpy().copy() for x in (k_i8, k_scale, k_mean, q_i8, q_scale, o)])
+    for other in outs[1:]:
+        for a, b in zip(outs[0], other):
+            assert np.array_equal(a.view(np.uint8), b.view(np.uint8))
+
+
+def test_host_side_errors_leave_no_side_effects():
+    print("[case] error paths", flush=True)
+    q = torch.zeros((1, 1, 64, 64), dtype=torch.float16, device="cuda")
+    with pytest.raises(sage.SageError) as e:
+        sage.sage_quant_q(q, 0.125, block_q=48)
+    assert e.value.status == 3
+    with pytest.raises(sage.SageError) as e:
+        sage.sage_quant_q(q, float("nan"), block_q=64)
+    assert e.value.status == 7
+    q96 = torch.zeros((1, 1, 64, 96), dtype=torch.float16, device="cuda")
+    with pytest.raises(sage.SageError) as e:
+        sage.sage_quant_q(q96, 0.125, block_q=64)
+    assert e.value.status == 3
+    ws = torch.zeros(1, dtype=torch.int64, device="cuda")
+    with pytest.raises(sage.SageError) as e:
+        sage.sage_smooth_quant_k(q, 64, workspace=ws)
+    assert e.value.status == 4
+    torch.cuda.synchronize()

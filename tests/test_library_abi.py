@@ -1,0 +1,72 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every symbol the header declares,
+and validates arguments on the host (no kernel is launched here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2410_02367_amd import binding
+    return binding.load()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "sage.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sage_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_symbols()
+    assert {"sage_quant_q", "sage_smooth_quant_k", "sage_attn_fwd"} <= set(names)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_binding_covers_the_header():
+    from paper_2410_02367_amd import binding
+    assert sorted(binding.EXPORTS) == declared_symbols()
+    import paper_2410_02367_amd as pkg
+    for n in binding.EXPORTS:
+        assert callable(getattr(pkg, n))
+
+
+def test_status_strings(lib):
+    assert lib.sage_status_string(0) == b"SAGE_OK"
+    for code in range(1, 8):
+        assert lib.sage_status_string(code).startswith(b"SAGE_ERR_")
+    assert lib.sage_status_string(99) == b"SAGE_ERR_UNKNOWN"
+
+
+def test_workspace_query(lib):
+    assert lib.sage_smooth_quant_k_workspace(1, 2, 256, 64) == 2 * 64 * 8
+    assert lib.sage_smooth_quant_k_workspace(1, 8, 131072, 128) == 8 * 128 * 8
+    assert lib.sage_smooth_quant_k_workspace(0, 8, 10, 128) == 0
+
+
+def test_host_validation_rejects_bad_arguments_before_any_launch(lib):
+    f = ctypes.c_float
+    good = ctypes.c_void_p(0x1000)          # never dereferenced: validation fails first
+    odd = ctypes.c_void_p(0x1004)
+    # NULL pointers
+    assert lib.sage_quant_q(None, good, good, 1, 1, 64, 64, f(0.125), 64, None) == 1
+    assert lib.sage_attn_fwd(good, good, good, good, None, good, 1, 1, 64, 64, 0, f(0.125), 128, 64, None) == 1
+    assert lib.sage_smooth_quant_k(good, good, good, good, None, 0, 1, 1, 64, 64, 64, None) == 1
+    # shapes
+    assert lib.sage_quant_q(good, good, good, 0, 1, 64, 64, f(0.125), 64, None) == 2
+    assert lib.sage_quant_q(good, good, good, 1, 1, (1 << 23) + 1, 64, f(0.125), 64, None) == 2
+    assert lib.sage_quant_q(good, good, good, 1, 1, 64, 96, f(0.125), 64, None) == 3
+    assert lib.sage_quant_q(good, good, good, 1, 1, 64, 64, f(0.125), 48, None) == 3
+    assert lib.sage_attn_fwd(good, good, good, good, good, good, 1, 1, 64, 64, 0, f(0.125), 128, 32, None) == 3
+    # values
+    assert lib.sage_quant_q(good, good, good, 1, 1, 64, 64, f(float("inf")), 64, None) == 7
+    assert lib.sage_attn_fwd(good, good, good, good, good, good, 1, 1, 64, 64, 0, f(-1.0), 128, 64, None) == 7
+    # workspace, alignment
+    assert lib.sage_smooth_quant_k(good, good, good, good, good, 8, 1, 1, 64, 64, 64, None) == 4
+    assert lib.sage_quant_q(odd, good, good, 1, 1, 64, 64, f(0.125), 64, None) == 5
+    assert lib.sage_attn_qk_i32_debug(good, odd, good, 1, 1, 64, 64, None) == 5
