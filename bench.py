@@ -1,0 +1,186 @@
+#!/usr/bin/env python3
+"""Benchmark of the SageAttention forward hot path on one MI355X.
+
+A step = one pass of the whole path (K pre-pass, Q pre-pass, fused attention) over one batch of
+synthetic input that is already resident in HBM.  Prints ONE JSON line.
+
+  metric   attention TOPS = 4*B*H*N^2*D / t (halved when causal), t = time of one step
+  roofline the fused attention kernel against the dense INT8 MFMA peak, its duration measured
+           with HIP events on the launch stream inside the timed region
+  cpu_baseline the CPU oracle timed on a bounded sample of the same workload
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+INT8_PEAK_TOPS = 5000.0      # MI355X dense INT8 MFMA, published
+FP16_PEAK_TFLOPS = 2500.0    # MI355X dense FP16 MFMA, published
+
+
+def cpu_baseline(w, seconds_budget=20.0):
+    """Oracle (Algorithm-1 level, as it stands) on one head of the workload: the full pre-pass of that
+    head plus a spread of Q blocks, scaled to the head's block-pair count."""
+    import numpy as np
+
+    import oracle
+    import sage_inputs as si
+
+    q, k, v = si.slab(w, 0, 0)
+    t0 = time.perf_counter()
+    kq, ks, km = oracle.smooth_quant_k(k[None, None], w.block_k)
+    qq, qs = oracle.quant_q(q[None, None], w.sm_scale, w.block_q)
+    t_pre = time.perf_counter() - t0
+    Tm = (w.N + w.block_q - 1) // w.block_q
+    Tn = (w.N + w.block_k - 1) // w.block_k
+
+    def pairs(i):
+        if not w.causal:
+            return Tn
+        last_row = min(w.N, (i + 1) * w.block_q) - 1
+        return last_row // w.block_k + 1
+
+    total_pairs = sum(pairs(i) for i in range(Tm))
+    # probe one block to size the sample
+    mid = Tm // 2
+    t0 = time.perf_counter()
+    oracle.attn_l2_slab(qq[0, 0], qs[0, 0], kq[0, 0], ks[0, 0], v, w.causal, w.block_q, w.block_k, q_blocks=[mid])
+    t_one = time.perf_counter() - t0
+    per_pair = t_one / pairs(mid)
+    threads = oracle.num_threads()
+    avg_pairs = total_pairs / Tm
+    n_blocks = int(max(threads, min(Tm, seconds_budget * threads / max(per_pair * avg_pairs, 1e-9))))
+    n_blocks = max(threads, (n_blocks // threads) * threads)
+    blocks = sorted(set(np.linspace(0, Tm - 1, n_blocks).round().astype(int).tolist()))
+    t0 = time.perf_counter()
+    oracle.attn_l2_slab(qq[0, 0], qs[0, 0], kq[0, 0], ks[0, 0], v, w.causal, w.block_q, w.block_k, q_blocks=blocks)
+    t_blocks = time.perf_counter() - t0
+    sampled_pairs = sum(pairs(i) for i in blocks)
+    t_head = t_pre + t_blocks * total_pairs / sampled_pairs
+    ops_head = w.ops / (w.B * w.H)
+    return {
+        "value": ops_head / t_head / 1e12,
+        "unit": "TOPS",
+        "cores": threads,
+        "kind": "oracle",
+        "sample": (f"1 of {w.B * w.H} heads: full pre-pass ({t_pre:.2f}s) + {len(blocks)} of {Tm} Q blocks "
+                   f"({t_blocks:.2f}s, {sampled_pairs} of {total_pairs} block pairs), scaled to the head"),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg3_prefill16k")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (one process, no collectives); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2410_02367_amd as sage
+    import sage_inputs as si
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the library has no CPU path", file=sys.stderr)
+        sys.exit(2)
+    sage.load()
+    w = si.WORKLOADS[args.workload]
+    torch.cuda.set_device(0)
+    q, k, v = si.full(w)
+    qd, kd, vd = (torch.from_numpy(a).cuda() for a in (q, k, v))
+    del q, k, v
+    B, H, N, D = w.B, w.H, w.N, w.D
+    nbq, nbk = (N + w.block_q - 1) // w.block_q, (N + w.block_k - 1) // w.block_k
+    q_i8 = torch.empty((B, H, N, D), dtype=torch.int8, device="cuda")
+    k_i8 = torch.empty_like(q_i8)
+    q_scale = torch.empty((B, H, nbq), dtype=torch.float32, device="cuda")
+    k_scale = torch.empty((B, H, nbk), dtype=torch.float32, device="cuda")
+    k_mean = torch.empty((B, H, D), dtype=torch.float32, device="cuda")
+    ws = torch.empty(sage.sage_smooth_quant_k_workspace(B, H, N, D) // 8, dtype=torch.int64, device="cuda")
+    out = torch.empty((B, H, N, D), dtype=torch.float16, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+          for _ in range(args.steps)]
+
+    def step(i=None):
+        if i is not None:
+            ev[i][0].record(stream)
+        sage.sage_smooth_quant_k(kd, w.block_k, k_i8, k_scale, k_mean, ws, stream)
+        sage.sage_quant_q(qd, w.sm_scale, w.block_q, q_i8, q_scale, stream)
+        if i is not None:
+            ev[i][1].record(stream)
+        sage.sage_attn_fwd(q_i8, q_scale, k_i8, k_scale, vd, w.causal, w.sm_scale, w.block_q, w.block_k, out, stream)
+        if i is not None:
+            ev[i][2].record(stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    attn_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / args.steps
+    pre_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / args.steps
+    assert bool(torch.isfinite(out[0, 0, :64].float()).all())
+
+    ops = w.ops
+    value = ops / (ms_per_step * 1e-3) / 1e12
+    attn_tops = ops / (attn_ms * 1e-3) / 1e12
+    result = {
+        "metric": "attention TOPS (4*B*H*N^2*D/t, halved if causal) at N=16K D=128; % MFMA peak",
+        "value": value,
+        "unit": "TOPS",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int8 QK^T (int32 acc) + fp16 PV (fp32 acc)",
+        "data": "synthetic",
+        "config": {"workload": f"{w.name}: B={B} H={H} N={N} D={D} causal={w.causal} fp16 in/out, "
+                               f"block_q={w.block_q} block_k={w.block_k}; step = K pre-pass + Q pre-pass + attention"},
+        "attn_kernel_ms": attn_ms,
+        "prepass_ms": pre_ms,
+        "attn_only_tops": attn_tops,
+        "pct_int8_mfma_peak_whole_step": 100.0 * value / INT8_PEAK_TOPS,
+        "roofline": {
+            "bound": "mfma",
+            "achieved": attn_tops,
+            "peak": INT8_PEAK_TOPS,
+            "unit": "TFLOP/s",
+            "frac": attn_tops / INT8_PEAK_TOPS,
+            "traffic": None,
+            "kernel": "sage_attn_kernel",
+            "note": ("achieved = counted ops (half INT8 ops, half FP16 flops) / mean attention-kernel time from HIP "
+                     "events on the launch stream; peak = dense INT8 MFMA. Against the blended ceiling of this "
+                     "algorithm (2/3 of the INT8 peak, because P~V runs at the FP16 rate) the fraction is "
+                     f"{attn_tops / (INT8_PEAK_TOPS * 2 / 3):.4f}"),
+        },
+        "paper_context": "paper reports ~2.1x over FlashAttention2 and ~2.7x over xformers on RTX4090 (340 TOPS, 52% of its INT8 peak)",
+    }
+    if not args.no_cpu_baseline:
+        del qd, kd, vd
+        result["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()
