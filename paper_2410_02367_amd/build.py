@@ -14,6 +14,7 @@ HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-ffp-contract=off",                                   # quantizer arithmetic: one rounding per operation
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed-fp32 code generation
+    "-mllvm", "-amdgpu-mfma-vgpr-form",                    # scores must land in VALU-readable registers
     "-Wall",
 ]
 
