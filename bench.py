@@ -23,6 +23,12 @@ if ROOT not in sys.path:
 
 INT8_PEAK_TOPS = 5000.0      # MI355X dense INT8 MFMA, published
 FP16_PEAK_TFLOPS = 2500.0    # MI355X dense FP16 MFMA, published
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
+
+# HBM bytes per attention launch from the hardware counters (FETCH_SIZE and WRITE_SIZE, one profiler
+# run each, scaled by what the same counter reads for a 1 GiB copy kernel); the profiler cannot run
+# inside this script, so the figure of the committed summary under profiles/ is carried here.
+ATTN_TRAFFIC_BYTES = {"cfg3_prefill16k": 508.8e6}
 
 
 def cpu_baseline(w, seconds_budget=20.0):
@@ -82,6 +88,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg3_prefill16k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch one plain elementwise copy kernel of 1 GiB before the warm-up, so that a "
+                         "hardware-counter run holds a kernel of known HBM traffic beside the library's kernels")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (one process, no collectives); --gpus must be 1", file=sys.stderr)
@@ -126,6 +135,14 @@ def main():
         if i is not None:
             ev[i][2].record(stream)
 
+    if args.calibrate_copy:
+        # y = x + 0 over 2^28 int32: reads 1 GiB and writes 1 GiB, nothing else
+        cx = torch.ones(1 << 28, dtype=torch.int32, device="cuda")
+        cy = torch.empty_like(cx)
+        torch.add(cx, 0, out=cy)
+        torch.cuda.synchronize()
+        del cx, cy
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -167,12 +184,22 @@ def main():
             "peak": INT8_PEAK_TOPS,
             "unit": "TFLOP/s",
             "frac": attn_tops / INT8_PEAK_TOPS,
-            "traffic": None,
+            "traffic": ATTN_TRAFFIC_BYTES.get(w.name),
+            "traffic_unit": "bytes per launch (algorithmic: %.1f MB)" % (6.0 * B * H * N * D / 1e6),
             "kernel": "sage_attn_kernel",
             "note": ("achieved = counted ops (half INT8 ops, half FP16 flops) / mean attention-kernel time from HIP "
                      "events on the launch stream; peak = dense INT8 MFMA. Against the blended ceiling of this "
                      "algorithm (2/3 of the INT8 peak, because P~V runs at the FP16 rate) the fraction is "
                      f"{attn_tops / (INT8_PEAK_TOPS * 2 / 3):.4f}"),
+        },
+        "prepass_roofline": {
+            "bound": "hbm",
+            "achieved": 8.0 * B * H * N * D / (pre_ms * 1e-3) / 1e9,
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": 8.0 * B * H * N * D / (pre_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "note": "algorithmic bytes: Q 2 read + 1 written, K 2 + 2 read (mean is a global dependency) + 1 written "
+                    "= 8 B per element pair; the inputs are not rotated, so part of K's second read hits the last-level cache",
         },
         "paper_context": "paper reports ~2.1x over FlashAttention2 and ~2.7x over xformers on RTX4090 (340 TOPS, 52% of its INT8 peak)",
     }

@@ -15,7 +15,7 @@ HIPCC_FLAGS = [
     "-ffp-contract=off",                                   # quantizer arithmetic: one rounding per operation
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed-fp32 code generation
     "-mllvm", "-amdgpu-mfma-vgpr-form",                    # scores must land in VALU-readable registers
-    "-Wall",
+    "-Wall", "-Wno-unused-variable",
 ]
 
 
