@@ -1,10 +1,11 @@
 // Fused SageAttention forward kernel for gfx950 (Algorithm 1, inner loops).
 //
 // Work decomposition
-//   One workgroup = 4 wavefronts (one per SIMD, so each may use the full 512-register budget)
-//   = 256 query rows, 64 per wavefront as two 32-row sub-tiles.  Key/value tiles of 64 tokens are
-//   double-buffered in LDS and shared by the 4 wavefronts; every K^ / V^T operand read from LDS
-//   feeds two matrix instructions (one per query sub-tile).
+//   One workgroup = 8 wavefronts (two per SIMD, 256 registers each) = 256 query rows, 32 per
+//   wavefront (a build option gives 4 wavefronts of 64 rows instead, each LDS operand then feeding
+//   two matrix instructions).  Key/value tiles of 64 tokens are double-buffered in LDS and shared
+//   by all wavefronts; they are brought in by asynchronous global->LDS loads that bypass the
+//   register file.
 //   Scores are computed TRANSPOSED, S^T = K^ Q^^T, with the 32x32x32 INT8 matrix instruction: each
 //   lane then owns one query column and 16 keys per 32-key sub-tile, so
 //     - row max / row sum need one cross-lane step (lane <-> lane+32),
@@ -14,22 +15,39 @@
 //   V^T operands come from the row-major V tile in LDS through the transposing LDS read.
 //
 // Schedule (software pipeline inside every wavefront)
-//   On this chip the softmax arithmetic (VALU + transcendental) of a tile costs about as many
-//   issue cycles as its matrix instructions.  A wavefront that alternates a matrix phase and a
-//   softmax phase leaves one pipe idle at any time (and two such wavefronts on a SIMD fall into
-//   lock-step instead of complementing each other).  So every wavefront runs three tiles at once:
-//   while the softmax of tile j is computed (VALU), the matrix pipe is fed with P~V of tile j-1
-//   and K^Q^^T of tile j+1.  A step is a flat sequence of LDS operands, each feeding one matrix
-//   instruction per query sub-tile; after every matrix instruction comes one "chunk" of softmax
-//   VALU work (2 scores: 2 FMA, 2 exp2, 1 pack, 1 row-sum), fenced so the order survives:
-//        slot A  PV_{j-1}[ 0:16]                      slot D  PV_{j-1}[48:64] | softmax_j[32:48]
-//        slot B  PV_{j-1}[16:32] | softmax_j[ 0:16]   slot E  QK_{j+1}[ 0:32] | softmax_j[48:64]
-//        slot C  PV_{j-1}[32:48] | softmax_j[16:32]   slot F  QK_{j+1}[32:64]
-//   S and P~ live in single register buffers: a 16-key group of P~_{j-1} is consumed by its
-//   matrix instructions one slot before the softmax overwrites it, and each half of S_{j+1} is
-//   produced after the softmax has consumed that half of S_j.
+//   A wavefront issues its instructions in order, about one per 5 cycles whatever its kind, and a
+//   matrix instruction overlaps only with what follows it in the same stream or with the other
+//   wavefront of the SIMD.  Every wavefront therefore runs three tiles at once: the softmax of
+//   tile j (VALU) is spread between the matrix instructions of P~V of tile j-1 and K^Q^^T of tile
+//   j+1.  A step is a flat sequence of LDS operands, each feeding one matrix instruction per query
+//   sub-tile, with VALU work after every matrix instruction, fenced so the order survives:
+//        slot A  PV_{j-1}[ 0:16] | row maximum of S_j   slot D  PV_{j-1}[48:64] | softmax_j[32:48]
+//        slot B  PV_{j-1}[16:32] | softmax_j[ 0:16]     slot E  QK_{j+1}[ 0:32] | softmax_j[48:64]
+//        slot C  PV_{j-1}[32:48] | softmax_j[16:32]     slot F  QK_{j+1}[32:64]
+//   (a softmax "chunk" = 2 scores: 2 FMA, 2 exp2, 1 pack).  S and P~ live in single register
+//   buffers: a 16-key group of P~_{j-1} is consumed by its matrix instructions before the softmax
+//   overwrites it, and each half of S_{j+1} is produced after the softmax has consumed that half
+//   of S_j.
 //   The running maximum is only raised when a row's tile maximum exceeds it by more than 2^8
-//   (P~ <= 256 fits FP16 comfortably); the O rescale is then a rare, wave-uniform branch.
+//   (P~ <= 256 fits FP16 comfortably); the rescale of O is then a rare branch between slots A and B.
+//
+// Register files
+//   The matrix instructions are written as inline assembly so that the register file of every
+//   operand is chosen by hand: O^T (QS*DT*16 registers), the row sums, the resident Q^ operands
+//   and the ones operand are pinned in the accumulator file (AGPRs) -- only matrix instructions
+//   touch them in the steady state, so there are no AGPR<->VGPR moves at all -- while scores, P~,
+//   LDS operands and staging data are ordinary variables in VGPRs.
+//   The O^T / row-sum statements name their accumulator as an INPUT and update that register
+//   behind the compiler's back: to the compiler the accumulators are loop-invariant values, which
+//   it keeps in one place; refresh() ("+a") tells it the truth before C++ code reads them (rare
+//   rescale, epilogue).  This only works while the compiler never copies such a value to a second
+//   register inside the loops, so the build inspects the generated assembly for that.
+//   The compiler does not know these are matrix instructions, so the waits it would insert are
+//   placed by hand:
+//     - 12 wait states between a matrix instruction that writes a register and a VALU or memory
+//       instruction that reads or writes it (score_fence(), refresh());
+//     - 2 wait states between a VALU write of a register and a matrix instruction reading it --
+//       guaranteed by construction: P~ is packed at least one slot before it is consumed.
 //
 // Register layout facts used below (established on hardware by a probe):
 //   32x32 result:  lane l, register r  ->  row 8*(r/4) + 4*(l/32) + r%4, column l%32
@@ -49,6 +67,7 @@
 //     v_dot2c run on the matrix pipe as well, but block it for VALU work -- measured.)
 #include "sage_internal.h"
 #include <type_traits>
+#include <utility>
 
 namespace sage {
 
@@ -57,44 +76,36 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 typedef _Float16 v4h __attribute__((ext_vector_type(4)));
-typedef __fp16 v2hh __attribute__((ext_vector_type(2)));
 typedef short v4s __attribute__((ext_vector_type(4)));
 
 #define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
 
+// Build-time shape of a workgroup.  The default (8 wavefronts of 32 rows: two wavefronts per SIMD,
+// 256 registers each) measured slightly faster than 4 wavefronts of 64 rows (one per SIMD, every
+// LDS operand shared by two matrix instructions); both pass the same tests.
 #ifndef SAGE_NWAVES
-#define SAGE_NWAVES 4
+#define SAGE_NWAVES 8
 #endif
 #ifndef SAGE_QS
-#define SAGE_QS 2
-#endif
-#ifndef SAGE_PHASED
-#define SAGE_PHASED 0
-#endif
-#ifndef SAGE_PRIO
-#define SAGE_PRIO 0
-#endif
-// The magic accumulator seed must stay resident.  With one wavefront per SIMD (512 registers) it is
-// pinned in the accumulator half of the file; with two per SIMD the kernel must not touch AGPRs at
-// all, or the compiler splits the 256-register budget 128/128.
-#if SAGE_NWAVES * SAGE_QS * 32 / 64 <= 4 && SAGE_QS >= 2
-#define SAGE_PIN_MAGIC(m) asm volatile("" : "+a"(m))
-#else
-#define SAGE_PIN_MAGIC(m) asm volatile("" : "+v"(m))
-#endif
-#ifndef SAGE_LAUNCH_BOUNDS
-#define SAGE_LAUNCH_BOUNDS __launch_bounds__(SAGE_NWAVES * 64, 1)
+#define SAGE_QS 1
 #endif
 constexpr int NWAVES = SAGE_NWAVES;    // wavefronts per workgroup
 constexpr int QS = SAGE_QS;            // 32-row query sub-tiles per wavefront
 constexpr int NTHREADS = NWAVES * 64;
 constexpr int WROWS = 32 * QS;         // query rows per wavefront
 constexpr int QTILE = NWAVES * WROWS;  // query rows per workgroup
-constexpr int KTILE = 64;            // keys per LDS tile
+constexpr int KTILE = 64;              // keys per LDS tile
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr int MAGIC_I = 0x4B400000;        // bit pattern of 12582912.0f = 1.5 * 2^23
 constexpr float MAGIC_F = 12582912.0f;
 constexpr float MAX_SLACK = 8.0f;          // log2 of the largest P~ tolerated before the maximum is raised
+
+// Compile-time loop: f(std::integral_constant<int, 0>{}), ..., f(std::integral_constant<int, N-1>{}).
+template <class F, int... I>
+__device__ __forceinline__ void static_for_impl(F& f, std::integer_sequence<int, I...>) { (f(std::integral_constant<int, I>{}), ...); }
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) { static_for_impl(f, std::make_integer_sequence<int, N>{}); }
+#define IDX(x) (std::remove_reference_t<decltype(x)>::value)
 
 // LDS tiles are unpadded; 16-byte chunks are XOR-swizzled inside each row so that the operand
 // reads of 16 consecutive rows touch every bank once.
@@ -111,15 +122,41 @@ __device__ __forceinline__ float as_f32(int v) { return __builtin_bit_cast(float
 __device__ __forceinline__ int as_i32(float v) { return __builtin_bit_cast(int, v); }
 __device__ __forceinline__ int imax3(int a, int b, int c) { return max(max(a, b), c); }
 
-#ifdef SAGE_DBG_TIMING
-__device__ unsigned long long g_timing[16384 * 8];
-#define TSTAMP(k) do { unsigned long long now_ = __builtin_amdgcn_s_memtime(); tacc[k] += now_ - tlast; tlast = now_; } while (0)
-#else
-#define TSTAMP(k) do {} while (0)
-#endif
+// ---- matrix instructions, register files chosen by hand
+// S^T block: scores in VGPRs (the softmax reads them with VALU instructions); the destination and
+// the accumulator input of one instruction must sit in the same register file, so the seed is a
+// VGPR tuple as well.  The Q^ operand is pinned in AGPRs.
+__device__ __forceinline__ void qk_mfma_first(v16i& acc, const v4i& a, const v4i& q, const v16i& seed) {
+    asm volatile("v_mfma_i32_32x32x32_i8 %0, %1, %2, %3" : "=&v"(acc) : "v"(a), "a"(q), "v"(seed));
+}
+__device__ __forceinline__ void qk_mfma_next(v16i& acc, const v4i& a, const v4i& q) {
+    asm volatile("v_mfma_i32_32x32x32_i8 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "a"(q));
+}
+// O^T block acc += V^T operand (VGPRs, from LDS) x P~^T operand (VGPRs).  acc is declared as an
+// input and modified in place (see "Register files" above).
+__device__ __forceinline__ void pv_mfma(const v16f& acc, const v8h& a, const v8h& b) {
+    asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : : "a"(acc), "v"(a), "v"(b));
+}
+// row sums acc += ones x P~^T operand, same convention
+__device__ __forceinline__ void l_mfma(const v16f& acc, const v4i& ones, const v8h& b) {
+    asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : : "a"(acc), "a"(ones), "v"(b));
+}
+// One 16-byte-per-lane load from global memory straight into LDS: lane l lands at LDS byte address
+// lds_addr + 16*l (lds_addr wave-uniform).  Written as assembly because the compiler, which cannot
+// tell which LDS bytes such a load writes, makes every later LDS read wait for it (vmcnt(0)) and
+// so turns the asynchronous load into a synchronous one.  Completion is tracked by hand: the
+// issuing wavefront waits with s_waitcnt vmcnt before the barrier that publishes the tile.
+__device__ __forceinline__ void load_to_lds16(const void* gaddr, unsigned lds_addr) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(gaddr), "s"(lds_addr) : "memory");
+}
+// Tells the compiler that an accumulator changed, 12 wait states after the last matrix instruction
+// that wrote it (all of these statements are volatile, so their order is kept).
+__device__ __forceinline__ void refresh(v16f& acc) { asm volatile("s_nop 11" : "+a"(acc)); }
+// Makes a value opaque and resident in the accumulator file.
+template <class T> __device__ __forceinline__ void pin_a(T& x) { asm volatile("" : "+a"(x)); }
 
 template <int D, bool CAUSAL, bool DUMP>
-__global__ void SAGE_LAUNCH_BOUNDS
+__global__ void __launch_bounds__(NTHREADS)
 sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
                  const int8_t* __restrict__ ki, const float* __restrict__ ksc,
                  const _Float16* __restrict__ vg, _Float16* __restrict__ og,
@@ -132,12 +169,9 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
     constexpr int KS = D / 32;          // INT8 MFMA steps along the head dimension
     constexpr int DT = D / 32;          // 32-wide output tiles along the head dimension
     constexpr int KVEC = KB / 16, VVEC = VB / 16;               // 16-byte vectors per tile
-    constexpr int KL = (KVEC + NTHREADS - 1) / NTHREADS, VL = (VVEC + NTHREADS - 1) / NTHREADS;    // per thread
-    // when a tile has fewer vectors than the workgroup has threads, only the first threads move data
-    constexpr bool K_PART = KVEC % NTHREADS != 0, V_PART = VVEC % NTHREADS != 0;
-    static_assert(!K_PART || KL == 1, "partial staging only for single-vector tiles");
-    static_assert(!V_PART || VL == 1, "partial staging only for single-vector tiles");
-    const bool k_mine = !K_PART || threadIdx.x < KVEC, v_mine = !V_PART || threadIdx.x < VVEC;
+    static_assert(KVEC % 64 == 0 && VVEC % 64 == 0, "whole vectors per wavefront instruction");
+    // load instructions per wavefront and tile (the last may cover only the first wavefronts)
+    constexpr int KL = (KVEC + NTHREADS - 1) / NTHREADS, VL = (VVEC + NTHREADS - 1) / NTHREADS;
     constexpr int KCH = KROW / 16, VCH = VROW / 16;             // chunks per row
     __shared__ __attribute__((aligned(1024))) unsigned char lds[2 * KB + 2 * VB];
 
@@ -153,14 +187,11 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
     const int t = threadIdx.x, lane = t & 63;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);     // wave-uniform: keeps control flow scalar
     const int ql = lane & 31, g = lane >> 5;
-#if SAGE_PRIO
-    if (wave >= NWAVES / 2) __builtin_amdgcn_s_setprio(0); else __builtin_amdgcn_s_setprio(3);
-#endif
     const int qrow0 = qt * QTILE + wave * WROWS;     // first row of the wavefront; sub-tile qs starts 32*qs later
     const size_t slab = (size_t)bh * N;
     const int nbq = (N + (1 << shift_q) - 1) >> shift_q, nbk = (N + (1 << shift_k) - 1) >> shift_k;
 
-    // Q^ operands (B matrix of S^T = K^ Q^^T) stay in registers for the whole kernel.
+    // Q^ operands (B matrix of S^T = K^ Q^^T) stay in accumulator registers for the whole kernel.
     v4i qreg[QS][KS];
     float dq[QS];
 #pragma unroll
@@ -170,6 +201,7 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
         for (int ks = 0; ks < KS; ++ks) {
             qreg[qs][ks] = (v4i){0, 0, 0, 0};
             if (q_row < N) qreg[qs][ks] = *(const v4i*)(qi + (slab + q_row) * D + ks * 32 + g * 16);
+            pin_a(qreg[qs][ks]);
         }
         dq[qs] = 0.0f;
         if (!DUMP) {
@@ -177,6 +209,22 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
             dq[qs] = qsc[(size_t)bh * nbq + (rc >> shift_q)] * LOG2E;
         }
     }
+    v16f acc_o[QS][DT];      // O^T accumulators
+    v16f acc_l[QS];          // row sums l, accumulated on the matrix pipe (every register of a lane holds its query's l)
+#pragma unroll
+    for (int qs = 0; qs < QS; ++qs) {
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc_o[qs][dt][r] = 0.0f;
+            pin_a(acc_o[qs][dt]);
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc_l[qs][r] = 0.0f;
+        pin_a(acc_l[qs]);
+    }
+    v4i ones4 = {0x3C003C00, 0x3C003C00, 0x3C003C00, 0x3C003C00};     // FP16 (1, 1) pairs
+    pin_a(ones4);
     const float* __restrict__ ksc_bh = ksc + (size_t)bh * nbk;
 
     // kv tiles visited by the workgroup (T) and by this wavefront (Tw <= T: tiles above the
@@ -190,10 +238,12 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
         Tw = last < T ? last : T;
     }
 
-    // ---- global -> register -> LDS staging.  Thread t moves the 16-byte vectors t, t+256, ...
-    // of the (linear, unpadded) LDS tile; the global chunk it fetches is the swizzled one.  Rows
-    // past N are clamped to the last row: their scores are masked, so the values never matter.
-    v4i kpre[KL], vpre[VL];
+    // ---- global -> LDS tile loads without staging registers (the load unit writes LDS directly).
+    // Instruction i of wavefront w fills the 16-byte vectors (NTHREADS*i + 64*w) .. +63 of the
+    // (linear, unpadded) LDS tile, one per lane; the global chunk a lane fetches is the swizzled
+    // one.  Rows past N are clamped to the last row: their scores are masked, so the values never
+    // matter.  The loads are asynchronous: a wavefront waits for its own (vmcnt) before the barrier
+    // that publishes the tile.
     int k_goff[KL], v_goff[VL];          // byte offsets inside a full tile (row * pitch + swizzled chunk)
 #pragma unroll
     for (int i = 0; i < KL; ++i) {
@@ -207,35 +257,34 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
     }
     const unsigned char* k_slab = (const unsigned char*)(ki + slab * D);
     const unsigned char* v_slab = (const unsigned char*)(vg + slab * D);
-    auto fetch_k = [&](int j) {
+    const unsigned lds_base = (unsigned)(size_t)LDS_PTR(unsigned char, lds);     // LDS byte address of the tile area
+    auto load_k = [&](int j, int buf) {
         const int kv0 = j * KTILE, lim = N - 1 - kv0;
         const unsigned char* kt = k_slab + (size_t)kv0 * D;
 #pragma unroll
         for (int i = 0; i < KL; ++i) {
-            int row = k_goff[i] / D, rc = row < lim ? row : lim;
-            if (k_mine) kpre[i] = *(const v4i*)(kt + k_goff[i] + (rc - row) * D);
+            if (NTHREADS * (i + 1) > KVEC && NTHREADS * i + wave * 64 >= KVEC) continue;   // piece beyond the tile for this wavefront
+            int delta = 0;
+            if (kv0 + KTILE > N) { int row = k_goff[i] / D, rc = row < lim ? row : lim; delta = (rc - row) * D; }
+            load_to_lds16(kt + k_goff[i] + delta, lds_base + buf * KB + (NTHREADS * i + wave * 64) * 16);
         }
     };
-    auto fetch_v = [&](int j) {
+    auto load_v = [&](int j, int buf) {
         if (DUMP) return;                 // the score dump never touches V
         const int kv0 = j * KTILE, lim = N - 1 - kv0;
         const unsigned char* vt = v_slab + (size_t)kv0 * 2 * D;
 #pragma unroll
         for (int i = 0; i < VL; ++i) {
-            int row = v_goff[i] / (2 * D), rc = row < lim ? row : lim;
-            if (v_mine) vpre[i] = *(const v4i*)(vt + v_goff[i] + (rc - row) * 2 * D);
+            if (NTHREADS * (i + 1) > VVEC && NTHREADS * i + wave * 64 >= VVEC) continue;
+            int delta = 0;
+            if (kv0 + KTILE > N) { int row = v_goff[i] / (2 * D), rc = row < lim ? row : lim; delta = (rc - row) * 2 * D; }
+            load_to_lds16(vt + v_goff[i] + delta, lds_base + 2 * KB + buf * VB + (NTHREADS * i + wave * 64) * 16);
         }
     };
-    auto stage_k = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < KL; ++i)
-            if (k_mine) *(v4i*)(lds + buf * KB + (t + NTHREADS * i) * 16) = kpre[i];
-    };
-    auto stage_v = [&](int buf) {
-        if (DUMP) return;
-#pragma unroll
-        for (int i = 0; i < VL; ++i)
-            if (v_mine) *(v4i*)(lds + 2 * KB + buf * VB + (t + NTHREADS * i) * 16) = vpre[i];
+    // own tile loads landed (vmcnt(0)), then the workgroup barrier
+    auto tiles_ready_barrier = [&]() {
+        __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0); expcnt and lgkmcnt fields at their maximum = no wait
+        __syncthreads();
     };
 
     // ---- per-lane LDS read offsets
@@ -254,78 +303,81 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
         v_off[dt] = v_row * VROW + chunk * 16 + (li & 1) * 8;
     }
 
-    v16f acc_o[QS][DT];
-    v16i acc_s[QS][2];
-    v4i pk[QS][2][2];
-    v16f acc_l[QS];          // row sums l, accumulated on the matrix pipe (every register of a lane holds its query's l)
-    float m_run[QS];
+    v16i acc_s[QS][2];       // S^T of the current tile, two 32-key halves per sub-tile (raw int32 + seed)
+    v4i pk[QS][2][2];        // P~^T as FP16 pairs: [sub-tile][32-key half][16-key group]
+    float m_run[QS], sc[QS], bias[QS], m_cand[QS];
+    int pmax[QS][DT];        // partial integer row maxima of the current tile
 #pragma unroll
     for (int qs = 0; qs < QS; ++qs) {
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc_o[qs][dt][r] = 0.0f;
 #pragma unroll
         for (int a = 0; a < 2; ++a)
 #pragma unroll
             for (int b = 0; b < 2; ++b) pk[qs][a][b] = (v4i){0, 0, 0, 0};
         m_run[qs] = -__builtin_inff();
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc_l[qs][r] = 0.0f;
+        sc[qs] = 0.0f; bias[qs] = 0.0f; m_cand[qs] = 0.0f;
     }
-    v8h ones8;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) ones8[e] = (_Float16)1.0f;
-
     v16i magic;
 #pragma unroll
     for (int r = 0; r < 16; ++r) magic[r] = MAGIC_I;
-    SAGE_PIN_MAGIC(magic);      // keep it resident (accumulator file): re-materializing costs 16 moves per sub-tile
+    asm volatile("" : "+v"(magic));      // keep it resident: re-materializing costs 16 moves per sub-tile
+    float dk_next = DUMP ? 0.0f : ksc_bh[0];
+
+    // 12 wait states between the matrix instructions that wrote the scores and the first VALU or
+    // memory instruction that touches them; the operands tie every later use to the fence.
+    auto score_fence = [&]() {
+        static_assert(QS == 1 || QS == 2, "the fence lists the score registers explicitly");
+        if constexpr (QS == 2) asm volatile("s_nop 11" : "+v"(acc_s[0][0]), "+v"(acc_s[0][1]), "+v"(acc_s[QS - 1][0]), "+v"(acc_s[QS - 1][1]));
+        else asm volatile("s_nop 11" : "+v"(acc_s[0][0]), "+v"(acc_s[0][1]));
+    };
 
     // ---- pieces of per-tile work
     // half of S^T = K^ Q^^T (INT8, int32 accumulate): 32-key sub-tile s of the K^ tile in buffer kbuf
-    auto qk_half = [&](int kbuf, int s) {
+    auto qk_half = [&](int kbuf, auto S) {
+        constexpr int s = IDX(S);
         const unsigned char* kb = lds + kbuf * KB + s * 32 * KROW;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            v4i a = *(const v4i*)(kb + k_off[ks]);
-#pragma unroll
-            for (int qs = 0; qs < QS; ++qs)
-                acc_s[qs][s] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, qreg[qs][ks], ks == 0 ? magic : acc_s[qs][s], 0, 0, 0);
-        }
+        static_for<KS>([&](auto KSI) {
+            constexpr int ks = IDX(KSI);
+            const v4i a = *(const v4i*)(kb + k_off[ks]);
+            static_for<QS>([&](auto QSI) {
+                constexpr int qs = IDX(QSI);
+                if constexpr (ks == 0) qk_mfma_first(acc_s[qs][s], a, qreg[qs][ks], magic);
+                else qk_mfma_next(acc_s[qs][s], a, qreg[qs][ks]);
+            });
+        });
     };
-    // O^T += V^T P~^T for the 16 keys of group (s, u) of the V tile in buffer vbuf
-    auto pv_group = [&](int vbuf, int s, int u) {
+    // O^T += V^T P~^T for the 16 keys of group (s, u) of the V tile in buffer vbuf, and their row sums
+    auto pv_group = [&](int vbuf, auto S, auto U) {
+        constexpr int s = IDX(S), u = IDX(U);
         const unsigned char* vb = lds + 2 * KB + vbuf * VB + (32 * s + 16 * u) * VROW;
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
+        static_for<DT>([&](auto DTI) {
+            constexpr int dt = IDX(DTI);
             v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(v4s, vb + v_off[dt]));
             v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(v4s, vb + v_off[dt] + 8 * VROW));
-            v8h a = __builtin_bit_cast(v8h, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-#pragma unroll
-            for (int qs = 0; qs < QS; ++qs)
-                acc_o[qs][dt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, __builtin_bit_cast(v8h, pk[qs][s][u]), acc_o[qs][dt], 0, 0, 0);
-        }
+            const v8h a = __builtin_bit_cast(v8h, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+            static_for<QS>([&](auto QSI) {
+                constexpr int qs = IDX(QSI);
+                pv_mfma(acc_o[qs][dt], a, __builtin_bit_cast(v8h, pk[qs][s][u]));
+            });
+        });
+        static_for<QS>([&](auto QSI) {
+            constexpr int qs = IDX(QSI);
+            l_mfma(acc_l[qs], ones4, __builtin_bit_cast(v8h, pk[qs][s][u]));
+        });
     };
 
-    // Running-maximum bookkeeping for the tile whose scores sit in acc_s (tile j), done BETWEEN
-    // pipeline steps so that the step itself stays one straight-line block:
-    //   - on diagonal / tail tiles, hidden keys (beyond N, or after the query when causal) get the
-    //     bit pattern of -inf, which the integer maximum ignores and which exponentiates to 0;
-    //   - the running maximum is raised only if some row's tile maximum exceeds it by MAX_SLACK;
-    //     then O, l and the not-yet-accumulated P~ of tile j-1 are rescaled (rare).
-    float sc[QS], bias[QS];
-    float dk_next = DUMP ? 0.0f : ksc_bh[0];
-    auto prepare = [&](int j) {
+    // ---- running-maximum bookkeeping for the tile whose scores sit in acc_s (tile j)
+    // begin_tile: scale of the tile; on diagonal / tail tiles, hidden keys (beyond N, or after the
+    // query when causal) get the bit pattern of -inf, which is below every real score as an
+    // integer and exponentiates to 0.
+    auto begin_tile = [&](int j) {
         const int kv0 = j * KTILE;
+        score_fence();
         const float dk = dk_next;                      // loaded one step ahead
         {
             const int jn = j + 1 < kv_tiles_all ? j + 1 : j;
             dk_next = ksc_bh[(jn * KTILE) >> shift_k];
         }
         const bool need_mask = (kv0 + KTILE > N) || (CAUSAL && kv0 + KTILE - 1 > qrow0);
-        float m_cand[QS];
-        bool want = false;
 #pragma unroll
         for (int qs = 0; qs < QS; ++qs) {
             // a zero scale (all-zero quantization block) would turn -inf * scale into NaN
@@ -341,82 +393,126 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
                         acc_s[qs][s][r] = hide ? (int)0xFF800000 : acc_s[qs][s][r];
                     }
             }
-            int mi = acc_s[qs][0][0];
+        }
+    };
+    // partial_max(qs, p): integer maximum over part p (of DT) of sub-tile qs's 32 scores per lane;
+    // issued between the matrix instructions of the step's first slot.
+    auto partial_max = [&](auto QSI, auto P) {
+        constexpr int qs = IDX(QSI), p = IDX(P);
+        constexpr int CNT = 32 / DT, FIRST = p * CNT;              // flat index = 16*s + r
+        auto val = [&](int f) { return acc_s[qs][f >> 4][f & 15]; };
+        int mi = val(FIRST);
 #pragma unroll
-            for (int r = 1; r < 16; r += 2) mi = imax3(mi, acc_s[qs][0][r], acc_s[qs][0][(r + 1) & 15]);
+        for (int f = FIRST + 1; f + 1 < FIRST + CNT; f += 2) mi = imax3(mi, val(f), val(f + 1));
+        pmax[qs][p] = max(mi, val(FIRST + CNT - 1));
+    };
+    // finish_max: row maximum of the tile; returns whether some row of the wavefront must raise
+    // its running maximum.
+    auto finish_max = [&]() -> bool {
+        bool want = false;
 #pragma unroll
-            for (int r = 0; r < 16; r += 2) mi = imax3(mi, acc_s[qs][1][r], acc_s[qs][1][r + 1]);
+        for (int qs = 0; qs < QS; ++qs) {
+            int mi = pmax[qs][0];
+#pragma unroll
+            for (int p = 1; p < DT; ++p) mi = max(mi, pmax[qs][p]);
             mi = max(mi, swap32i(mi));
             m_cand[qs] = (mi < 0) ? -__builtin_inff() : (as_f32(mi) - MAGIC_F) * sc[qs];
             want = want || (m_cand[qs] > m_run[qs] + MAX_SLACK);
         }
-        if (__builtin_amdgcn_ballot_w64(want) != 0ull) {
+        return __builtin_amdgcn_ballot_w64(want) != 0ull;
+    };
+    // The rare path: new running maximum; O^T, l and the P~ still waiting for its matrix
+    // instructions are rescaled.
+    auto raise_maximum = [&]() {
 #pragma unroll
-            for (int qs = 0; qs < QS; ++qs) {
-                const float m_new = __builtin_fmaxf(m_run[qs], m_cand[qs]);
-                const float alpha = __builtin_amdgcn_exp2f(m_run[qs] - m_new);
-                m_run[qs] = m_new;
+        for (int qs = 0; qs < QS; ++qs) {
+            refresh(acc_l[qs]);
 #pragma unroll
-                for (int r = 0; r < 16; ++r) acc_l[qs][r] *= alpha;
-                typedef _Float16 h2 __attribute__((ext_vector_type(2)));
-                const h2 a2 = {(_Float16)alpha, (_Float16)alpha};
-#pragma unroll
-                for (int s = 0; s < 2; ++s)
-#pragma unroll
-                    for (int u = 0; u < 2; ++u)
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            int w = pk[qs][s][u][e];
-                            pk[qs][s][u][e] = __builtin_bit_cast(int, __builtin_bit_cast(h2, w) * a2);
-                        }
-#pragma unroll
-                for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) acc_o[qs][dt][r] *= alpha;
-            }
+            for (int dt = 0; dt < DT; ++dt) refresh(acc_o[qs][dt]);
         }
+#pragma unroll
+        for (int qs = 0; qs < QS; ++qs) {
+            const float m_new = __builtin_fmaxf(m_run[qs], m_cand[qs]);
+            const float alpha = __builtin_amdgcn_exp2f(m_run[qs] - m_new);
+            m_run[qs] = m_new;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc_l[qs][r] *= alpha;
+            pin_a(acc_l[qs]);
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc_o[qs][dt][r] *= alpha;
+                pin_a(acc_o[qs][dt]);
+            }
+            typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+            const h2 a2 = {(_Float16)alpha, (_Float16)alpha};
+#pragma unroll
+            for (int s = 0; s < 2; ++s)
+#pragma unroll
+                for (int u = 0; u < 2; ++u)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        int w = pk[qs][s][u][e];
+                        pk[qs][s][u][e] = __builtin_bit_cast(int, __builtin_bit_cast(h2, w) * a2);
+                    }
+        }
+    };
+    auto set_bias = [&]() {
 #pragma unroll
         for (int qs = 0; qs < QS; ++qs) bias[qs] = -__builtin_fmaf(MAGIC_F, sc[qs], m_run[qs]);   // exp2 argument = acc*sc + bias
     };
 
-    // One pipeline step, a single straight-line block: softmax of tile j (scores in acc_s, scale
-    // and bias from prepare(j)), P~V of tile j-1, K^Q^^T of tile j+1.  For j = 0 the P~ registers
-    // are zero and the V buffer that is read is zero-filled, so that P~V adds nothing.
+    // ---- one pipeline step: softmax of tile j (scores in acc_s), P~V of tile j-1, K^Q^^T of tile
+    // j+1.  For j = 0 the P~ registers are zero and the V buffer that is read is zero-filled, so
+    // that P~V adds nothing.
     //
     // Flat operand sequence o = 0 .. 4*DT + 2*KS - 1: four P~V groups (DT operands each), then
-    // the two K^Q^^T halves (KS operands each).  Operand o+1 is read from LDS before the matrix
-    // instructions of operand o are issued.
+    // the two K^Q^^T halves (KS operands each).  Operand o+PD is read from LDS before the matrix
+    // instructions of operand o are issued.  The step comes in two parts:
+    //   step_a  the first P~V group, with the row maximum of tile j computed between its matrix
+    //           instructions (nothing of tile j's softmax can start before the maximum is known);
+    //   step_b  everything else, with the softmax chunks between the matrix instructions.
+    // Between the two the (rare) raise of the running maximum takes place.
     constexpr int NOPS = 4 * DT + 2 * KS;
-    constexpr int PD = 2;        // LDS operands are read PD operands ahead of their matrix instructions
+    constexpr int PD = 3;        // LDS operands are read PD operands ahead of their matrix instructions
     v4i opnd[PD + 1];            // operand ring (V^T operands are reinterpreted)
-    auto load_operand = [&](int o, int vbuf, int kbuf) {
-        if (o < 4 * DT) {
-            const int grp_su = o / DT, dt = o % DT;         // group (s,u) = (grp_su / 2, grp_su % 2)
+    auto load_operand = [&](auto O, int vbuf, int kbuf) {
+        constexpr int o = IDX(O);
+        if constexpr (o < 4 * DT) {
+            constexpr int grp_su = o / DT, dt = o % DT;         // group (s,u) = (grp_su / 2, grp_su % 2)
             const unsigned char* vb = lds + 2 * KB + vbuf * VB + 16 * grp_su * VROW + v_off[dt];
             v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(v4s, vb));
             v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(v4s, vb + 8 * VROW));
             opnd[o % (PD + 1)] = __builtin_bit_cast(v4i, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
         } else {
-            const int half = (o - 4 * DT) / KS, ks = (o - 4 * DT) % KS;
+            constexpr int half = (o - 4 * DT) / KS, ks = (o - 4 * DT) % KS;
             opnd[o % (PD + 1)] = *(const v4i*)(lds + kbuf * KB + half * 32 * KROW + k_off[ks]);
         }
     };
-    auto issue_mfma = [&](int o, int qs) {
-        if (o < 4 * DT) {
-            const int grp_su = o / DT, dt = o % DT;
-            acc_o[qs][dt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, opnd[o % (PD + 1)]),
-                                                                    __builtin_bit_cast(v8h, pk[qs][grp_su >> 1][grp_su & 1]),
-                                                                    acc_o[qs][dt], 0, 0, 0);
+    auto issue_mfma = [&](auto O, auto QSI) {
+        constexpr int o = IDX(O), qs = IDX(QSI);
+        if constexpr (o < 4 * DT) {
+            constexpr int grp_su = o / DT, dt = o % DT;
+            pv_mfma(acc_o[qs][dt], __builtin_bit_cast(v8h, opnd[o % (PD + 1)]), __builtin_bit_cast(v8h, pk[qs][grp_su >> 1][grp_su & 1]));
         } else {
-            const int half = (o - 4 * DT) / KS, ks = (o - 4 * DT) % KS;
-            acc_s[qs][half] = __builtin_amdgcn_mfma_i32_32x32x32_i8(opnd[o % (PD + 1)], qreg[qs][ks],
-                                                                    ks == 0 ? magic : acc_s[qs][half], 0, 0, 0);
+            constexpr int half = (o - 4 * DT) / KS, ks = (o - 4 * DT) % KS;
+            if constexpr (ks == 0) qk_mfma_first(acc_s[qs][half], opnd[o % (PD + 1)], qreg[qs][ks], magic);
+            else qk_mfma_next(acc_s[qs][half], opnd[o % (PD + 1)], qreg[qs][ks]);
         }
+    };
+    auto row_sums = [&](auto G) {
+        // row sums of a 16-key group just consumed: l += 1^T P~^T on the matrix pipe
+        constexpr int grp_su = IDX(G);
+        static_for<QS>([&](auto QSI) {
+            constexpr int qs = IDX(QSI);
+            l_mfma(acc_l[qs], ones4, __builtin_bit_cast(v8h, pk[qs][grp_su >> 1][grp_su & 1]));
+        });
+        __builtin_amdgcn_sched_barrier(0);
     };
     // The softmax of a tile is cut into chunks of two scores of one query sub-tile; chunk ch
     // belongs to 16-key group ch / (4*QS).  A chunk passes three stages in three consecutive
-    // pipeline ticks (scale+bias FMA, exp2, pack + row sum) so that dependent instructions of
-    // one chunk are never adjacent in the single in-order instruction stream.
+    // pipeline ticks (scale+bias FMA, exp2, pack) so that dependent instructions of one chunk are
+    // never adjacent in the single in-order instruction stream.
     constexpr int CHUNKS = 4 * QS;                     // chunks per 16-key group
     constexpr int NCH = 4 * CHUNKS;                    // chunks per tile
     float xs[3][2];
@@ -438,84 +534,55 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
         const f2 pp = {xs[ch % 3][0], xs[ch % 3][1]};
         pk[qs][grp_su >> 1][grp_su & 1][pair] = __builtin_bit_cast(int, __builtin_convertvector(pp, h2));
     };
-    auto step = [&](int j) {
+    constexpr int MF_PER_SLOT = DT * QS;               // matrix instructions per slot (DT == KS)
+    static_assert(CHUNKS % MF_PER_SLOT == 0, "whole chunks per matrix instruction");
+    constexpr int CPM = CHUNKS / MF_PER_SLOT;          // pipeline ticks per matrix instruction
+    // Chunk c enters the pipeline at tick c, right after matrix instruction MF_PER_SLOT + c/CPM:
+    // its P~ group is packed after the group's P~V of tile j-1 has been issued, and each half of
+    // S_j is consumed before the K^Q^^T of that half is issued.
+    static_assert(MF_PER_SLOT + (NCH / 2 - 1) / CPM < 4 * MF_PER_SLOT, "first half of S consumed before it is overwritten");
+    static_assert(MF_PER_SLOT + (NCH - 1) / CPM < 4 * MF_PER_SLOT + KS * QS, "second half of S consumed before it is overwritten");
+    static_assert(MF_PER_SLOT + (NCH + 1) / CPM < NOPS * QS, "last chunk packed inside the step");
+    auto step_a = [&](int j) {
         const int vbuf = (j - 1) & 1, kbuf = (j + 1) & 1;
-        constexpr int MF_PER_SLOT = DT * QS;               // matrix instructions per slot (DT == KS)
-        static_assert(CHUNKS % MF_PER_SLOT == 0, "whole chunks per matrix instruction");
-        constexpr int CPM = CHUNKS / MF_PER_SLOT;          // pipeline ticks per matrix instruction
-        constexpr int LEAD = MF_PER_SLOT - (2 + CPM - 1) / CPM;   // first tick: so that chunk 0 is packed right after slot A
-#if SAGE_PHASED
-        // matrix phase / VALU phase / matrix phase: overlap is left to the OTHER wavefront of the SIMD
-        load_operand(0, vbuf, kbuf);
-#pragma unroll
-        for (int o = 0; o < 4 * DT; ++o) {
-            if (o + 1 < 4 * DT) load_operand(o + 1, vbuf, kbuf);
-#pragma unroll
-            for (int qs = 0; qs < QS; ++qs) issue_mfma(o, qs);
-        }
-#pragma unroll
-        for (int grp_su = 0; grp_su < 4; ++grp_su)
-#pragma unroll
-            for (int qs = 0; qs < QS; ++qs)
-                acc_l[qs] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ones8, __builtin_bit_cast(v8h, pk[qs][grp_su >> 1][grp_su & 1]), acc_l[qs], 0, 0, 0);
+        static_for<PD>([&](auto O) { load_operand(O, vbuf, kbuf); });
         __builtin_amdgcn_sched_barrier(0);
-        load_operand(4 * DT, vbuf, kbuf);
-#pragma unroll
-        for (int n = 0; n < NCH + 2; ++n) {
-            if (n - 2 >= 0 && n - 2 < NCH) chunk_pack(n - 2);
-            if (n - 1 >= 0 && n - 1 < NCH) chunk_exp(n - 1);
-            if (n >= 0 && n < NCH) chunk_fma(n);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int o = 4 * DT; o < NOPS; ++o) {
-            if (o + 1 < NOPS) load_operand(o + 1, vbuf, kbuf);
-#pragma unroll
-            for (int qs = 0; qs < QS; ++qs) issue_mfma(o, qs);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-#else
-#pragma unroll
-        for (int o = 0; o < PD; ++o) load_operand(o, vbuf, kbuf);
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int o = 0; o < NOPS; ++o) {
-#ifndef SAGE_ABL_NOLDS
-            if (o + PD < NOPS) load_operand(o + PD, vbuf, kbuf);
-#endif
-#pragma unroll
-            for (int qs = 0; qs < QS; ++qs) {
-#ifndef SAGE_ABL_NOMFMA
-                issue_mfma(o, qs);
-#endif
-                const int mm = o * QS + qs;                // index of the matrix instruction in the step
+        static_for<DT>([&](auto O) {
+            constexpr int o = IDX(O);
+            load_operand(std::integral_constant<int, o + PD>{}, vbuf, kbuf);
+            static_for<QS>([&](auto QSI) {
+                issue_mfma(O, QSI);
+                partial_max(QSI, O);
+                __builtin_amdgcn_sched_barrier(0);
+            });
+        });
+        row_sums(std::integral_constant<int, 0>{});
+    };
+    auto step_b = [&](int j) {
+        const int vbuf = (j - 1) & 1, kbuf = (j + 1) & 1;
+        static_for<NOPS - DT>([&](auto OO) {
+            constexpr int o = IDX(OO) + DT;
+            if constexpr (o + PD < NOPS) load_operand(std::integral_constant<int, o + PD>{}, vbuf, kbuf);
+            static_for<QS>([&](auto QSI) {
+                constexpr int qs = IDX(QSI);
+                issue_mfma(std::integral_constant<int, o>{}, QSI);
+                constexpr int mm = o * QS + qs;            // index of the matrix instruction in the step
 #pragma unroll
                 for (int c = 0; c < CPM; ++c) {
-                    const int n = (mm - LEAD) * CPM + c;   // pipeline tick
-#ifndef SAGE_ABL_NOVALU
+                    const int n = (mm - MF_PER_SLOT) * CPM + c;   // pipeline tick
                     if (n - 2 >= 0 && n - 2 < NCH) chunk_pack(n - 2);
                     if (n - 1 >= 0 && n - 1 < NCH) chunk_exp(n - 1);
                     if (n >= 0 && n < NCH) chunk_fma(n);
-#endif
                 }
                 __builtin_amdgcn_sched_barrier(0);
-            }
-            if (o < 4 * DT && o % DT == DT - 1) {
-                // row sums of the 16-key group just consumed: l += 1^T P~^T on the matrix pipe
-#pragma unroll
-                for (int qs = 0; qs < QS; ++qs) {
-                    const int grp_su = o / DT;
-                    acc_l[qs] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ones8, __builtin_bit_cast(v8h, pk[qs][grp_su >> 1][grp_su & 1]),
-                                                                        acc_l[qs], 0, 0, 0);
-                }
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        }
-#endif
+            });
+            if constexpr (o < 4 * DT && o % DT == DT - 1) row_sums(std::integral_constant<int, o / DT>{});
+        });
     };
 
     auto dump_tile = [&](int j) {
         const int kv0 = j * KTILE;
+        score_fence();
 #pragma unroll
         for (int qs = 0; qs < QS; ++qs) {
             const int q_row = qrow0 + 32 * qs + ql;
@@ -529,82 +596,62 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
         }
     };
 
-    // ---- prologue: K^(0), K^(1) into LDS; V(0), K^(2) into the staging registers; S_0
+    // ---- prologue: K^(0), K^(1) into LDS, the V buffer that step 0 reads zero-filled; S_0
     if (!DUMP) {
 #pragma unroll
         for (int i = 0; i < VL; ++i)
-            if (v_mine) *(v4i*)(lds + 2 * KB + VB + (t + NTHREADS * i) * 16) = (v4i){0, 0, 0, 0};
+            if (NTHREADS * i + wave * 64 < VVEC) *(v4i*)(lds + 2 * KB + VB + (t + NTHREADS * i) * 16) = (v4i){0, 0, 0, 0};
     }
-    fetch_k(0); stage_k(0);
-    if (T > 1) { fetch_k(1); stage_k(1); }
-    fetch_v(0);
-    if (T > 2) fetch_k(2);
-    __syncthreads();
-    qk_half(0, 0);
-    qk_half(0, 1);
+    load_k(0, 0);
+    if (T > 1) load_k(1, 1);
+    tiles_ready_barrier();
+    qk_half(0, std::integral_constant<int, 0>{});
+    qk_half(0, std::integral_constant<int, 1>{});
 
-    // ---- main loop.  At the top of iteration j the buffers of V(j-2) and K^(j) are free (their
-    // last readers ran in iteration j-1): V(j) and K^(j+2) are written there from the staging
-    // registers and the next pair is fetched.  Iteration j reads V(j-1) and K^(j+1).
-    // Every wavefront passes T+1 barriers; the loops below are kept free of per-iteration branches
-    // around the accumulators (straight-line bodies keep them in place in the register file).
+    // ---- main loop.  Time slot j lies between barriers j and j+1.  At barrier j the tiles
+    // requested in slot j-1 have landed and the buffers of V(j-2) and K^(j) are free (their last
+    // readers ran in slot j-1): V(j) and K^(j+2) are requested into them and have the whole slot
+    // to arrive.  Slot j reads V(j-1) and K^(j+1).  Every wavefront passes T+1 barriers after the
+    // prologue's.
     auto turn = [&](int j) {
-#ifndef SAGE_ABL_NOBARRIER
-        __syncthreads();
-#endif
-#ifndef SAGE_ABL_NOSTAGE
-        if (j < T) stage_v(j & 1);
-        if (j + 2 < T) stage_k(j & 1);
-        if (j + 1 < T) fetch_v(j + 1);
-        if (j + 3 < T) fetch_k(j + 3);
-#endif
+        tiles_ready_barrier();
+        if (j < T) load_v(j, j & 1);
+        if (j + 2 < T) load_k(j + 2, j & 1);
     };
     int j = 0;
     if (DUMP) {
         for (; j < T; ++j) {
             turn(j);
             dump_tile(j);
-            qk_half((j + 1) & 1, 0);
-            qk_half((j + 1) & 1, 1);
+            qk_half((j + 1) & 1, std::integral_constant<int, 0>{});
+            qk_half((j + 1) & 1, std::integral_constant<int, 1>{});
         }
         return;
     }
-#ifdef SAGE_DBG_TIMING
-    unsigned long long tacc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    unsigned long long tlast = __builtin_amdgcn_s_memtime();
-    const unsigned long long tstart = tlast;
-#endif
+    // The inner loop holds nothing but the steady state: a tile whose maximum forces a rescale
+    // leaves it, is finished on the slow path, and the inner loop is entered again.  (The empty
+    // assembly statements carry a value around the loop that the compiler cannot see through; they
+    // keep it from restructuring the loop nest, which made it spill registers.)
+    unsigned opaque = 0;
     for (; j < Tw; ++j) {
-        TSTAMP(0);
-#ifdef SAGE_ABL_CHEAPPREP
-#pragma unroll
-        for (int qs = 0; qs < QS; ++qs) { sc[qs] = dq[qs] * 1e-5f; m_run[qs] = 20.0f; bias[qs] = -__builtin_fmaf(MAGIC_F, sc[qs], m_run[qs]); }
-#else
-        prepare(j);
-#endif
-        TSTAMP(1);
+        asm volatile("" : "+s"(opaque));
         turn(j);
-        TSTAMP(2);
-        step(j);
-        TSTAMP(3);
+        begin_tile(j);
+        asm volatile("" : "+s"(opaque));
+        step_a(j);
+        if (finish_max()) raise_maximum();
+        set_bias();
+        asm volatile("" : "+s"(opaque));
+        step_b(j);
+        asm volatile("" : "+s"(opaque));
     }
-#ifdef SAGE_DBG_TIMING
-    if (lane == 0 && gidx < 16384 / 8) {
-        unsigned long long* d = g_timing + (gidx * 4 + wave) * 8;
-        for (int k = 0; k < 5; ++k) d[k] = tacc[k];
-        d[5] = __builtin_amdgcn_s_memtime() - tstart; d[6] = Tw; d[7] = tstart;
-    }
-#endif
     // the P~V of the wavefront's last tile ...
     turn(j);
     {
         const int vbuf = (j - 1) & 1;
-        pv_group(vbuf, 0, 0); pv_group(vbuf, 0, 1); pv_group(vbuf, 1, 0); pv_group(vbuf, 1, 1);
-#pragma unroll
-        for (int grp_su = 0; grp_su < 4; ++grp_su)
-#pragma unroll
-            for (int qs = 0; qs < QS; ++qs)
-                acc_l[qs] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ones8, __builtin_bit_cast(v8h, pk[qs][grp_su >> 1][grp_su & 1]), acc_l[qs], 0, 0, 0);
+        static_for<4>([&](auto G) {
+            pv_group(vbuf, std::integral_constant<int, (IDX(G) >> 1)>{}, std::integral_constant<int, (IDX(G) & 1)>{});
+        });
     }
     // ... and the wavefront keeps feeding the workgroup's tile pipeline until all are done.
     for (++j; j <= T; ++j) turn(j);
@@ -613,6 +660,9 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
 #pragma unroll
     for (int qs = 0; qs < QS; ++qs) {
         const int q_row = qrow0 + 32 * qs + ql;
+        refresh(acc_l[qs]);
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) refresh(acc_o[qs][dt]);
         const float inv = 1.0f / acc_l[qs][0];
         if (q_row < N) {
             _Float16* orow = og + (slab + q_row) * D;
@@ -655,11 +705,5 @@ hipError_t launch_attn(const int8_t* qq, const float* qscale, const int8_t* kq, 
     if (D == 64) return launch_d<64>(qq, qscale, kq, kscale, v, o, sdump, BH, N, causal, block_q, block_k, st);
     return launch_d<128>(qq, qscale, kq, kscale, v, o, sdump, BH, N, causal, block_q, block_k, st);
 }
-
-#ifdef SAGE_DBG_TIMING
-extern "C" int sage_dbg_read_timing(void* host, size_t bytes) {
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_timing), bytes);
-}
-#endif
 
 }  // namespace sage
