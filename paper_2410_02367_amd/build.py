@@ -42,40 +42,34 @@ def build(verbose: bool = False, extra=()) -> str:
     return LIB
 
 
-def verify_attention_isa(extra=()) -> None:
-    """Checks the generated code of the attention kernels for what their hand-placed register use
-    relies on (see "Register files" at the top of sage_attn.hip).  The matrix instructions update
-    accumulator registers that they name as inputs, so the compiler must keep every accumulator in
-    one place between them:
+def check_attention_asm(text: str) -> list:
+    """Checks the assembly text of the attention kernels for what their hand-placed register use
+    relies on (see "Register files" at the top of sage_attn.hip) and returns the list of problems
+    found.  The matrix instructions update accumulator registers that they name as inputs, so the
+    compiler must keep every accumulator in one place between them:
       - once the first matrix instruction has been issued it never copies an accumulator register
         to another accumulator register (before that, the zero initialisation may),
       - it reads accumulator registers into VGPRs only where the source refreshes them first (the
         rare rescale and the epilogue), i.e. never inside a block that issues matrix instructions,
       - nothing spills to scratch memory,
       - and it never touches m0, which the hand-written global->LDS loads set.
-    Raises RuntimeError if any of this does not hold."""
+    Instructions between ";;#ASMSTART" and ";;#ASMEND" are the source's own assembly."""
     import re
-    import tempfile
-    flags = [f for f in HIPCC_FLAGS if f not in ("-shared", "-fPIC")]
-    with tempfile.TemporaryDirectory() as tmp:
-        out = os.path.join(tmp, "sage_attn.s")
-        cmd = [hipcc(), *flags, *extra, "-S", "--cuda-device-only", "-o", out, os.path.join(CSRC, "sage_attn.hip")]
-        res = subprocess.run(cmd, capture_output=True, text=True)
-        if res.returncode != 0:
-            raise RuntimeError("hipcc -S failed:\n" + res.stderr)
-        text = open(out).read()
     kernels = re.findall(r"^(_ZN4sage16sage_attn_kernel\w+):.*?^\.Lfunc_end\d+:", text, re.S | re.M)
     bodies = re.findall(r"^_ZN4sage16sage_attn_kernel\w+:.*?^\.Lfunc_end\d+:", text, re.S | re.M)
-    if len(bodies) != 6:
-        raise RuntimeError(f"expected 6 attention kernels in the assembly, found {len(bodies)}")
     problems = []
+    if len(bodies) != 6:
+        problems.append(f"expected 6 attention kernels in the assembly, found {len(bodies)}")
     for name, body in zip(kernels, bodies):
-        block_has_mfma, block_reads = False, []
+        state = {"mfma": False, "reads": []}
         in_asm = False
         seen_mfma = False
+
         def close_block():
-            if block_has_mfma and block_reads:
-                problems.append(f"{name}: accumulator read next to matrix instructions: {block_reads[0]}")
+            if state["mfma"] and state["reads"]:
+                problems.append(f"{name}: accumulator read next to matrix instructions: {state['reads'][0]}")
+            state["mfma"], state["reads"] = False, []
+
         for line in body.split("\n"):
             code = line.split(";")[0].strip()
             if "#ASMSTART" in line:
@@ -86,24 +80,37 @@ def verify_attention_isa(extra=()) -> None:
                 continue
             if re.match(r"^\.LBB\d+_\d+:", line) or code.startswith("s_cbranch") or code.startswith("s_branch"):
                 close_block()
-                block_has_mfma, block_reads = False, []
                 continue
             if not code or code.startswith("."):
                 continue
             if in_asm:
                 if code.startswith("v_mfma"):
-                    block_has_mfma = True
+                    state["mfma"] = True
                     seen_mfma = True
                 continue
             if code.startswith("v_accvgpr_mov") and seen_mfma:
                 problems.append(f"{name}: accumulator-to-accumulator copy: {code}")
             if code.startswith("v_accvgpr_read"):
-                block_reads.append(code)
+                state["reads"].append(code)
             if code.startswith("scratch_"):
                 problems.append(f"{name}: scratch access: {code}")
             if re.search(r"\bm0\b", code):
                 problems.append(f"{name}: compiler-generated use of m0: {code}")
         close_block()
+    return problems
+
+
+def verify_attention_isa(extra=()) -> None:
+    """Compiles sage_attn.hip to assembly and raises RuntimeError if check_attention_asm() objects."""
+    import tempfile
+    flags = [f for f in HIPCC_FLAGS if f not in ("-shared", "-fPIC")]
+    with tempfile.TemporaryDirectory() as tmp:
+        out = os.path.join(tmp, "sage_attn.s")
+        cmd = [hipcc(), *flags, *extra, "-S", "--cuda-device-only", "-o", out, os.path.join(CSRC, "sage_attn.hip")]
+        res = subprocess.run(cmd, capture_output=True, text=True)
+        if res.returncode != 0:
+            raise RuntimeError("hipcc -S failed:\n" + res.stderr)
+        problems = check_attention_asm(open(out).read())
     if problems:
         raise RuntimeError("attention kernel ISA check failed:\n  " + "\n  ".join(problems[:20]))
 

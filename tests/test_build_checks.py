@@ -1,0 +1,63 @@
+"""The build inspects the assembly of the attention kernels (their matrix instructions are inline
+assembly that updates accumulator registers behind the compiler's back).  These tests plant each
+kind of violation in a small fake assembly text and make sure the checker objects; no GPU needed."""
+from paper_2410_02367_amd.build import check_attention_asm
+
+KERNELS = ["_ZN4sage16sage_attn_kernelILi%dELb%dELb%dEEEvPKa" % (d, c, dump)
+           for d in (64, 128) for c, dump in ((0, 1), (1, 0), (0, 0))]
+
+
+def fake(body_of_first: str) -> str:
+    parts = []
+    for i, k in enumerate(KERNELS):
+        body = body_of_first if i == 0 else "\ts_endpgm\n"
+        parts.append(f"{k}:\n{body}.Lfunc_end{i}:\n")
+    return "\n".join(parts)
+
+
+CLEAN = """\tv_accvgpr_mov_b32 a16, a0
+\ts_cbranch_scc1 .LBB0_2
+.LBB0_1:
+\t;;#ASMSTART
+\tv_mfma_f32_32x32x16_f16 a[0:15], v[0:3], v[4:7], a[0:15]
+\t;;#ASMEND
+\tv_fma_f32 v1, v2, v3, v4
+\ts_cbranch_scc1 .LBB0_1
+.LBB0_2:
+\t;;#ASMSTART
+\ts_nop 11
+\t;;#ASMEND
+\tv_accvgpr_read_b32 v9, a3
+\ts_endpgm
+"""
+
+
+def test_clean_text_passes():
+    assert check_attention_asm(fake(CLEAN)) == []
+
+
+def test_missing_kernel_is_reported():
+    text = fake(CLEAN).split(KERNELS[-1])[0]
+    assert any("expected 6" in p for p in check_attention_asm(text))
+
+
+def test_accumulator_copy_after_first_matrix_instruction_is_reported():
+    bad = CLEAN.replace("\tv_fma_f32 v1, v2, v3, v4\n", "\tv_fma_f32 v1, v2, v3, v4\n\tv_accvgpr_mov_b32 a20, a4\n")
+    assert any("accumulator-to-accumulator copy" in p for p in check_attention_asm(fake(bad)))
+
+
+def test_accumulator_read_beside_matrix_instructions_is_reported():
+    bad = CLEAN.replace("\tv_fma_f32 v1, v2, v3, v4\n", "\tv_accvgpr_read_b32 v1, a4\n")
+    assert any("accumulator read next to matrix instructions" in p for p in check_attention_asm(fake(bad)))
+
+
+def test_scratch_and_m0_are_reported():
+    bad = CLEAN.replace("\tv_fma_f32 v1, v2, v3, v4\n", "\tscratch_store_dword off, v1, off\n\ts_mov_b32 m0, s4\n")
+    problems = check_attention_asm(fake(bad))
+    assert any("scratch access" in p for p in problems)
+    assert any("use of m0" in p for p in problems)
+
+
+def test_m0_inside_the_sources_own_assembly_is_allowed():
+    ok = CLEAN.replace("\ts_nop 11\n", "\ts_mov_b32 m0, s4\n\ts_nop 0\n\tglobal_load_lds_dwordx4 v[0:1], off\n")
+    assert check_attention_asm(fake(ok)) == []

@@ -23,6 +23,10 @@ SMALL = [
     si.custom("blocks_32_64", 1, 1, 200, 128, False, 32, 64, seed=si.BASE_SEED + 15),
     si.custom("one_token", 1, 1, 1, 64, True, 128, 64, seed=si.BASE_SEED + 16),
     si.custom("short", 2, 1, 31, 128, False, 128, 64, seed=si.BASE_SEED + 17),
+    si.custom("blocks_64_128_d128", 1, 2, 700, 128, True, 64, 128, seed=si.BASE_SEED + 18),
+    si.custom("whole_tiles", 2, 2, 512, 128, False, 128, 64, seed=si.BASE_SEED + 19),
+    si.custom("one_short_of_a_tile", 1, 2, 255, 64, True, 128, 64, seed=si.BASE_SEED + 21),
+    si.custom("one_past_a_tile", 1, 2, 257, 128, True, 128, 64, seed=si.BASE_SEED + 22),
 ]
 
 
@@ -61,6 +65,29 @@ def test_causal_first_row_is_v0_bit_exact_and_constant_k_gives_prefix_means():
     assert np.abs(o[0, 0].astype(np.float64) - prefix).max() <= ABS_TOL
     o_nc = sage.sage_attn_fwd(q_i8, q_scale, k_i8, k_scale, to_dev(v), False, 0.125, 128, 64).cpu().numpy()
     assert np.abs(o_nc[0, 0].astype(np.float64) - v[0, 0].astype(np.float64).mean(0)[None]).max() <= ABS_TOL
+
+
+@pytest.mark.parametrize("D,causal", [(128, False), (128, True), (64, True)])
+def test_scores_that_keep_rising_force_a_rescale_at_every_tile(D, causal):
+    """Scores grow linearly with the key index (about 13 nats per 64-key tile), so the running
+    maximum has to be raised -- and O, l rescaled -- at every tile a row visits."""
+    print(f"[case] rising scores D{D} causal={causal}", flush=True)
+    N = 1100
+    g = np.random.default_rng(7 + D)
+    u = g.standard_normal(D); u /= np.linalg.norm(u)
+    t = (np.arange(N) - N / 2)[:, None]
+    k = (t * 0.05 * u[None, :] + 0.01 * g.standard_normal((N, D))).astype(np.float16)[None, None]
+    q = (4.0 * np.sqrt(D) * u[None, :] + 0.1 * g.standard_normal((N, D))).astype(np.float16)[None, None]
+    v = g.standard_normal((1, 1, N, D)).astype(np.float16)
+    sm = float(np.float32(1.0) / np.sqrt(np.float32(D)))
+    (q_i8, q_scale, k_i8, k_scale, k_mean), (qq, qs, kq, ks, km) = assert_prepass_bit_exact(q, k, sm, 128, 64)
+    o_gpu = sage.sage_attn_fwd(q_i8, q_scale, k_i8, k_scale, to_dev(v), causal, sm, 128, 64)
+    torch.cuda.synchronize()
+    o_ref = oracle.attn_l2(qq, qs, kq, ks, v, causal, 128, 64)
+    assert_output_close(o_gpu.cpu().numpy(), o_ref, f"rising_d{D}")
+    # the construction does what it says: the last tile's scores exceed the first tile's by far
+    s = oracle.qk_i32(qq[0, 0], kq[0, 0])[N - 1].astype(np.float64) * qs[0, 0, -1] * np.repeat(ks[0, 0], 64)[:N]
+    assert s[-64:].max() - s[:64].max() > 100.0
 
 
 def test_results_are_deterministic_run_to_run():
