@@ -58,8 +58,8 @@ def check_attention_asm(text: str) -> list:
     kernels = re.findall(r"^(_ZN4sage16sage_attn_kernel\w+):.*?^\.Lfunc_end\d+:", text, re.S | re.M)
     bodies = re.findall(r"^_ZN4sage16sage_attn_kernel\w+:.*?^\.Lfunc_end\d+:", text, re.S | re.M)
     problems = []
-    if len(bodies) != 6:
-        problems.append(f"expected 6 attention kernels in the assembly, found {len(bodies)}")
+    if len(bodies) != 12:
+        problems.append(f"expected 12 attention kernels in the assembly, found {len(bodies)}")
     for name, body in zip(kernels, bodies):
         state = {"mfma": False, "reads": []}
         in_asm = False

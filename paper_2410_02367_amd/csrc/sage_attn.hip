@@ -2,9 +2,9 @@
 //
 // Work decomposition
 //   One workgroup = 8 wavefronts (two per SIMD, 256 registers each) = 256 query rows, 32 per
-//   wavefront (a build option gives 4 wavefronts of 64 rows instead, each LDS operand then feeding
-//   two matrix instructions).  Key/value tiles of 64 tokens are double-buffered in LDS and shared
-//   by all wavefronts; they are brought in by asynchronous global->LDS loads that bypass the
+//   wavefront; for D = 64 and for small problems 4 wavefronts = 128 rows, two workgroups per CU.
+//   Key/value tiles of 64 tokens are double-buffered in LDS and shared by all wavefronts of the
+//   workgroup; they are brought in by asynchronous global->LDS loads that bypass the
 //   register file.
 //   Scores are computed TRANSPOSED, S^T = K^ Q^^T, with the 32x32x32 INT8 matrix instruction: each
 //   lane then owns one query column and 16 keys per 32-key sub-tile, so
@@ -80,20 +80,17 @@ typedef short v4s __attribute__((ext_vector_type(4)));
 
 #define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
 
-// Build-time shape of a workgroup.  The default (8 wavefronts of 32 rows: two wavefronts per SIMD,
-// 256 registers each) measured slightly faster than 4 wavefronts of 64 rows (one per SIMD, every
-// LDS operand shared by two matrix instructions); both pass the same tests.
-#ifndef SAGE_NWAVES
-#define SAGE_NWAVES 8
-#endif
+// Shape of a workgroup: NW wavefronts (a template parameter of the kernel, 8 or 4) of WROWS rows.
+//   8 wavefronts, one workgroup per CU  -- two wavefronts per SIMD share one set of LDS tiles;
+//   4 wavefronts, two workgroups per CU -- chosen by the launcher for D = 64 (4 % faster there)
+//                                          and whenever the larger tile would leave CUs without work.
+// QS = 2 (64 rows per wavefront, every LDS operand feeding two matrix instructions) is a build
+// option for one wavefront per SIMD; it measured 2-3 % slower than the default.
 #ifndef SAGE_QS
 #define SAGE_QS 1
 #endif
-constexpr int NWAVES = SAGE_NWAVES;    // wavefronts per workgroup
 constexpr int QS = SAGE_QS;            // 32-row query sub-tiles per wavefront
-constexpr int NTHREADS = NWAVES * 64;
 constexpr int WROWS = 32 * QS;         // query rows per wavefront
-constexpr int QTILE = NWAVES * WROWS;  // query rows per workgroup
 constexpr int KTILE = 64;              // keys per LDS tile
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr int MAGIC_I = 0x4B400000;        // bit pattern of 12582912.0f = 1.5 * 2^23
@@ -155,13 +152,15 @@ __device__ __forceinline__ void refresh(v16f& acc) { asm volatile("s_nop 11" : "
 // Makes a value opaque and resident in the accumulator file.
 template <class T> __device__ __forceinline__ void pin_a(T& x) { asm volatile("" : "+a"(x)); }
 
-template <int D, bool CAUSAL, bool DUMP>
-__global__ void __launch_bounds__(NTHREADS)
+template <int D, int NW, bool CAUSAL, bool DUMP>
+__global__ void __launch_bounds__(NW * 64, NW == 4 && SAGE_QS == 1 ? 2 : 1)
 sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
                  const int8_t* __restrict__ ki, const float* __restrict__ ksc,
                  const _Float16* __restrict__ vg, _Float16* __restrict__ og,
                  int32_t* __restrict__ sdump,
                  int N, int shift_q, int shift_k, int tiles_q, int per_xcd, long total_tiles) {
+    constexpr int NWAVES = NW, NTHREADS = NW * 64;
+    constexpr int QTILE = NW * WROWS;   // query rows per workgroup
     constexpr int KROW = D;             // bytes per K^ row in LDS
     constexpr int VROW = 2 * D;         // bytes per V row in LDS
     constexpr int KB = KTILE * KROW;    // bytes per K^ tile
@@ -679,10 +678,11 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
     }
 }
 
-template <int D>
-static hipError_t launch_d(const int8_t* qq, const float* qscale, const int8_t* kq, const float* kscale,
-                           const void* v, void* o, int32_t* sdump, int BH, int N, int causal,
-                           int block_q, int block_k, hipStream_t st) {
+template <int D, int NW>
+static hipError_t launch_dn(const int8_t* qq, const float* qscale, const int8_t* kq, const float* kscale,
+                            const void* v, void* o, int32_t* sdump, int BH, int N, int causal,
+                            int block_q, int block_k, hipStream_t st) {
+    constexpr int QTILE = NW * WROWS, NTHREADS = NW * 64;
     const int tiles_q = (N + QTILE - 1) / QTILE;
     const long total = (long)BH * tiles_q;
     const int per_xcd = (int)((total + 7) / 8);
@@ -691,12 +691,24 @@ static hipError_t launch_d(const int8_t* qq, const float* qscale, const int8_t* 
     const _Float16* vp = (const _Float16*)v;
     _Float16* op = (_Float16*)o;
     if (sdump)
-        sage_attn_kernel<D, false, true><<<grid, NTHREADS, 0, st>>>(qq, qscale, kq, kscale, vp, op, sdump, N, shift_q, shift_k, tiles_q, per_xcd, total);
+        sage_attn_kernel<D, NW, false, true><<<grid, NTHREADS, 0, st>>>(qq, qscale, kq, kscale, vp, op, sdump, N, shift_q, shift_k, tiles_q, per_xcd, total);
     else if (causal)
-        sage_attn_kernel<D, true, false><<<grid, NTHREADS, 0, st>>>(qq, qscale, kq, kscale, vp, op, sdump, N, shift_q, shift_k, tiles_q, per_xcd, total);
+        sage_attn_kernel<D, NW, true, false><<<grid, NTHREADS, 0, st>>>(qq, qscale, kq, kscale, vp, op, sdump, N, shift_q, shift_k, tiles_q, per_xcd, total);
     else
-        sage_attn_kernel<D, false, false><<<grid, NTHREADS, 0, st>>>(qq, qscale, kq, kscale, vp, op, sdump, N, shift_q, shift_k, tiles_q, per_xcd, total);
+        sage_attn_kernel<D, NW, false, false><<<grid, NTHREADS, 0, st>>>(qq, qscale, kq, kscale, vp, op, sdump, N, shift_q, shift_k, tiles_q, per_xcd, total);
     return hipGetLastError();
+}
+
+template <int D>
+static hipError_t launch_d(const int8_t* qq, const float* qscale, const int8_t* kq, const float* kscale,
+                           const void* v, void* o, int32_t* sdump, int BH, int N, int causal,
+                           int block_q, int block_k, hipStream_t st) {
+    // 256-row workgroups unless that leaves fewer workgroups than the chip has room for at once
+    // (256 CUs): then 128-row workgroups, two per CU, double the count.  D = 64 always takes them.
+    const long big_tiles = (long)BH * ((N + 8 * WROWS - 1) / (8 * WROWS));
+    const bool small = QS == 1 && (D == 64 || big_tiles < 2 * 256);
+    if (small) return launch_dn<D, 4>(qq, qscale, kq, kscale, v, o, sdump, BH, N, causal, block_q, block_k, st);
+    return launch_dn<D, 8>(qq, qscale, kq, kscale, v, o, sdump, BH, N, causal, block_q, block_k, st);
 }
 
 hipError_t launch_attn(const int8_t* qq, const float* qscale, const int8_t* kq, const float* kscale,

@@ -53,6 +53,11 @@ WORKLOADS = {
     "cfg4_video": Workload("cfg4_video", 2, 30, 17776, 64, False, 128, 64, 0.5, 3.0, 0.0, 1.0, BASE_SEED + 4),
     # long-context prefill
     "cfg5_prefill128k": Workload("cfg5_prefill128k", 1, 8, 131072, 128, True, 128, 64, 1.0, 4.0, 0.0, 1.0, BASE_SEED + 5),
+    # the remaining shapes of the paper's real-shape speed table (short and mid-length sequences)
+    "shape_llm_1536": Workload("shape_llm_1536", 4, 32, 1536, 128, True, 128, 64, 1.0, 4.0, 0.0, 1.0, BASE_SEED + 6),
+    "shape_image_7285": Workload("shape_image_7285", 2, 32, 7285, 64, False, 128, 64, 0.5, 3.0, 0.0, 1.0, BASE_SEED + 7),
+    "shape_image_1105": Workload("shape_image_1105", 4, 24, 1105, 64, False, 128, 64, 0.5, 3.0, 0.0, 1.0, BASE_SEED + 8),
+    "shape_vit_197": Workload("shape_vit_197", 12, 64, 197, 64, False, 128, 64, 0.5, 3.0, 0.0, 1.0, BASE_SEED + 9),
 }
 
 

@@ -17,7 +17,8 @@ from gpu_util import assert_output_close, bits, to_dev
 
 pytestmark = pytest.mark.gpu
 
-CASES = [("cfg2_image", 2, 6), ("cfg3_prefill16k", 2, 6), ("cfg4_video", 2, 5), ("cfg5_prefill128k", 1, 4)]
+CASES = [("cfg2_image", 2, 6), ("cfg3_prefill16k", 2, 6), ("cfg4_video", 2, 5), ("cfg5_prefill128k", 1, 4),
+         ("shape_llm_1536", 2, 12), ("shape_image_7285", 2, 8), ("shape_image_1105", 2, 9), ("shape_vit_197", 2, 2)]
 
 
 def sample_blocks(Tm, n, seed):
