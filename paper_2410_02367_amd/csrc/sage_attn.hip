@@ -143,8 +143,9 @@ __device__ __forceinline__ void l_mfma(const v16f& acc, const v4i& ones, const v
 // tell which LDS bytes such a load writes, makes every later LDS read wait for it (vmcnt(0)) and
 // so turns the asynchronous load into a synchronous one.  Completion is tracked by hand: the
 // issuing wavefront waits with s_waitcnt vmcnt before the barrier that publishes the tile.
-__device__ __forceinline__ void load_to_lds16(const void* gaddr, unsigned lds_addr) {
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(gaddr), "s"(lds_addr) : "memory");
+__device__ __forceinline__ void load_to_lds16(const void* gbase, unsigned goff, unsigned lds_addr) {
+    // address = wave-uniform 64-bit base (scalar registers) + per-lane 32-bit byte offset
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(goff), "s"(gbase), "s"(lds_addr) : "memory");
 }
 // Tells the compiler that an accumulator changed, 12 wait states after the last matrix instruction
 // that wrote it (all of these statements are volatile, so their order is kept).
@@ -263,9 +264,13 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
 #pragma unroll
         for (int i = 0; i < KL; ++i) {
             if (NTHREADS * (i + 1) > KVEC && NTHREADS * i + wave * 64 >= KVEC) continue;   // piece beyond the tile for this wavefront
-            int delta = 0;
-            if (kv0 + KTILE > N) { int row = k_goff[i] / D, rc = row < lim ? row : lim; delta = (rc - row) * D; }
-            load_to_lds16(kt + k_goff[i] + delta, lds_base + buf * KB + (NTHREADS * i + wave * 64) * 16);
+            int off = k_goff[i];
+            if (kv0 + KTILE > N) {       // last tile only; the empty statement keeps this a branch instead of a select
+                asm volatile("");
+                int row = k_goff[i] / D, rc = row < lim ? row : lim;
+                off += (rc - row) * D;
+            }
+            load_to_lds16(kt, off, lds_base + buf * KB + (NTHREADS * i + wave * 64) * 16);
         }
     };
     auto load_v = [&](int j, int buf) {
@@ -275,9 +280,13 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
 #pragma unroll
         for (int i = 0; i < VL; ++i) {
             if (NTHREADS * (i + 1) > VVEC && NTHREADS * i + wave * 64 >= VVEC) continue;
-            int delta = 0;
-            if (kv0 + KTILE > N) { int row = v_goff[i] / (2 * D), rc = row < lim ? row : lim; delta = (rc - row) * 2 * D; }
-            load_to_lds16(vt + v_goff[i] + delta, lds_base + 2 * KB + buf * VB + (NTHREADS * i + wave * 64) * 16);
+            int off = v_goff[i];
+            if (kv0 + KTILE > N) {
+                asm volatile("");
+                int row = v_goff[i] / (2 * D), rc = row < lim ? row : lim;
+                off += (rc - row) * 2 * D;
+            }
+            load_to_lds16(vt, off, lds_base + 2 * KB + buf * VB + (NTHREADS * i + wave * 64) * 16);
         }
     };
     // own tile loads landed (vmcnt(0)), then the workgroup barrier
