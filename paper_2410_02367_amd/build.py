@@ -53,6 +53,10 @@ def check_attention_asm(text: str) -> list:
         rare rescale and the epilogue), i.e. never inside a block that issues matrix instructions,
       - nothing spills to scratch memory,
       - and it never touches m0, which the hand-written global->LDS loads set.
+      - no instruction touches a VGPR within 12 wait states of a matrix instruction writing it
+        (except the next matrix instruction of the same accumulation chain), and no matrix
+        instruction reads a VGPR that one of the two preceding instructions wrote -- the waits the
+        compiler would insert if it knew these were matrix instructions.
     Instructions between ";;#ASMSTART" and ";;#ASMEND" are the source's own assembly."""
     import re
     kernels = re.findall(r"^(_ZN4sage16sage_attn_kernel\w+):.*?^\.Lfunc_end\d+:", text, re.S | re.M)
@@ -60,10 +64,25 @@ def check_attention_asm(text: str) -> list:
     problems = []
     if len(bodies) != 12:
         problems.append(f"expected 12 attention kernels in the assembly, found {len(bodies)}")
+
+    def vregs(operand: str) -> set:
+        """VGPR numbers named by one operand such as v12 or v[12:15]."""
+        m = re.fullmatch(r"v\[(\d+):(\d+)\]", operand)
+        if m:
+            return set(range(int(m.group(1)), int(m.group(2)) + 1))
+        m = re.fullmatch(r"v(\d+)", operand)
+        return {int(m.group(1))} if m else set()
+
+    def operands(code: str) -> list:
+        parts = code.split(None, 1)
+        return [o.strip() for o in parts[1].split(",")] if len(parts) > 1 else []
+
     for name, body in zip(kernels, bodies):
         state = {"mfma": False, "reads": []}
         in_asm = False
         seen_mfma = False
+        pending = []          # [registers written by a matrix instruction, wait states since, its text]
+        recent = []           # VGPRs written by the last two non-matrix instructions
 
         def close_block():
             if state["mfma"] and state["reads"]:
@@ -80,11 +99,43 @@ def check_attention_asm(text: str) -> list:
                 continue
             if re.match(r"^\.LBB\d+_\d+:", line) or code.startswith("s_cbranch") or code.startswith("s_branch"):
                 close_block()
+                if code.startswith("s_branch"):
+                    pending, recent = [], []          # nothing falls through an unconditional branch
+                elif code:
+                    for p_ in pending:
+                        p_[1] += 1
                 continue
             if not code or code.startswith("."):
                 continue
+            ops = operands(code)
+            touched = set().union(*[vregs(o) for o in ops]) if ops else set()
+            is_mfma = code.startswith("v_mfma")
+            # --- hazard windows
+            for p_ in pending:
+                same_chain = is_mfma and ops and vregs(ops[0]) == p_[0] and vregs(ops[-1]) == p_[0]
+                if touched & p_[0] and not same_chain:
+                    problems.append(f"{name}: '{code}' touches the result of '{p_[2]}' after {p_[1]} wait states")
+            if is_mfma:
+                for o in ops[1:]:
+                    for w in recent:
+                        if vregs(o) & w:
+                            problems.append(f"{name}: '{code}' reads a register written less than 2 wait states before")
+            m = re.match(r"s_nop\s+(\d+)", code)
+            step = int(m.group(1)) + 1 if m else 1
+            for p_ in pending:
+                p_[1] += step
+            pending = [p_ for p_ in pending if p_[1] < 12]
+            if is_mfma:
+                dst = vregs(ops[0]) if ops else set()
+                if dst:
+                    pending.append([dst, 0, code])
+                recent = []
+            else:
+                wrote = vregs(ops[0]) if ops and code.startswith("v_") else set()      # VALU results only: loads are covered by s_waitcnt
+                recent = ([wrote] + recent)[:2] if step == 1 else []
+            # --- register-file rules
             if in_asm:
-                if code.startswith("v_mfma"):
+                if is_mfma:
                     state["mfma"] = True
                     seen_mfma = True
                 continue

@@ -61,3 +61,25 @@ def test_scratch_and_m0_are_reported():
 def test_m0_inside_the_sources_own_assembly_is_allowed():
     ok = CLEAN.replace("\ts_nop 11\n", "\ts_mov_b32 m0, s4\n\ts_nop 0\n\tglobal_load_lds_dwordx4 v[0:1], off\n")
     assert check_attention_asm(fake(ok)) == []
+
+
+def test_touching_a_matrix_result_too_early_is_reported():
+    early = CLEAN.replace("\tv_fma_f32 v1, v2, v3, v4\n",
+                          "\t;;#ASMSTART\n\tv_mfma_i32_32x32x32_i8 v[8:23], v[0:3], a[0:3], v[8:23]\n\t;;#ASMEND\n"
+                          "\tv_add_f32_e32 v30, v31, v32\n\tv_exp_f32_e32 v9, v30\n")
+    assert any("touches the result" in p for p in check_attention_asm(fake(early)))
+    # the same access after a long enough pause is fine, and so is the next instruction of the chain
+    late = early.replace("\tv_add_f32_e32 v30, v31, v32\n", "\ts_nop 11\n")
+    assert check_attention_asm(fake(late)) == []
+    chain = CLEAN.replace("\tv_fma_f32 v1, v2, v3, v4\n",
+                          "\t;;#ASMSTART\n\tv_mfma_i32_32x32x32_i8 v[8:23], v[0:3], a[0:3], v[8:23]\n\t;;#ASMEND\n"
+                          "\t;;#ASMSTART\n\tv_mfma_i32_32x32x32_i8 v[8:23], v[4:7], a[4:7], v[8:23]\n\t;;#ASMEND\n\ts_nop 11\n")
+    assert check_attention_asm(fake(chain)) == []
+
+
+def test_matrix_instruction_reading_a_fresh_valu_result_is_reported():
+    bad = CLEAN.replace("\t;;#ASMSTART\n\tv_mfma_f32_32x32x16_f16 a[0:15], v[0:3], v[4:7], a[0:15]\n",
+                        "\tv_cvt_pk_f16_f32 v5, v20, v21\n\t;;#ASMSTART\n\tv_mfma_f32_32x32x16_f16 a[0:15], v[0:3], v[4:7], a[0:15]\n")
+    assert any("less than 2 wait states" in p for p in check_attention_asm(fake(bad)))
+    ok = bad.replace("\tv_cvt_pk_f16_f32 v5, v20, v21\n", "\tv_cvt_pk_f16_f32 v5, v20, v21\n\tv_mov_b32_e32 v40, v41\n\tv_mov_b32_e32 v42, v41\n")
+    assert check_attention_asm(fake(ok)) == []
