@@ -653,6 +653,10 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
         step_b(j);
         asm volatile("" : "+s"(opaque));
     }
+    // The scores of tile Tw that the last step produced are never read: keep their registers
+    // untouched until the matrix instructions have written them (the compiler would hand them out
+    // as temporaries at once).
+    score_fence();
     // the P~V of the wavefront's last tile ...
     turn(j);
     {
