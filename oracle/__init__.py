@@ -138,45 +138,56 @@ def qk_i32(qq: np.ndarray, kq: np.ndarray, row0: int = 0, nrows: int | None = No
     return s
 
 
-def attn_l2(qq, q_scale, kq, k_scale, v, causal: bool, block_q: int, block_k: int, flags: int = 0):
-    """Algorithm 1 on whole [B, H, N, D] tensors -> fp16 output."""
+def attn_l2(qq, q_scale, kq, k_scale, v, causal: bool, block_q: int, block_k: int, flags: int = 0,
+            gran_q: int | None = None, gran_k: int | None = None):
+    """Algorithm 1 on whole [B, H, N, D] tensors -> fp16 output.
+
+    gran_q / gran_k: tokens per scale of Q^ / K^ (default: the loop's block sizes, i.e. SAGEAttn-B;
+    1 = the per-token quantizer of Section 3.2, i.e. SAGEAttn-T)."""
+    gran_q = block_q if gran_q is None else gran_q
+    gran_k = block_k if gran_k is None else gran_k
     v = _f16(v); B, H, N, D = v.shape
     qq = np.ascontiguousarray(qq, np.int8); kq = np.ascontiguousarray(kq, np.int8)
     q_scale = np.ascontiguousarray(q_scale, np.float32); k_scale = np.ascontiguousarray(k_scale, np.float32)
     assert qq.shape == (B, H, N, D) and kq.shape == (B, H, N, D)
-    assert q_scale.shape == (B, H, nblocks(N, block_q)) and k_scale.shape == (B, H, nblocks(N, block_k))
+    assert q_scale.shape == (B, H, nblocks(N, gran_q)) and k_scale.shape == (B, H, nblocks(N, gran_k))
     o = np.zeros((B, H, N, D), np.float16)
-    _L().sage_oracle_attn_l2(_p(qq), _p(q_scale), _p(kq), _p(k_scale), _p(v),
-                             *map(ctypes.c_int, (B, H, N, D, int(causal), block_q, block_k)),
-                             ctypes.c_uint(flags), _p(o))
+    _L().sage_oracle_attn_l2_g(_p(qq), _p(q_scale), _p(kq), _p(k_scale), _p(v),
+                               *map(ctypes.c_int, (B, H, N, D, int(causal), block_q, block_k, gran_q, gran_k)),
+                               ctypes.c_uint(flags), _p(o))
     return o
 
 
 def attn_l2_slab(qq, q_scale, kq, k_scale, v, causal: bool, block_q: int, block_k: int,
-                 q_blocks=None, flags: int = 0):
+                 q_blocks=None, flags: int = 0, gran_q: int | None = None, gran_k: int | None = None):
     """Algorithm 1 on one slab [N, D] for the listed Q blocks (all if None).
 
-    Returns an fp16 [N, D] array; rows of blocks that were not requested are zero."""
+    Returns an fp16 [N, D] array; rows of blocks that were not requested are zero.
+    gran_q / gran_k as in attn_l2."""
+    gran_q = block_q if gran_q is None else gran_q
+    gran_k = block_k if gran_k is None else gran_k
     v = _f16(v); N, D = v.shape
     qq = np.ascontiguousarray(qq, np.int8); kq = np.ascontiguousarray(kq, np.int8)
     q_scale = np.ascontiguousarray(q_scale, np.float32); k_scale = np.ascontiguousarray(k_scale, np.float32)
-    assert q_scale.shape == (nblocks(N, block_q),) and k_scale.shape == (nblocks(N, block_k),)
+    assert q_scale.shape == (nblocks(N, gran_q),) and k_scale.shape == (nblocks(N, gran_k),)
     o = np.zeros((N, D), np.float16)
     if q_blocks is None:
         blocks, nb = None, -1
     else:
         blocks = np.ascontiguousarray(q_blocks, np.int32); nb = len(blocks)
         assert nb == 0 or (blocks.min() >= 0 and blocks.max() < nblocks(N, block_q))
-    _L().sage_oracle_attn_l2_slab(_p(qq), _p(q_scale), _p(kq), _p(k_scale), _p(v),
-                                  *map(ctypes.c_int, (N, D, int(causal), block_q, block_k)),
-                                  ctypes.c_uint(flags),
+    _L().sage_oracle_attn_l2_slab_g(_p(qq), _p(q_scale), _p(kq), _p(k_scale), _p(v),
+                                    *map(ctypes.c_int, (N, D, int(causal), block_q, block_k, gran_q, gran_k)),
+                                    ctypes.c_uint(flags),
                                   _p(blocks) if blocks is not None else None, ctypes.c_int(nb), _p(o))
     return o
 
 
 def attn_l1_slab(qq, q_scale, kq, k_scale, v, causal: bool, block_q: int, block_k: int,
                  row0: int = 0, nrows: int | None = None) -> np.ndarray:
-    """Quantized scores, exact fp64 softmax and P V (Section 4.1 with P, V unquantized)."""
+    """Quantized scores, exact fp64 softmax and P V (Section 4.1 with P, V unquantized).
+
+    block_q / block_k are the tokens per scale (1 = per-token quantizer); there is no block loop."""
     v = _f16(v); N, D = v.shape
     qq = np.ascontiguousarray(qq, np.int8); kq = np.ascontiguousarray(kq, np.int8)
     q_scale = np.ascontiguousarray(q_scale, np.float32); k_scale = np.ascontiguousarray(k_scale, np.float32)

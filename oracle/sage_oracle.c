@@ -218,10 +218,13 @@ void sage_oracle_qk_i32(const int8_t* qq, const int8_t* kq, int N, int D, int ro
 
 /* Q block `i` (rows i*bq .. min(N,(i+1)*bq)-1) of one slab; writes those rows of o (fp16 bits, [N,D]).
  * Causal reading: key j is visible to query t iff j <= t; kv blocks entirely above the diagonal
- * are not visited. */
+ * are not visited.
+ * gq / gk = tokens per scale of Q^ / K^: equal to bq / bkv for Algorithm 1 (one scale per block of
+ * the loop), 1 for the per-token quantizer of Section 3.2 (SAGEAttn-T): query t is dequantized
+ * with q_scale[t / gq], key j with k_scale[j / gk]. */
 static void l2_q_block(const int8_t* qq, const float* q_scale, const int8_t* kq, const float* k_scale,
-                       const uint16_t* v, int N, int D, int causal, int bq, int bkv, unsigned flags,
-                       int i, uint16_t* o) {
+                       const uint16_t* v, int N, int D, int causal, int bq, int bkv, int gq, int gk,
+                       unsigned flags, int i, uint16_t* o) {
     int r0 = i * bq, r1 = r0 + bq < N ? r0 + bq : N, nr = r1 - r0;
     int Tn = (N + bkv - 1) / bkv;
     float* m = (float*)malloc(sizeof(float) * nr);
@@ -230,20 +233,18 @@ static void l2_q_block(const int8_t* qq, const float* q_scale, const int8_t* kq,
     float* S = (float*)malloc(sizeof(float) * (size_t)nr * bkv);
     float* Pt = (float*)malloc(sizeof(float) * (size_t)bkv);
     for (int a = 0; a < nr; ++a) { m[a] = -INFINITY; l[a] = 0.0f; }
-    float dq = q_scale[i];
 
     for (int j = 0; j < Tn; ++j) {
         int c0 = j * bkv, c1 = c0 + bkv < N ? c0 + bkv : N, nc = c1 - c0;
         if (causal && c0 > r1 - 1) break;
-        float dk = k_scale[j];
         /* S = Matmul(Q^_i, K^_j^T) * dQ[i] * dK[j], then the mask */
         for (int a = 0; a < nr; ++a)
             for (int b = 0; b < nc; ++b) {
                 int32_t acc = 0;
                 for (int c = 0; c < D; ++c)
                     acc += (int32_t)qq[(int64_t)(r0 + a) * D + c] * (int32_t)kq[(int64_t)(c0 + b) * D + c];
-                volatile float t1 = (float)acc * dq;
-                volatile float t2 = t1 * dk;
+                volatile float t1 = (float)acc * q_scale[(r0 + a) / gq];
+                volatile float t2 = t1 * k_scale[(c0 + b) / gk];
                 S[a * bkv + b] = (causal && (c0 + b) > (r0 + a)) ? -INFINITY : t2;
             }
         /* online softmax and O update, row by row */
@@ -300,37 +301,54 @@ static void l2_q_block(const int8_t* qq, const float* q_scale, const int8_t* kq,
 }
 
 /* L2 on one slab for a list of Q blocks (nblocks < 0: all of them). Rows of other blocks in
- * `o` are left untouched. */
-void sage_oracle_attn_l2_slab(const int8_t* qq, const float* q_scale, const int8_t* kq,
-                              const float* k_scale, const uint16_t* v, int N, int D, int causal,
-                              int block_q, int block_k, unsigned flags,
-                              const int* blocks, int nblocks, uint16_t* o) {
+ * `o` are left untouched.  gran_q / gran_k: tokens per scale (see l2_q_block). */
+void sage_oracle_attn_l2_slab_g(const int8_t* qq, const float* q_scale, const int8_t* kq,
+                                const float* k_scale, const uint16_t* v, int N, int D, int causal,
+                                int block_q, int block_k, int gran_q, int gran_k, unsigned flags,
+                                const int* blocks, int nblocks, uint16_t* o) {
     int Tm = (N + block_q - 1) / block_q;
     int n = nblocks < 0 ? Tm : nblocks;
 #pragma omp parallel for schedule(dynamic)
     for (int u = 0; u < n; ++u) {
         int i = nblocks < 0 ? u : blocks[u];
-        l2_q_block(qq, q_scale, kq, k_scale, v, N, D, causal, block_q, block_k, flags, i, o);
+        l2_q_block(qq, q_scale, kq, k_scale, v, N, D, causal, block_q, block_k, gran_q, gran_k, flags, i, o);
     }
 }
+/* Algorithm 1 proper: one scale per block of the loop. */
+void sage_oracle_attn_l2_slab(const int8_t* qq, const float* q_scale, const int8_t* kq,
+                              const float* k_scale, const uint16_t* v, int N, int D, int causal,
+                              int block_q, int block_k, unsigned flags,
+                              const int* blocks, int nblocks, uint16_t* o) {
+    sage_oracle_attn_l2_slab_g(qq, q_scale, kq, k_scale, v, N, D, causal, block_q, block_k,
+                               block_q, block_k, flags, blocks, nblocks, o);
+}
 
-/* L2 on whole tensors [B,H,N,D]. */
-void sage_oracle_attn_l2(const int8_t* qq, const float* q_scale, const int8_t* kq, const float* k_scale,
-                         const uint16_t* v, int B, int H, int N, int D, int causal,
-                         int block_q, int block_k, unsigned flags, uint16_t* o) {
-    int Tm = (N + block_q - 1) / block_q, Tn = (N + block_k - 1) / block_k;
+/* L2 on whole tensors [B,H,N,D]; scales [B,H,ceil(N/gran)]. */
+void sage_oracle_attn_l2_g(const int8_t* qq, const float* q_scale, const int8_t* kq, const float* k_scale,
+                           const uint16_t* v, int B, int H, int N, int D, int causal,
+                           int block_q, int block_k, int gran_q, int gran_k, unsigned flags, uint16_t* o) {
+    int Tm = (N + block_q - 1) / block_q;
+    int nsq = (N + gran_q - 1) / gran_q, nsk = (N + gran_k - 1) / gran_k;
     int64_t units = (int64_t)B * H * Tm;
 #pragma omp parallel for schedule(dynamic)
     for (int64_t u = 0; u < units; ++u) {
         int64_t s = u / Tm; int i = (int)(u % Tm);
-        l2_q_block(qq + s * N * D, q_scale + s * Tm, kq + s * N * D, k_scale + s * Tn,
-                   v + s * N * D, N, D, causal, block_q, block_k, flags, i, o + s * N * D);
+        l2_q_block(qq + s * N * D, q_scale + s * nsq, kq + s * N * D, k_scale + s * nsk,
+                   v + s * N * D, N, D, causal, block_q, block_k, gran_q, gran_k, flags, i,
+                   o + s * N * D);
     }
+}
+void sage_oracle_attn_l2(const int8_t* qq, const float* q_scale, const int8_t* kq, const float* k_scale,
+                         const uint16_t* v, int B, int H, int N, int D, int causal,
+                         int block_q, int block_k, unsigned flags, uint16_t* o) {
+    sage_oracle_attn_l2_g(qq, q_scale, kq, k_scale, v, B, H, N, D, causal, block_q, block_k,
+                          block_q, block_k, flags, o);
 }
 
 /* ------------------------------------------------------------------ L1: quantized S, exact softmax */
 
-/* Rows [row0,row0+nrows) of one slab: S = dQ dK S^ in fp64, two-pass softmax, fp64 P V. */
+/* Rows [row0,row0+nrows) of one slab: S = dQ dK S^ in fp64, two-pass softmax, fp64 P V.
+ * block_q / block_k are the tokens per scale here (1 = per-token quantizer); L1 has no block loop. */
 void sage_oracle_attn_l1_slab(const int8_t* qq, const float* q_scale, const int8_t* kq,
                               const float* k_scale, const uint16_t* v, int N, int D, int causal,
                               int block_q, int block_k, int row0, int nrows, double* o /* [nrows,D] */) {

@@ -255,3 +255,97 @@ def test_cfg1_end_to_end_accuracy_against_exact_attention():
     ref = np.stack([oracle.attn_l0_slab(q[0, h], k[0, h], v[0, h], False, w.sm_scale) for h in range(w.H)])[None]
     m = oracle.accuracy_metrics(ref, o)
     assert m["cos"] > 0.9999 and m["rel_l1"] < 0.03
+
+
+# ------------------------------------------------------------------ per-token scales (SAGEAttn-T)
+
+def brute_quantized_attention(qq, dq_tok, kq, dk_tok, v, causal):
+    """softmax(diag(dQ) Q^ K^^T diag(dK)) V with numpy in fp64, one scale per token -- Section 4.1's
+    formula with Section 3.2's per-token quantizer, independent of the C code."""
+    s = (qq.astype(np.float64) @ kq.astype(np.float64).T) * dq_tok.astype(np.float64)[:, None] * dk_tok.astype(np.float64)[None, :]
+    if causal:
+        n = s.shape[0]
+        s = np.where(np.arange(n)[None, :] > np.arange(n)[:, None], -np.inf, s)
+    p = np.exp(s - s.max(axis=1, keepdims=True))
+    return (p / p.sum(axis=1, keepdims=True)) @ v.astype(np.float64)
+
+
+@pytest.mark.parametrize("N,D,bq,bk,causal", [(200, 32, 64, 32, False), (177, 64, 128, 64, True)])
+def test_per_token_scales_repeated_from_block_scales_reproduce_algorithm_1_bit_for_bit(N, D, bq, bk, causal):
+    # a per-token scale vector that is constant inside every block IS the per-block method
+    q, k, v = rand_qkv(31 + N, N, D, k_bias=2.0)
+    qq, qd, kq, kd = quantized_inputs(q, k, v, 0.2, bq, bk)
+    base = oracle.attn_l2_slab(qq, qd, kq, kd, v, causal, bq, bk)
+    qd_tok, kd_tok = np.repeat(qd, bq)[:N], np.repeat(kd, bk)[:N]
+    tok = oracle.attn_l2_slab(qq, qd_tok, kq, kd_tok, v, causal, bq, bk, gran_q=1, gran_k=1)
+    assert np.array_equal(base.view(np.uint16), tok.view(np.uint16))
+    mixed = oracle.attn_l2_slab(qq, qd_tok, kq, kd, v, causal, bq, bk, gran_q=1)
+    assert np.array_equal(base.view(np.uint16), mixed.view(np.uint16))
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_per_token_levels_match_the_numpy_definition_with_unrelated_scale_vectors(causal):
+    # random codes and two unrelated scale vectors: a scale applied along the wrong axis, or
+    # indexed by the block instead of the token, changes the result by far more than the tolerance
+    g = np.random.default_rng(77)
+    N, D = 150, 32
+    qq = g.integers(-127, 128, (N, D), dtype=np.int8); kq = g.integers(-127, 128, (N, D), dtype=np.int8)
+    dq = (g.uniform(0.2, 3.0, N) * 2e-3).astype(np.float32); dk = (g.uniform(0.2, 3.0, N) * 2e-3).astype(np.float32)
+    v = g.standard_normal((N, D)).astype(np.float16)
+    ref = brute_quantized_attention(qq, dq, kq, dk, v, causal)
+    o1 = oracle.attn_l1_slab(qq, dq, kq, dk, v, causal, 1, 1)
+    assert np.abs(o1 - ref).max() <= 1e-12
+    o2 = oracle.attn_l2_slab(qq, dq, kq, dk, v, causal, 64, 32, gran_q=1, gran_k=1).astype(np.float64)
+    assert np.abs(o2 - ref).max() <= 1e-3 + 2.0 ** -11 * np.abs(ref).max()
+    swapped = brute_quantized_attention(qq, dk, kq, dq, v, causal)
+    assert np.abs(swapped - ref).max() > 0.05           # the inputs do tell the two axes apart
+    # the loop's block sizes do not matter once the scales are per token
+    o3 = oracle.attn_l2_slab(qq, dq, kq, dk, v, causal, 32, 64, gran_q=1, gran_k=1).astype(np.float64)
+    assert np.abs(o3 - o2).max() <= 1e-3
+
+
+def test_per_token_whole_tensor_entry_equals_slab_entry():
+    w = si.custom("t", 2, 2, 150, 32, True, 64, 32)
+    q, k, v = si.full(w)
+    kq, ks, km = oracle.smooth_quant_k(k, 1)
+    qq, qs = oracle.quant_q(q, w.sm_scale, 1)
+    assert ks.shape == (2, 2, 150) and qs.shape == (2, 2, 150)
+    o = oracle.attn_l2(qq, qs, kq, ks, v, True, 64, 32, gran_q=1, gran_k=1)
+    for b in range(2):
+        for h in range(2):
+            o_s = oracle.attn_l2_slab(qq[b, h], qs[b, h], kq[b, h], ks[b, h], v[b, h], True, 64, 32, gran_q=1, gran_k=1)
+            assert np.array_equal(o[b, h].view(np.uint16), o_s.view(np.uint16))
+
+
+def test_per_token_accuracy_on_normal_inputs_matches_the_papers_order_of_magnitude():
+    nums = paper_numbers()
+    cos_p, l1_p, rmse_p = nums["sageattn_t_normal"]
+    q, k, v = rand_qkv(0, 1024, 64)
+    sm = 0.125
+    ref = oracle.attn_l0_slab(q, k, v, False, sm)
+    qq, qd, kq, kd = quantized_inputs(q, k, v, sm, 1, 1)
+    m_t = oracle.accuracy_metrics(ref, oracle.attn_l1_slab(qq, qd, kq, kd, v, False, 1, 1))
+    assert m_t["cos"] > 0.9999 and round(m_t["cos"], 3) == cos_p
+    assert l1_p / 4 < m_t["rel_l1"] < l1_p * 2 and rmse_p / 4 < m_t["rmse"] < rmse_p * 2
+    # the paper's ordering: per-token is (slightly) more accurate than per-block on the same inputs
+    qq, qd, kq, kd = quantized_inputs(q, k, v, sm, 128, 64)
+    m_b = oracle.accuracy_metrics(ref, oracle.attn_l1_slab(qq, qd, kq, kd, v, False, 128, 64))
+    assert m_t["rel_l1"] < m_b["rel_l1"] and m_t["rmse"] < m_b["rmse"]
+    assert m_t["rel_l1"] > 0.5 * m_b["rel_l1"]          # ... but of the same order (paper: 0.019 against 0.021)
+
+
+def test_per_token_scales_absorb_token_outliers_that_hurt_per_block_scales():
+    """A few tokens 30x larger than the rest share their block's scale under the per-block
+    quantizer and crush the other tokens' codes; the per-token quantizer is immune."""
+    q, k, v = rand_qkv(9, 512, 64)
+    g = np.random.default_rng(10)
+    big = g.choice(512, 16, replace=False)
+    q = q.copy(); k = k.copy()
+    q[big] *= np.float16(30.0); k[g.choice(512, 16, replace=False)] *= np.float16(30.0)
+    sm = 0.02
+    ref = oracle.attn_l0_slab(q, k, v, False, sm)
+    qq, qd, kq, kd = quantized_inputs(q, k, v, sm, 1, 1)
+    m_t = oracle.accuracy_metrics(ref, oracle.attn_l1_slab(qq, qd, kq, kd, v, False, 1, 1))
+    qq, qd, kq, kd = quantized_inputs(q, k, v, sm, 128, 64)
+    m_b = oracle.accuracy_metrics(ref, oracle.attn_l1_slab(qq, qd, kq, kd, v, False, 128, 64))
+    assert m_t["rmse"] < 0.5 * m_b["rmse"] and m_t["cos"] > 0.99 > m_b["cos"]
