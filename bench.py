@@ -31,7 +31,7 @@ HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 ATTN_TRAFFIC_BYTES = {"cfg3_prefill16k": 516.5e6}
 
 
-def cpu_baseline(w, seconds_budget=20.0):
+def cpu_baseline(w, seconds_budget=20.0, per_token=False):
     """Oracle (Algorithm-1 level, as it stands) on one head of the workload: the full pre-pass of that
     head plus a spread of Q blocks, scaled to the head's block-pair count."""
     import numpy as np
@@ -41,8 +41,9 @@ def cpu_baseline(w, seconds_budget=20.0):
 
     q, k, v = si.slab(w, 0, 0)
     t0 = time.perf_counter()
-    kq, ks, km = oracle.smooth_quant_k(k[None, None], w.block_k)
-    qq, qs = oracle.quant_q(q[None, None], w.sm_scale, w.block_q)
+    gran = dict(gran_q=1, gran_k=1) if per_token else {}
+    kq, ks, km = oracle.smooth_quant_k(k[None, None], 1 if per_token else w.block_k)
+    qq, qs = oracle.quant_q(q[None, None], w.sm_scale, 1 if per_token else w.block_q)
     t_pre = time.perf_counter() - t0
     Tm = (w.N + w.block_q - 1) // w.block_q
     Tn = (w.N + w.block_k - 1) // w.block_k
@@ -57,7 +58,7 @@ def cpu_baseline(w, seconds_budget=20.0):
     # probe one block to size the sample
     mid = Tm // 2
     t0 = time.perf_counter()
-    oracle.attn_l2_slab(qq[0, 0], qs[0, 0], kq[0, 0], ks[0, 0], v, w.causal, w.block_q, w.block_k, q_blocks=[mid])
+    oracle.attn_l2_slab(qq[0, 0], qs[0, 0], kq[0, 0], ks[0, 0], v, w.causal, w.block_q, w.block_k, q_blocks=[mid], **gran)
     t_one = time.perf_counter() - t0
     per_pair = t_one / pairs(mid)
     threads = oracle.num_threads()
@@ -66,7 +67,7 @@ def cpu_baseline(w, seconds_budget=20.0):
     n_blocks = max(threads, (n_blocks // threads) * threads)
     blocks = sorted(set(np.linspace(0, Tm - 1, n_blocks).round().astype(int).tolist()))
     t0 = time.perf_counter()
-    oracle.attn_l2_slab(qq[0, 0], qs[0, 0], kq[0, 0], ks[0, 0], v, w.causal, w.block_q, w.block_k, q_blocks=blocks)
+    oracle.attn_l2_slab(qq[0, 0], qs[0, 0], kq[0, 0], ks[0, 0], v, w.causal, w.block_q, w.block_k, q_blocks=blocks, **gran)
     t_blocks = time.perf_counter() - t0
     sampled_pairs = sum(pairs(i) for i in blocks)
     t_head = t_pre + t_blocks * total_pairs / sampled_pairs
@@ -88,6 +89,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg3_prefill16k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--scales", choices=("block", "token"), default="block",
+                    help="block: one scale per block_q / block_k tokens (Algorithm 1, the headline); "
+                         "token: one scale per token of Q and K (the SAGEAttn-T kernel)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one plain elementwise copy kernel of 1 GiB before the warm-up, so that a "
                          "hardware-counter run holds a kernel of known HBM traffic beside the library's kernels")
@@ -111,7 +115,9 @@ def main():
     qd, kd, vd = (torch.from_numpy(a).cuda() for a in (q, k, v))
     del q, k, v
     B, H, N, D = w.B, w.H, w.N, w.D
-    nbq, nbk = (N + w.block_q - 1) // w.block_q, (N + w.block_k - 1) // w.block_k
+    per_token = args.scales == "token"
+    bq, bk = (1, 1) if per_token else (w.block_q, w.block_k)
+    nbq, nbk = (N + bq - 1) // bq, (N + bk - 1) // bk
     q_i8 = torch.empty((B, H, N, D), dtype=torch.int8, device="cuda")
     k_i8 = torch.empty_like(q_i8)
     q_scale = torch.empty((B, H, nbq), dtype=torch.float32, device="cuda")
@@ -127,11 +133,11 @@ def main():
     def step(i=None):
         if i is not None:
             ev[i][0].record(stream)
-        sage.sage_smooth_quant_k(kd, w.block_k, k_i8, k_scale, k_mean, ws, stream)
-        sage.sage_quant_q(qd, w.sm_scale, w.block_q, q_i8, q_scale, stream)
+        sage.sage_smooth_quant_k(kd, bk, k_i8, k_scale, k_mean, ws, stream)
+        sage.sage_quant_q(qd, w.sm_scale, bq, q_i8, q_scale, stream)
         if i is not None:
             ev[i][1].record(stream)
-        sage.sage_attn_fwd(q_i8, q_scale, k_i8, k_scale, vd, w.causal, w.sm_scale, w.block_q, w.block_k, out, stream)
+        sage.sage_attn_fwd(q_i8, q_scale, k_i8, k_scale, vd, w.causal, w.sm_scale, bq, bk, out, stream)
         if i is not None:
             ev[i][2].record(stream)
 
@@ -173,7 +179,9 @@ def main():
         "dtype": "int8 QK^T (int32 acc) + fp16 PV (fp32 acc)",
         "data": "synthetic",
         "config": {"workload": f"{w.name}: B={B} H={H} N={N} D={D} causal={w.causal} fp16 in/out, "
-                               f"block_q={w.block_q} block_k={w.block_k}; step = K pre-pass + Q pre-pass + attention"},
+                               + ("one scale per token of Q and K (SAGEAttn-T)" if per_token else
+                                  f"block_q={w.block_q} block_k={w.block_k}")
+                               + "; step = K pre-pass + Q pre-pass + attention"},
         "attn_kernel_ms": attn_ms,
         "prepass_ms": pre_ms,
         "attn_only_tops": attn_tops,
@@ -184,7 +192,7 @@ def main():
             "peak": INT8_PEAK_TOPS,
             "unit": "TFLOP/s",
             "frac": attn_tops / INT8_PEAK_TOPS,
-            "traffic": ATTN_TRAFFIC_BYTES.get(w.name),
+            "traffic": None if per_token else ATTN_TRAFFIC_BYTES.get(w.name),
             "traffic_unit": "bytes per launch (algorithmic: %.1f MB)" % (6.0 * B * H * N * D / 1e6),
             "kernel": "sage_attn_kernel",
             "note": ("achieved = counted ops (half INT8 ops, half FP16 flops) / mean attention-kernel time from HIP "
@@ -205,7 +213,7 @@ def main():
     }
     if not args.no_cpu_baseline:
         del qd, kd, vd
-        result["cpu_baseline"] = cpu_baseline(w)
+        result["cpu_baseline"] = cpu_baseline(w, per_token=per_token)
     print(json.dumps(result))
 
 

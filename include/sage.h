@@ -1,5 +1,5 @@
 /*
- * libsage -- SageAttention forward pass (SAGEAttn-B) for AMD gfx950, C ABI.
+ * libsage -- SageAttention forward pass (SAGEAttn-B and SAGEAttn-T) for AMD gfx950, C ABI.
  *
  * The three calls are the three stages of Algorithm 1 of the SageAttention paper:
  *   sage_smooth_quant_k : "Preprocessing" K = K - mean(K) (Section 4.2) followed by the per-block
@@ -8,6 +8,9 @@
  *                         quantizing (Section 4.6, "Fusion Tricks");
  *   sage_attn_fwd       : the tiled loop of Algorithm 1: S = Q^ K^^T * dQ * dK, online softmax
  *                         (Section 3.1), O += P~.to(FP16) V (Section 4.4), O = diag(l)^-1 O.
+ * A block size of 1 selects Section 3.2's per-token quantizer (one scale per token) instead of the
+ * per-block one; block_q = block_k = 1 in all three calls is the SAGEAttn-T kernel of Section 4.5's
+ * table of kernels.  The two sides are independent: any block_q goes with any block_k.
  *
  * Conventions shared by every call
  *   - All pointers are DEVICE pointers (HIP global memory) unless stated; the library never
@@ -27,7 +30,7 @@
  *   mean[c]  = fp32( (exact sum over the N tokens of K[t,c]) / N ), the division done in fp64;
  *   Ks       = fp32(K) - mean                         (fp32, not re-rounded to fp16);
  *   Qs       = fp32(Q) * sm_scale                     (fp32);
- *   per block of `block` consecutive tokens (all D channels): amax = max |X|,
+ *   per block of `block` consecutive tokens (all D channels; block = 1: per token): amax = max |X|,
  *   delta    = amax / 127   (fp32 division),  r = amax > 0 ? 127 / amax : 0  (fp32 division),
  *   X^       = clamp(round_half_even(X * r), -127, 127);  an all-zero block has delta = 0, X^ = 0.
  *   S^       = Q^ K^^T in int32, exact.
@@ -64,7 +67,7 @@ const char* sage_status_string(int status);
  *   q_i8    out [B,H,N,D] int8, values in [-127,127]
  *   q_scale out [B,H,ceil(N/block_q)] fp32 (delta_Q)
  *   sm_scale    the softmax scale, normally 1/sqrt(D); finite and > 0
- *   block_q     tokens per scale: 32, 64 or 128
+ *   block_q     tokens per scale: 1 (per-token quantizer), 32, 64 or 128
  */
 int sage_quant_q(const void* q_f16, int8_t* q_i8, float* q_scale,
                  int B, int H, int N, int D, float sm_scale, int block_q, void* stream);
@@ -82,7 +85,7 @@ size_t sage_smooth_quant_k_workspace(int B, int H, int N, int D);
  *   workspace   device scratch of at least sage_smooth_quant_k_workspace() bytes, 8-byte aligned;
  *               contents on entry are ignored, contents on return are unspecified.  Two calls
  *               that share a workspace must be ordered on the same stream.
- *   block_k     tokens per scale: 32, 64 or 128
+ *   block_k     tokens per scale: 1 (per-token quantizer), 32, 64 or 128
  */
 int sage_smooth_quant_k(const void* k_f16, int8_t* k_i8, float* k_scale, float* k_mean,
                         void* workspace, size_t workspace_bytes,
@@ -98,7 +101,9 @@ int sage_smooth_quant_k(const void* k_f16, int8_t* k_i8, float* k_scale, float* 
  *   causal      0: every key is visible; non-zero: key j is visible to query t iff j <= t
  *   sm_scale    the value that was given to sage_quant_q; it is already inside q_i8/q_scale and is
  *               NOT applied again here -- it is only validated (finite, > 0)
- *   block_q     32, 64 or 128;  block_k  64 or 128
+ *   block_q     1, 32, 64 or 128;  block_k  1, 64 or 128 -- the values the scales were made with.
+ *               With block_k = 1 every score is dequantized with its own key's scale before the
+ *               row maximum is taken (a few percent slower); block_q = 1 costs nothing.
  */
 int sage_attn_fwd(const int8_t* q_i8, const float* q_scale,
                   const int8_t* k_i8, const float* k_scale,

@@ -73,7 +73,7 @@ def _nblk(N: int, block: int) -> int:
 
 
 def sage_quant_q(q: torch.Tensor, sm_scale: float, block_q: int = 128, q_i8=None, q_scale=None, stream=None):
-    """psi_Q(Q * sm_scale) -> (q_i8 [B,H,N,D] int8, q_scale [B,H,ceil(N/block_q)] fp32)."""
+    """psi_Q(Q * sm_scale) -> (q_i8 [B,H,N,D] int8, q_scale [B,H,ceil(N/block_q)] fp32); block_q = 1: per token."""
     B, H, N, D = q.shape
     if q_i8 is None:
         q_i8 = torch.empty((B, H, N, D), dtype=torch.int8, device=q.device)
@@ -93,7 +93,7 @@ def sage_smooth_quant_k_workspace(B: int, H: int, N: int, D: int) -> int:
 
 def sage_smooth_quant_k(k: torch.Tensor, block_k: int = 64, k_i8=None, k_scale=None, k_mean=None,
                         workspace=None, stream=None):
-    """phi_K(K) -> (k_i8 int8, k_scale [B,H,ceil(N/block_k)] fp32, k_mean [B,H,D] fp32)."""
+    """phi_K(K) -> (k_i8 int8, k_scale [B,H,ceil(N/block_k)] fp32, k_mean [B,H,D] fp32); block_k = 1: per token."""
     B, H, N, D = k.shape
     if k_i8 is None:
         k_i8 = torch.empty((B, H, N, D), dtype=torch.int8, device=k.device)
@@ -115,7 +115,9 @@ def sage_smooth_quant_k(k: torch.Tensor, block_k: int = 64, k_i8=None, k_scale=N
 
 def sage_attn_fwd(q_i8, q_scale, k_i8, k_scale, v, causal: bool, sm_scale: float,
                   block_q: int = 128, block_k: int = 64, out=None, stream=None):
-    """Algorithm 1's loop on pre-quantized Q^, K^ and fp16 V -> O [B,H,N,D] fp16."""
+    """Algorithm 1's loop on pre-quantized Q^, K^ and fp16 V -> O [B,H,N,D] fp16.
+
+    block_q / block_k are the tokens per scale the tensors were quantized with (1 = per token)."""
     B, H, N, D = v.shape
     if out is None:
         out = torch.empty((B, H, N, D), dtype=torch.float16, device=v.device)

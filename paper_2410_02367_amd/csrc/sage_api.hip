@@ -18,7 +18,8 @@ int check_shape(int B, int H, int N, int D) {
     return SAGE_OK;
 }
 
-bool quant_block_ok(int b) { return b == 32 || b == 64 || b == 128; }
+// tokens per scale: 1 = per-token quantizer, else a per-block one
+bool quant_block_ok(int b) { return b == 1 || b == 32 || b == 64 || b == 128; }
 
 }  // namespace
 
@@ -76,7 +77,7 @@ int sage_attn_fwd(const int8_t* q_i8, const float* q_scale, const int8_t* k_i8, 
     if (!q_i8 || !q_scale || !k_i8 || !k_scale || !v_f16 || !o_f16) return SAGE_ERR_NULL;
     if (int e = check_shape(B, H, N, D)) return e;
     if (!quant_block_ok(block_q)) return SAGE_ERR_UNSUPPORTED;
-    if (block_k != 64 && block_k != 128) return SAGE_ERR_UNSUPPORTED;
+    if (block_k != 1 && block_k != 64 && block_k != 128) return SAGE_ERR_UNSUPPORTED;
     if (!std::isfinite(sm_scale) || !(sm_scale > 0.0f)) return SAGE_ERR_VALUE;
     if (!aligned(q_i8, 16) || !aligned(k_i8, 16) || !aligned(v_f16, 16) || !aligned(o_f16, 16) ||
         !aligned(q_scale, 4) || !aligned(k_scale, 4))

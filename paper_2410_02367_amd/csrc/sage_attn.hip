@@ -76,6 +76,7 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 typedef _Float16 v4h __attribute__((ext_vector_type(4)));
+typedef float v4f __attribute__((ext_vector_type(4)));
 typedef short v4s __attribute__((ext_vector_type(4)));
 
 #define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
@@ -153,7 +154,14 @@ __device__ __forceinline__ void refresh(v16f& acc) { asm volatile("s_nop 11" : "
 // Makes a value opaque and resident in the accumulator file.
 template <class T> __device__ __forceinline__ void pin_a(T& x) { asm volatile("" : "+a"(x)); }
 
-template <int D, int NW, bool CAUSAL, bool DUMP>
+// KTOK: one scale per key token (Section 3.2's per-token quantizer, the SAGEAttn-T kernel of
+// Section 4.5) instead of one per block of keys.  A lane's 32 scores of a tile then belong to 32
+// different scales, so the dequantization cannot be folded into the softmax FMA: wavefront 0
+// stages, per tile, a_k = delta_K[k] and b_k = -12582912 * a_k in LDS, every wavefront turns its
+// raw scores into t = S^ * delta_K[k] = fma(seeded score, a_k, b_k) while it takes the row maximum
+// (now a floating-point maximum), and the softmax FMA becomes t * (delta_Q log2 e) - m.  One
+// scale per QUERY token costs nothing in either variant: a lane owns one query.
+template <int D, int NW, bool CAUSAL, bool DUMP, bool KTOK>
 __global__ void __launch_bounds__(NW * 64, NW == 4 && SAGE_QS == 1 ? 2 : 1)
 sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
                  const int8_t* __restrict__ ki, const float* __restrict__ ksc,
@@ -173,7 +181,9 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
     // load instructions per wavefront and tile (the last may cover only the first wavefronts)
     constexpr int KL = (KVEC + NTHREADS - 1) / NTHREADS, VL = (VVEC + NTHREADS - 1) / NTHREADS;
     constexpr int KCH = KROW / 16, VCH = VROW / 16;             // chunks per row
-    __shared__ __attribute__((aligned(1024))) unsigned char lds[2 * KB + 2 * VB];
+    static_assert(!(KTOK && DUMP), "the score dump has no scales");
+    constexpr int KSL = KTOK ? 2 * 2 * KTILE * 4 : 0;           // per-key (a, b) factors, two tiles
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[2 * KB + 2 * VB + KSL];
 
     // Workgroup -> (slab, query tile).  Consecutive workgroup ids land on the 8 XCDs in turn; give
     // each XCD a contiguous range of the (slab-major, heaviest-query-tile-first) order so that the
@@ -205,7 +215,7 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
         }
         dq[qs] = 0.0f;
         if (!DUMP) {
-            const int r0 = qrow0 + 32 * qs, rc = r0 < N ? r0 : N - 1;
+            const int rc = q_row < N ? q_row : N - 1;             // the lane's own query: any block_q down to 1
             dq[qs] = qsc[(size_t)bh * nbq + (rc >> shift_q)] * LOG2E;
         }
     }
@@ -314,7 +324,9 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
     v16i acc_s[QS][2];       // S^T of the current tile, two 32-key halves per sub-tile (raw int32 + seed)
     v4i pk[QS][2][2];        // P~^T as FP16 pairs: [sub-tile][32-key half][16-key group]
     float m_run[QS], sc[QS], bias[QS], m_cand[QS];
+    float seed_sc[QS];       // 12582912 * sc, exact (sc carries 22 significant bits)
     int pmax[QS][DT];        // partial integer row maxima of the current tile
+    float pmaxf[QS][DT];     // ... floating-point ones when every key has its own scale
 #pragma unroll
     for (int qs = 0; qs < QS; ++qs) {
 #pragma unroll
@@ -322,13 +334,37 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
 #pragma unroll
             for (int b = 0; b < 2; ++b) pk[qs][a][b] = (v4i){0, 0, 0, 0};
         m_run[qs] = -__builtin_inff();
-        sc[qs] = 0.0f; bias[qs] = 0.0f; m_cand[qs] = 0.0f;
+        sc[qs] = 0.0f; bias[qs] = 0.0f; m_cand[qs] = 0.0f; seed_sc[qs] = 0.0f;
     }
     v16i magic;
 #pragma unroll
     for (int r = 0; r < 16; ++r) magic[r] = MAGIC_I;
     asm volatile("" : "+v"(magic));      // keep it resident: re-materializing costs 16 moves per sub-tile
-    float dk_next = DUMP ? 0.0f : ksc_bh[0];
+    float dk_next = (DUMP || KTOK) ? 0.0f : ksc_bh[0];
+    // KTOK: wavefront 0 carries the scale of key (tile j, lane) from the load in slot j-1 to the
+    // LDS write before barrier j.
+    float dk_tok = 0.0f;
+    float* const ksl = (float*)(lds + 2 * KB + 2 * VB);          // [tile parity][a | b][key]
+    auto request_key_scales = [&](int j) {
+        if constexpr (KTOK) {
+            if (wave == 0) {
+                const int key = j * KTILE + lane;
+                dk_tok = ksc_bh[key < N ? key : N - 1];
+            }
+        }
+    };
+    auto publish_key_scales = [&](int j) {
+        if constexpr (KTOK) {
+            if (wave == 0) {
+                // a zero scale (all-zero token) would turn -inf * scale into NaN for hidden keys
+                // 22 significant bits, so that 12582912 * a = 3 * 2^22 * a is exact and the fma
+                // below returns S^ * a rounded once
+                const float a = as_f32(as_i32(__builtin_fmaxf(dk_tok, 1e-30f)) & ~3);
+                ksl[(j & 1) * 2 * KTILE + lane] = a;
+                ksl[(j & 1) * 2 * KTILE + KTILE + lane] = -MAGIC_F * a;
+            }
+        }
+    };
 
     // 12 wait states between the matrix instructions that wrote the scores and the first VALU or
     // memory instruction that touches them; the operands tie every later use to the fence.
@@ -387,8 +423,9 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
     auto begin_tile = [&](int j) {
         const int kv0 = j * KTILE;
         score_tie();
-        const float dk = dk_next;                      // loaded one step ahead
-        {
+        float dk = 1.0f;
+        if constexpr (!KTOK) {
+            dk = dk_next;                              // loaded one step ahead
             const int jn = j + 1 < kv_tiles_all ? j + 1 : j;
             dk_next = ksc_bh[(jn * KTILE) >> shift_k];
         }
@@ -397,6 +434,15 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
         for (int qs = 0; qs < QS; ++qs) {
             // a zero scale (all-zero quantization block) would turn -inf * scale into NaN
             sc[qs] = __builtin_fmaxf(dq[qs] * dk, 1e-30f);
+            if constexpr (!KTOK) {
+                // The exp2 argument is fma(seeded score, sc, bias) with bias = -(12582912 * sc + m):
+                // it equals S^ * sc - m rounded ONCE only if that bias is exact.  The product is
+                // exact once sc is cut to 22 significant bits (a relative change of 2^-22 in the
+                // scale); the sum is exact when m is a multiple of the product's ulp, which
+                // finish_max() checks and raise_maximum() establishes.
+                sc[qs] = as_f32(as_i32(sc[qs]) & ~3);
+                seed_sc[qs] = MAGIC_F * sc[qs];
+            }
             if (need_mask) {
                 const int q_row = qrow0 + 32 * qs + ql;
 #pragma unroll
@@ -412,9 +458,30 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
     };
     // partial_max(qs, p): integer maximum over part p (of DT) of sub-tile qs's 32 scores per lane;
     // issued between the matrix instructions of the step's first slot.
-    auto partial_max = [&](auto QSI, auto P) {
+    auto partial_max = [&](auto QSI, auto P, int j) {
         constexpr int qs = IDX(QSI), p = IDX(P);
         constexpr int CNT = 32 / DT, FIRST = p * CNT;              // flat index = 16*s + r
+        if constexpr (KTOK) {
+            // registers 4*q4 .. +3 of sub-tile s are keys 32*s + 8*q4 + 4*g .. +3: one 16-byte
+            // read each of a and b; the scores are replaced by t = S^ * delta_K[key]
+            const float* kf = ksl + (j & 1) * 2 * KTILE + 4 * g;
+            float mf = -__builtin_inff();
+#pragma unroll
+            for (int f = FIRST; f < FIRST + CNT; f += 4) {
+                const int s_ = f >> 4, r = f & 15;
+                const v4f a = *(const v4f*)(kf + 32 * s_ + 2 * r), b = *(const v4f*)(kf + KTILE + 32 * s_ + 2 * r);
+                float tv[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    tv[e] = __builtin_fmaf(as_f32(acc_s[qs][s_][r + e]), a[e], b[e]);
+                    acc_s[qs][s_][r + e] = as_i32(tv[e]);
+                }
+                mf = __builtin_fmaxf(__builtin_fmaxf(mf, tv[0]), tv[1]);
+                mf = __builtin_fmaxf(__builtin_fmaxf(mf, tv[2]), tv[3]);
+            }
+            pmaxf[qs][p] = mf;
+            return;
+        }
         auto val = [&](int f) { return acc_s[qs][f >> 4][f & 15]; };
         int mi = val(FIRST);
 #pragma unroll
@@ -427,11 +494,23 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
         bool want = false;
 #pragma unroll
         for (int qs = 0; qs < QS; ++qs) {
-            int mi = pmax[qs][0];
+            if constexpr (KTOK) {
+                float mf = pmaxf[qs][0];
 #pragma unroll
-            for (int p = 1; p < DT; ++p) mi = max(mi, pmax[qs][p]);
-            mi = max(mi, swap32i(mi));
-            m_cand[qs] = (mi < 0) ? -__builtin_inff() : (as_f32(mi) - MAGIC_F) * sc[qs];
+                for (int p = 1; p < DT; ++p) mf = __builtin_fmaxf(mf, pmaxf[qs][p]);
+                mf = __builtin_fmaxf(mf, as_f32(swap32i(as_i32(mf))));
+                m_cand[qs] = mf * sc[qs];               // -inf stays -inf: sc > 0
+            } else {
+                int mi = pmax[qs][0];
+#pragma unroll
+                for (int p = 1; p < DT; ++p) mi = max(mi, pmax[qs][p]);
+                mi = max(mi, swap32i(mi));
+                m_cand[qs] = (mi < 0) ? -__builtin_inff() : (as_f32(mi) - MAGIC_F) * sc[qs];
+                // the maximum that this tile's bias would really subtract; it differs from m_run
+                // when m_run is not on the grid of this tile's (larger) scale
+                const float m_eff = (seed_sc[qs] + m_run[qs]) - seed_sc[qs];
+                want = want || (m_eff != m_run[qs]);
+            }
             want = want || (m_cand[qs] > m_run[qs] + MAX_SLACK);
         }
         return __builtin_amdgcn_ballot_w64(want) != 0ull;
@@ -447,7 +526,8 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
         }
 #pragma unroll
         for (int qs = 0; qs < QS; ++qs) {
-            const float m_new = __builtin_fmaxf(m_run[qs], m_cand[qs]);
+            float m_new = __builtin_fmaxf(m_run[qs], m_cand[qs]);
+            if constexpr (!KTOK) m_new = (seed_sc[qs] + m_new) - seed_sc[qs];    // onto the grid on which the bias is exact
             const float alpha = __builtin_amdgcn_exp2f(m_run[qs] - m_new);
             m_run[qs] = m_new;
 #pragma unroll
@@ -474,7 +554,8 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
     };
     auto set_bias = [&]() {
 #pragma unroll
-        for (int qs = 0; qs < QS; ++qs) bias[qs] = -__builtin_fmaf(MAGIC_F, sc[qs], m_run[qs]);   // exp2 argument = acc*sc + bias
+        for (int qs = 0; qs < QS; ++qs)       // exp2 argument = acc*sc + bias
+            bias[qs] = KTOK ? -m_run[qs] : -(seed_sc[qs] + m_run[qs]);
     };
 
     // ---- one pipeline step: softmax of tile j (scores in acc_s), P~V of tile j-1, K^Q^^T of tile
@@ -567,7 +648,7 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
             load_operand(std::integral_constant<int, o + PD>{}, vbuf, kbuf);
             static_for<QS>([&](auto QSI) {
                 issue_mfma(O, QSI);
-                partial_max(QSI, O);
+                partial_max(QSI, O, j);
                 __builtin_amdgcn_sched_barrier(0);
             });
         });
@@ -619,6 +700,7 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
     }
     load_k(0, 0);
     if (T > 1) load_k(1, 1);
+    request_key_scales(0);
     tiles_ready_barrier();
     qk_half(0, std::integral_constant<int, 0>{});
     qk_half(0, std::integral_constant<int, 1>{});
@@ -629,9 +711,12 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
     // to arrive.  Slot j reads V(j-1) and K^(j+1).  Every wavefront passes T+1 barriers after the
     // prologue's.
     auto turn = [&](int j) {
-        tiles_ready_barrier();
+        __builtin_amdgcn_s_waitcnt(0x0F70);     // own loads landed: vmcnt(0), no wait on the other counters
+        if (j < T) publish_key_scales(j);
+        __syncthreads();
         if (j < T) load_v(j, j & 1);
         if (j + 2 < T) load_k(j + 2, j & 1);
+        if (j + 1 < T) request_key_scales(j + 1);
     };
     int j = 0;
     if (DUMP) {
@@ -710,12 +795,14 @@ static hipError_t launch_dn(const int8_t* qq, const float* qscale, const int8_t*
     const int shift_q = __builtin_ctz((unsigned)block_q), shift_k = __builtin_ctz((unsigned)block_k);
     const _Float16* vp = (const _Float16*)v;
     _Float16* op = (_Float16*)o;
-    if (sdump)
-        sage_attn_kernel<D, NW, false, true><<<grid, NTHREADS, 0, st>>>(qq, qscale, kq, kscale, vp, op, sdump, N, shift_q, shift_k, tiles_q, per_xcd, total);
-    else if (causal)
-        sage_attn_kernel<D, NW, true, false><<<grid, NTHREADS, 0, st>>>(qq, qscale, kq, kscale, vp, op, sdump, N, shift_q, shift_k, tiles_q, per_xcd, total);
-    else
-        sage_attn_kernel<D, NW, false, false><<<grid, NTHREADS, 0, st>>>(qq, qscale, kq, kscale, vp, op, sdump, N, shift_q, shift_k, tiles_q, per_xcd, total);
+    const bool ktok = block_k == 1;
+#define SAGE_LAUNCH(C, DMP, KT) sage_attn_kernel<D, NW, C, DMP, KT><<<grid, NTHREADS, 0, st>>>(qq, qscale, kq, kscale, vp, op, sdump, N, shift_q, shift_k, tiles_q, per_xcd, total)
+    if (sdump) SAGE_LAUNCH(false, true, false);
+    else if (causal && ktok) SAGE_LAUNCH(true, false, true);
+    else if (causal) SAGE_LAUNCH(true, false, false);
+    else if (ktok) SAGE_LAUNCH(false, false, true);
+    else SAGE_LAUNCH(false, false, false);
+#undef SAGE_LAUNCH
     return hipGetLastError();
 }
 

@@ -144,11 +144,86 @@ __global__ void __launch_bounds__(256) quant_block_kernel(const _Float16* __rest
     }
 }
 
+// Per-token quantizer (Section 3.2): one scale per token row.  D/8 adjacent lanes own a row
+// (16 bytes each); the row's absmax is a butterfly over those lanes.  A workgroup covers
+// TOK_ROWS consecutive tokens, TOK_LPT rows per thread, all loads issued before the first use.
+constexpr int TOK_LPT = 8;
+template <int D, bool IS_K>
+__global__ void __launch_bounds__(256) quant_token_kernel(const _Float16* __restrict__ x,
+                                                          int8_t* __restrict__ xq,
+                                                          float* __restrict__ scale,
+                                                          float* __restrict__ k_mean,
+                                                          const long long* __restrict__ sums,
+                                                          int N, float sm_scale) {
+    constexpr int VPR = D / 8;
+    constexpr int RSTEP = 256 / VPR;
+    constexpr int ROWS = RSTEP * TOK_LPT;
+    const int t = threadIdx.x, c8 = t % VPR, rbase = t / VPR;
+    const int bh = blockIdx.y;
+    const int row0 = blockIdx.x * ROWS;
+
+    __shared__ float s_mean[D];
+    float mean[8];
+    if (IS_K) {
+        if (t < D) {
+            long long s = sums[(size_t)bh * D + t];
+            double avg = (double)s / (double)N;
+            float m = (float)(avg * 0x1p-24);
+            s_mean[t] = m;
+            if (blockIdx.x == 0) k_mean[(size_t)bh * D + t] = m;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int e = 0; e < 8; ++e) mean[e] = s_mean[c8 * 8 + e];
+    }
+
+    const size_t slab = ((size_t)bh * N + row0) * D + c8 * 8;
+    h8 raw[TOK_LPT];
+#pragma unroll
+    for (int i = 0; i < TOK_LPT; ++i) {
+        int r = rbase + i * RSTEP;
+        raw[i] = (h8){0, 0, 0, 0, 0, 0, 0, 0};
+        if (row0 + r < N) raw[i] = *(const h8*)(x + slab + (size_t)r * D);
+    }
+#pragma unroll
+    for (int i = 0; i < TOK_LPT; ++i) {
+        const int r = rbase + i * RSTEP;
+        float f[8];
+        float amax = 0.0f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            f[e] = (float)raw[i][e];
+            f[e] = IS_K ? (f[e] - mean[e]) : (f[e] * sm_scale);
+            amax = __builtin_fmaxf(amax, __builtin_fabsf(f[e]));
+        }
+#pragma unroll
+        for (int off = VPR / 2; off >= 1; off >>= 1) amax = __builtin_fmaxf(amax, __shfl_xor(amax, off, 64));
+        const float delta = amax / 127.0f;
+        const float rcp = amax > 0.0f ? 127.0f / amax : 0.0f;
+        if (row0 + r < N) {
+            if (c8 == 0) scale[(size_t)bh * N + row0 + r] = delta;
+            unsigned w[2] = {0u, 0u};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                float q = __builtin_rintf(f[e] * rcp);                 // round half to even
+                q = __builtin_fminf(__builtin_fmaxf(q, -127.0f), 127.0f);
+                w[e >> 2] |= ((unsigned)((int)q) & 0xffu) << (8 * (e & 3));
+            }
+            *(uint2*)(xq + slab + (size_t)r * D) = make_uint2(w[0], w[1]);
+        }
+    }
+}
+
 template <int D, bool IS_K>
 static hipError_t launch_quant(const void* x, int8_t* xq, float* scale, float* mean, const long long* sums,
                                int BH, int N, int block, float sm_scale, hipStream_t st) {
-    dim3 grid((N + block - 1) / block, BH);
     const _Float16* xp = (const _Float16*)x;
+    if (block == 1) {
+        constexpr int ROWS = (256 / (D / 8)) * TOK_LPT;
+        quant_token_kernel<D, IS_K><<<dim3((N + ROWS - 1) / ROWS, BH), 256, 0, st>>>(xp, xq, scale, mean, sums, N, sm_scale);
+        return hipGetLastError();
+    }
+    dim3 grid((N + block - 1) / block, BH);
     switch (block * D / 2048) {
         case 1: quant_block_kernel<D, 1, IS_K><<<grid, 256, 0, st>>>(xp, xq, scale, mean, sums, N, block, sm_scale); break;
         case 2: quant_block_kernel<D, 2, IS_K><<<grid, 256, 0, st>>>(xp, xq, scale, mean, sums, N, block, sm_scale); break;

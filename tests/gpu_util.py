@@ -19,6 +19,20 @@ def bits(a: np.ndarray) -> np.ndarray:
     return np.ascontiguousarray(a).view(np.uint32 if a.dtype == np.float32 else np.uint16)
 
 
+def with_token_outliers(w, gain=12.0, frac=0.03):
+    """The workload's tensors with a few Q and K tokens scaled up.  Their blocks get large scales,
+    the other tokens of those blocks small integer codes: one unit of an integer score is then a
+    large step of the softmax argument, which any shortcut in the dequantization must survive."""
+    import sage_inputs as si
+    q, k, v = si.full(w)
+    g = np.random.default_rng(w.seed + 1000)
+    q = q.copy(); k = k.copy()
+    for x in (q, k):
+        hit = g.random(x.shape[:3]) < frac
+        x[hit] = (x[hit].astype(np.float32) * gain).astype(np.float16)
+    return q, k, v
+
+
 def gpu_prepass(q, k, sm_scale, block_q, block_k):
     qd, kd = to_dev(q), to_dev(k)
     k_i8, k_scale, k_mean = sage.sage_smooth_quant_k(kd, block_k)

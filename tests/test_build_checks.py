@@ -3,8 +3,9 @@ assembly that updates accumulator registers behind the compiler's back).  These 
 kind of violation in a small fake assembly text and make sure the checker objects; no GPU needed."""
 from paper_2410_02367_amd.build import check_attention_asm
 
-KERNELS = ["_ZN4sage16sage_attn_kernelILi%dELi%dELb%dELb%dEEEvPKa" % (d, nw, c, dump)
-           for d in (64, 128) for nw in (4, 8) for c, dump in ((0, 1), (1, 0), (0, 0))]
+KERNELS = ["_ZN4sage16sage_attn_kernelILi%dELi%dELb%dELb%dELb%dEEEvPKa" % (d, nw, c, dump, ktok)
+           for d in (64, 128) for nw in (4, 8)
+           for c, dump, ktok in ((0, 1, 0), (1, 0, 0), (0, 0, 0), (1, 0, 1), (0, 0, 1))]
 
 
 def fake(body_of_first: str) -> str:
@@ -38,7 +39,7 @@ def test_clean_text_passes():
 
 def test_missing_kernel_is_reported():
     text = fake(CLEAN).split(KERNELS[-1])[0]
-    assert any("expected 12" in p for p in check_attention_asm(text))
+    assert any("expected 20" in p for p in check_attention_asm(text))
 
 
 def test_accumulator_copy_after_first_matrix_instruction_is_reported():

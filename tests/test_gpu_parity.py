@@ -9,7 +9,7 @@ import torch
 import oracle
 import paper_2410_02367_amd as sage
 import sage_inputs as si
-from gpu_util import ABS_TOL, assert_output_close, assert_prepass_bit_exact, bits, to_dev
+from gpu_util import ABS_TOL, assert_output_close, assert_prepass_bit_exact, bits, to_dev, with_token_outliers
 
 pytestmark = pytest.mark.gpu
 
@@ -88,6 +88,25 @@ def test_scores_that_keep_rising_force_a_rescale_at_every_tile(D, causal):
     # the construction does what it says: the last tile's scores exceed the first tile's by far
     s = oracle.qk_i32(qq[0, 0], kq[0, 0])[N - 1].astype(np.float64) * qs[0, 0, -1] * np.repeat(ks[0, 0], 64)[:N]
     assert s[-64:].max() - s[:64].max() > 100.0
+
+
+@pytest.mark.parametrize("D,causal,bq,bk", [(128, True, 128, 64), (64, False, 128, 64), (128, False, 64, 128)])
+def test_outlier_tokens_make_coarse_integer_scores_and_the_softmax_stays_exact(D, causal, bq, bk):
+    """A few tokens 12x larger than the rest: the other tokens of their blocks get small codes, the
+    product of the two scales is large, and one unit of S^ is a visible step of the softmax
+    argument.  The kernel folds dequantization, the fp32 seed of the integer accumulator and the
+    running maximum into one fma; that is only as exact as the oracle's two multiplications if the
+    folded constant is exact."""
+    print(f"[case] outlier tokens D{D} causal={causal} blocks {bq}x{bk}", flush=True)
+    w = si.custom("outlier_tokens_b", 1, 2, 900, D, causal, bq, bk, seed=si.BASE_SEED + 60 + D)
+    q, k, v = with_token_outliers(w)
+    (q_i8, q_scale, k_i8, k_scale, k_mean), (qq, qs, kq, ks, km) = assert_prepass_bit_exact(q, k, w.sm_scale, bq, bk)
+    o_gpu = sage.sage_attn_fwd(q_i8, q_scale, k_i8, k_scale, to_dev(v), causal, w.sm_scale, bq, bk)
+    torch.cuda.synchronize()
+    o_ref = oracle.attn_l2(qq, qs, kq, ks, v, causal, bq, bk)
+    assert_output_close(o_gpu.cpu().numpy(), o_ref, w.name)
+    # the regime is the intended one: the largest product of scales is far above the usual 1e-4
+    assert float(qs.max()) * float(ks.max()) > 0.02
 
 
 def test_results_are_deterministic_run_to_run():
