@@ -92,6 +92,18 @@ def scale_q(q: np.ndarray, sm_scale: float) -> np.ndarray:
     return out
 
 
+def rope(x: np.ndarray, cos: np.ndarray, sin: np.ndarray) -> np.ndarray:
+    """Rotate-half RoPE of fp16 x [..., N, D] with fp32 tables cos, sin [N, D/2] -> fp16 (Section 4.6's producer)."""
+    x = _f16(x); N, D = x.shape[-2:]
+    cos = np.ascontiguousarray(cos, np.float32); sin = np.ascontiguousarray(sin, np.float32)
+    assert D % 2 == 0 and cos.shape == (N, D // 2) and sin.shape == (N, D // 2)
+    y = np.empty_like(x)
+    xs, ys = x.reshape(-1, N, D), y.reshape(-1, N, D)
+    for i in range(xs.shape[0]):
+        _L().sage_oracle_rope(_p(xs[i]), _p(cos), _p(sin), ctypes.c_int(N), ctypes.c_int(D), _p(ys[i]))
+    return y
+
+
 def quant_per_block(x: np.ndarray, block: int, flags: int = 0):
     """Per-block INT8 quantizer psi of Section 3.2 on an fp32 [N, D] matrix -> (x_i8, delta)."""
     x = np.ascontiguousarray(x, np.float32); N, D = x.shape

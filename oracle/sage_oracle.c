@@ -129,6 +129,29 @@ void sage_oracle_scale_q(const uint16_t* q, float sm_scale, int N, int D, float*
     }
 }
 
+/* ------------------------------------------------------------------ Section 4.6: RoPE ahead of the quantizer */
+
+/* Rotary position embedding of one slab x[N,D] (fp16), the operator Section 4.6 fuses the
+ * quantizer into.  The paper only names it; the form taken here is the "rotate-half" one of the
+ * Llama-family models it evaluates: channel c < D/2 is paired with channel c + D/2,
+ *     y[t,c]       = x[t,c] cos[t,c] - x[t,c+D/2] sin[t,c]
+ *     y[t,c+D/2]   = x[t,c+D/2] cos[t,c] + x[t,c] sin[t,c]
+ * with the tables cos, sin [N, D/2] (fp32) given by the caller.  Each product and the sum are
+ * rounded to fp32, and y is rounded to fp16: it is the tensor the unfused model hands to the
+ * attention layer, so quantizing it "before it is written" gives what the unfused path gives. */
+void sage_oracle_rope(const uint16_t* x, const float* cs, const float* sn, int N, int D, uint16_t* y) {
+    int half = D / 2;
+    for (int t = 0; t < N; ++t)
+        for (int c = 0; c < half; ++c) {
+            float a = f16_to_f32(x[(int64_t)t * D + c]), b = f16_to_f32(x[(int64_t)t * D + c + half]);
+            float co = cs[(int64_t)t * half + c], si = sn[(int64_t)t * half + c];
+            volatile float ac = a * co, bs = b * si, bc = b * co, as = a * si;
+            volatile float lo = ac - bs, hi = bc + as;
+            y[(int64_t)t * D + c] = f32_to_f16(lo, 0);
+            y[(int64_t)t * D + c + half] = f32_to_f16(hi, 0);
+        }
+}
+
 /* ------------------------------------------------------------------ Section 3.2: per-block quantizer psi */
 
 /* x[N,D] fp32 -> xq[N,D] int8 and delta[ceil(N/block)]: one scale for every `block`
