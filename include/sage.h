@@ -92,6 +92,28 @@ int sage_smooth_quant_k(const void* k_f16, int8_t* k_i8, float* k_scale, float* 
                         int B, int H, int N, int D, int block_k, void* stream);
 
 /*
+ * The two pre-pass calls with the rotary position embedding applied on the fly -- Section 4.6
+ * ("Fusion Tricks"): the quantizer is fused into the operator that produces Q and K, so that the
+ * rotated fp16 tensors are never written to or re-read from memory.  The paper names RoPE without
+ * defining it; this is the rotate-half form: channel c < D/2 is paired with channel c + D/2,
+ *     y[t,c] = x[t,c] cos[t,c] - x[t,c+D/2] sin[t,c],   y[t,c+D/2] = x[t,c+D/2] cos[t,c] + x[t,c] sin[t,c],
+ * products and sum rounded to fp32, y rounded to fp16 (round to nearest even) -- exactly the
+ * tensor a separate RoPE kernel would store -- and then everything as in sage_quant_q /
+ * sage_smooth_quant_k on y (the K mean is the mean of the rotated K).  The results are therefore
+ * bit-identical to the unfused sequence.
+ *   rope_cos, rope_sin  in  [N, D/2] fp32, row t = position of token t, shared by all (batch,
+ *                       head) slabs; 16-byte aligned; required
+ * All other arguments, limits and error codes as in the unfused calls.
+ */
+int sage_rope_quant_q(const void* q_f16, const float* rope_cos, const float* rope_sin,
+                      int8_t* q_i8, float* q_scale,
+                      int B, int H, int N, int D, float sm_scale, int block_q, void* stream);
+int sage_rope_smooth_quant_k(const void* k_f16, const float* rope_cos, const float* rope_sin,
+                             int8_t* k_i8, float* k_scale, float* k_mean,
+                             void* workspace, size_t workspace_bytes,
+                             int B, int H, int N, int D, int block_k, void* stream);
+
+/*
  * The loop of Algorithm 1 (with Section 3.1's online softmax and Section 4.4's FP16 P~ V, here
  * accumulated in fp32 because gfx950's FP16 matrix instructions accumulate in fp32).
  *   q_i8, q_scale   from sage_quant_q (same block_q)

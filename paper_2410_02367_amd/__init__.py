@@ -11,6 +11,8 @@ from .binding import (  # noqa: F401
     sage_attn_fwd,
     sage_attn_qk_i32_debug,
     sage_quant_q,
+    sage_rope_quant_q,
+    sage_rope_smooth_quant_k,
     sage_smooth_quant_k,
     sage_smooth_quant_k_workspace,
     sage_status_string,

@@ -11,7 +11,8 @@ _LIB_PATH = os.path.join(_HERE, "libsage.so")
 _lib = None
 
 EXPORTS = ("sage_status_string", "sage_quant_q", "sage_smooth_quant_k_workspace",
-           "sage_smooth_quant_k", "sage_attn_fwd", "sage_attn_qk_i32_debug")
+           "sage_smooth_quant_k", "sage_rope_quant_q", "sage_rope_smooth_quant_k",
+           "sage_attn_fwd", "sage_attn_qk_i32_debug")
 
 
 class SageError(RuntimeError):
@@ -43,6 +44,12 @@ def load() -> ctypes.CDLL:
     lib.sage_smooth_quant_k.restype = c_int
     lib.sage_smooth_quant_k.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t,
                                         c_int, c_int, c_int, c_int, c_int, c_void_p]
+    lib.sage_rope_quant_q.restype = c_int
+    lib.sage_rope_quant_q.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                      c_int, c_int, c_int, c_int, c_float, c_int, c_void_p]
+    lib.sage_rope_smooth_quant_k.restype = c_int
+    lib.sage_rope_smooth_quant_k.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                             c_size_t, c_int, c_int, c_int, c_int, c_int, c_void_p]
     lib.sage_attn_fwd.restype = c_int
     lib.sage_attn_fwd.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                   c_int, c_int, c_int, c_int, c_int, c_float, c_int, c_int, c_void_p]
@@ -70,6 +77,54 @@ def _dev(t: torch.Tensor, dtype, name: str) -> int:
 
 def _nblk(N: int, block: int) -> int:
     return (N + block - 1) // block
+
+
+def _rope_tables(cos, sin, N: int, D: int):
+    for name, t in (("rope_cos", cos), ("rope_sin", sin)):
+        if tuple(t.shape) != (N, D // 2):
+            raise ValueError(f"{name}: expected shape ({N}, {D // 2}), got {tuple(t.shape)}")
+    return _dev(cos, torch.float32, "rope_cos"), _dev(sin, torch.float32, "rope_sin")
+
+
+def sage_rope_quant_q(q: torch.Tensor, rope_cos, rope_sin, sm_scale: float, block_q: int = 128,
+                      q_i8=None, q_scale=None, stream=None):
+    """sage_quant_q on RoPE(Q), the rotation applied on the fly (tables [N, D/2] fp32)."""
+    B, H, N, D = q.shape
+    pc, ps = _rope_tables(rope_cos, rope_sin, N, D)
+    if q_i8 is None:
+        q_i8 = torch.empty((B, H, N, D), dtype=torch.int8, device=q.device)
+    if q_scale is None:
+        q_scale = torch.empty((B, H, _nblk(N, block_q)), dtype=torch.float32, device=q.device)
+    st = load().sage_rope_quant_q(_dev(q, torch.float16, "q"), pc, ps, _dev(q_i8, torch.int8, "q_i8"),
+                                  _dev(q_scale, torch.float32, "q_scale"), B, H, N, D, float(sm_scale),
+                                  int(block_q), _stream(stream))
+    if st != 0:
+        raise SageError(st, "sage_rope_quant_q")
+    return q_i8, q_scale
+
+
+def sage_rope_smooth_quant_k(k: torch.Tensor, rope_cos, rope_sin, block_k: int = 64, k_i8=None, k_scale=None,
+                             k_mean=None, workspace=None, stream=None):
+    """sage_smooth_quant_k on RoPE(K), the rotation applied on the fly (tables [N, D/2] fp32)."""
+    B, H, N, D = k.shape
+    pc, ps = _rope_tables(rope_cos, rope_sin, N, D)
+    if k_i8 is None:
+        k_i8 = torch.empty((B, H, N, D), dtype=torch.int8, device=k.device)
+    if k_scale is None:
+        k_scale = torch.empty((B, H, _nblk(N, block_k)), dtype=torch.float32, device=k.device)
+    if k_mean is None:
+        k_mean = torch.empty((B, H, D), dtype=torch.float32, device=k.device)
+    need = sage_smooth_quant_k_workspace(B, H, N, D)
+    if workspace is None:
+        workspace = torch.empty((max(need, 8) + 7) // 8, dtype=torch.int64, device=k.device)
+    ws_bytes = workspace.numel() * workspace.element_size()
+    st = load().sage_rope_smooth_quant_k(_dev(k, torch.float16, "k"), pc, ps, _dev(k_i8, torch.int8, "k_i8"),
+                                         _dev(k_scale, torch.float32, "k_scale"),
+                                         _dev(k_mean, torch.float32, "k_mean"), workspace.data_ptr(), ws_bytes,
+                                         B, H, N, D, int(block_k), _stream(stream))
+    if st != 0:
+        raise SageError(st, "sage_rope_smooth_quant_k")
+    return k_i8, k_scale, k_mean
 
 
 def sage_quant_q(q: torch.Tensor, sm_scale: float, block_q: int = 128, q_i8=None, q_scale=None, stream=None):

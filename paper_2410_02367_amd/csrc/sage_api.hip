@@ -39,15 +39,46 @@ const char* sage_status_string(int status) {
     }
 }
 
-int sage_quant_q(const void* q_f16, int8_t* q_i8, float* q_scale,
+namespace {
+int quant_q_impl(const void* q_f16, const float* cs, const float* sn, bool rope, int8_t* q_i8, float* q_scale,
                  int B, int H, int N, int D, float sm_scale, int block_q, void* stream) {
-    if (!q_f16 || !q_i8 || !q_scale) return SAGE_ERR_NULL;
+    if (!q_f16 || !q_i8 || !q_scale || (rope && (!cs || !sn))) return SAGE_ERR_NULL;
     if (int e = check_shape(B, H, N, D)) return e;
     if (!quant_block_ok(block_q)) return SAGE_ERR_UNSUPPORTED;
     if (!std::isfinite(sm_scale) || !(sm_scale > 0.0f)) return SAGE_ERR_VALUE;
     if (!aligned(q_f16, 16) || !aligned(q_i8, 16) || !aligned(q_scale, 4)) return SAGE_ERR_ALIGN;
-    hipError_t e = sage::launch_quant_q(q_f16, q_i8, q_scale, B * H, N, D, sm_scale, block_q, (hipStream_t)stream);
+    if (rope && (!aligned(cs, 16) || !aligned(sn, 16))) return SAGE_ERR_ALIGN;
+    hipError_t e = sage::launch_quant_q(q_f16, q_i8, q_scale, B * H, N, D, sm_scale, block_q,
+                                        rope ? cs : nullptr, rope ? sn : nullptr, (hipStream_t)stream);
     return e == hipSuccess ? SAGE_OK : SAGE_ERR_LAUNCH;
+}
+
+int smooth_quant_k_impl(const void* k_f16, const float* cs, const float* sn, bool rope, int8_t* k_i8,
+                        float* k_scale, float* k_mean, void* workspace, size_t workspace_bytes,
+                        int B, int H, int N, int D, int block_k, void* stream) {
+    if (!k_f16 || !k_i8 || !k_scale || !k_mean || !workspace || (rope && (!cs || !sn))) return SAGE_ERR_NULL;
+    if (int e = check_shape(B, H, N, D)) return e;
+    if (!quant_block_ok(block_k)) return SAGE_ERR_UNSUPPORTED;
+    if (workspace_bytes < sage_smooth_quant_k_workspace(B, H, N, D)) return SAGE_ERR_WORKSPACE;
+    if (!aligned(k_f16, 16) || !aligned(k_i8, 16) || !aligned(k_scale, 4) || !aligned(k_mean, 4) ||
+        !aligned(workspace, 8))
+        return SAGE_ERR_ALIGN;
+    if (rope && (!aligned(cs, 16) || !aligned(sn, 16))) return SAGE_ERR_ALIGN;
+    hipError_t e = sage::launch_smooth_quant_k(k_f16, k_i8, k_scale, k_mean, (long long*)workspace,
+                                               B * H, N, D, block_k, rope ? cs : nullptr, rope ? sn : nullptr,
+                                               (hipStream_t)stream);
+    return e == hipSuccess ? SAGE_OK : SAGE_ERR_LAUNCH;
+}
+}  // namespace
+
+int sage_quant_q(const void* q_f16, int8_t* q_i8, float* q_scale,
+                 int B, int H, int N, int D, float sm_scale, int block_q, void* stream) {
+    return quant_q_impl(q_f16, nullptr, nullptr, false, q_i8, q_scale, B, H, N, D, sm_scale, block_q, stream);
+}
+
+int sage_rope_quant_q(const void* q_f16, const float* rope_cos, const float* rope_sin, int8_t* q_i8, float* q_scale,
+                      int B, int H, int N, int D, float sm_scale, int block_q, void* stream) {
+    return quant_q_impl(q_f16, rope_cos, rope_sin, true, q_i8, q_scale, B, H, N, D, sm_scale, block_q, stream);
 }
 
 size_t sage_smooth_quant_k_workspace(int B, int H, int N, int D) {
@@ -59,16 +90,16 @@ size_t sage_smooth_quant_k_workspace(int B, int H, int N, int D) {
 int sage_smooth_quant_k(const void* k_f16, int8_t* k_i8, float* k_scale, float* k_mean,
                         void* workspace, size_t workspace_bytes,
                         int B, int H, int N, int D, int block_k, void* stream) {
-    if (!k_f16 || !k_i8 || !k_scale || !k_mean || !workspace) return SAGE_ERR_NULL;
-    if (int e = check_shape(B, H, N, D)) return e;
-    if (!quant_block_ok(block_k)) return SAGE_ERR_UNSUPPORTED;
-    if (workspace_bytes < sage_smooth_quant_k_workspace(B, H, N, D)) return SAGE_ERR_WORKSPACE;
-    if (!aligned(k_f16, 16) || !aligned(k_i8, 16) || !aligned(k_scale, 4) || !aligned(k_mean, 4) ||
-        !aligned(workspace, 8))
-        return SAGE_ERR_ALIGN;
-    hipError_t e = sage::launch_smooth_quant_k(k_f16, k_i8, k_scale, k_mean, (long long*)workspace,
-                                               B * H, N, D, block_k, (hipStream_t)stream);
-    return e == hipSuccess ? SAGE_OK : SAGE_ERR_LAUNCH;
+    return smooth_quant_k_impl(k_f16, nullptr, nullptr, false, k_i8, k_scale, k_mean, workspace, workspace_bytes,
+                               B, H, N, D, block_k, stream);
+}
+
+int sage_rope_smooth_quant_k(const void* k_f16, const float* rope_cos, const float* rope_sin,
+                             int8_t* k_i8, float* k_scale, float* k_mean,
+                             void* workspace, size_t workspace_bytes,
+                             int B, int H, int N, int D, int block_k, void* stream) {
+    return smooth_quant_k_impl(k_f16, rope_cos, rope_sin, true, k_i8, k_scale, k_mean, workspace, workspace_bytes,
+                               B, H, N, D, block_k, stream);
 }
 
 int sage_attn_fwd(const int8_t* q_i8, const float* q_scale, const int8_t* k_i8, const float* k_scale,

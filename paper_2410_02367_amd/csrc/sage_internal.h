@@ -5,11 +5,13 @@
 
 namespace sage {
 
-// Pre-pass (HBM-bound).  All return the hipError_t of the launch.
+// Pre-pass (HBM-bound).  All return the hipError_t of the launch.  cs / sn: RoPE tables [N, D/2]
+// applied to the input rows on the fly, or both null for none.
 hipError_t launch_quant_q(const void* q, int8_t* qq, float* qscale, int BH, int N, int D,
-                          float sm_scale, int block, hipStream_t st);
+                          float sm_scale, int block, const float* cs, const float* sn, hipStream_t st);
 hipError_t launch_smooth_quant_k(const void* k, int8_t* kq, float* kscale, float* kmean,
-                                 long long* sums, int BH, int N, int D, int block, hipStream_t st);
+                                 long long* sums, int BH, int N, int D, int block,
+                                 const float* cs, const float* sn, hipStream_t st);
 
 // Fused attention (MFMA-bound).  sdump != nullptr selects the int32 score dump.
 hipError_t launch_attn(const int8_t* qq, const float* qscale, const int8_t* kq, const float* kscale,

@@ -5,6 +5,7 @@
 //   INT8 pack
 //   Q * sm_scale, per-block absmax,   -> Section 4.6 (scale folded into Q) + Section 3.2
 //   INT8 pack
+//   optionally RoPE applied on the fly -> Section 4.6 (quantizer fused into the producer of Q, K)
 //
 // Every fp16 value is an integer multiple of 2^-24, so the column sum is accumulated as an
 // integer count of 2^-24 units; the result does not depend on how tokens are split over
@@ -16,15 +17,50 @@ namespace sage {
 
 typedef _Float16 h8 __attribute__((ext_vector_type(8)));
 
+// The 8 channels 8*c8 .. 8*c8+7 of one token row (fp16 [D]).  With ROPE the row passes through the
+// rotary embedding first (Section 4.6: the quantizer is fused into the operator that produces Q
+// and K): channel c < D/2 is paired with c + D/2,
+//     y[c] = x[c] cos[c] - x[c+D/2] sin[c],    y[c+D/2] = x[c+D/2] cos[c] + x[c] sin[c],
+// every product and the sum rounded to fp32, y rounded to fp16 -- the tensor an unfused RoPE kernel
+// would have stored, so that the fused pre-pass returns exactly what the unfused one returns.
+// cos_row / sin_row point at the D/2 fp32 table entries of the token's position.  The partner
+// chunk is a second 16-byte load from the same cache line(s).
+template <int D, bool ROPE>
+__device__ __forceinline__ h8 load_row8(const _Float16* __restrict__ row, int c8,
+                                        const float* __restrict__ cos_row, const float* __restrict__ sin_row) {
+    const h8 own = *(const h8*)(row + c8 * 8);
+    if constexpr (!ROPE) {
+        return own;
+    } else {
+        constexpr int HALF = D / 2;
+        const int c = c8 * 8;
+        const bool upper = c >= HALF;
+        const int cp = upper ? c - HALF : c + HALF, ct = upper ? c - HALF : c;
+        const h8 partner = *(const h8*)(row + cp);
+        const float4 c0 = *(const float4*)(cos_row + ct), c1 = *(const float4*)(cos_row + ct + 4);
+        const float4 s0 = *(const float4*)(sin_row + ct), s1 = *(const float4*)(sin_row + ct + 4);
+        const float cs[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
+        const float sn[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
+        h8 y;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float oc = (float)own[e] * cs[e], ps = (float)partner[e] * sn[e];
+            y[e] = (_Float16)(upper ? oc + ps : oc - ps);
+        }
+        return y;
+    }
+}
+
 __global__ void __launch_bounds__(256) zero_sums_kernel(long long* sums, int n) {
     int i = blockIdx.x * 256 + threadIdx.x;
     if (i < n) sums[i] = 0;
 }
 
 // grid (ceil(N / CHUNK), BH); CHUNK = 32 rows per thread * (256 / (D/8)) row groups.
-template <int D>
+template <int D, bool ROPE>
 __global__ void __launch_bounds__(256) k_colsum_kernel(const _Float16* __restrict__ k,
-                                                       long long* __restrict__ sums, int N) {
+                                                       long long* __restrict__ sums, int N,
+                                                       const float* __restrict__ cs, const float* __restrict__ sn) {
     constexpr int VPR = D / 8;          // 16-byte vectors per token row
     constexpr int RG = 256 / VPR;       // row groups per workgroup
     constexpr int RPT = 32;             // rows per thread: keeps the int32 partials far from overflow
@@ -32,7 +68,7 @@ __global__ void __launch_bounds__(256) k_colsum_kernel(const _Float16* __restric
     const int t = threadIdx.x, c8 = t % VPR, rg = t / VPR;
     const int bh = blockIdx.y;
     const int row_base = blockIdx.x * CHUNK + rg;
-    const _Float16* base = k + ((size_t)bh * N) * D + c8 * 8;
+    const _Float16* base = k + ((size_t)bh * N) * D;
 
     int acc_hi[8], acc_lo[8];
 #pragma unroll
@@ -41,7 +77,7 @@ __global__ void __launch_bounds__(256) k_colsum_kernel(const _Float16* __restric
     for (int i = 0; i < RPT; ++i) {
         int r = row_base + i * RG;
         if (r < N) {
-            h8 x = *(const h8*)(base + (size_t)r * D);
+            h8 x = load_row8<D, ROPE>(base + (size_t)r * D, c8, cs + (size_t)r * (D / 2), sn + (size_t)r * (D / 2));
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 float f = (float)x[e];
@@ -75,13 +111,14 @@ __device__ __forceinline__ float wg_max(float v, float* red) {
 
 // One workgroup per quantization block of `block` tokens x D channels; block * D = 2048 * LPT.
 // IS_K: x - mean (mean derived from the exact sums); else x * sm_scale.
-template <int D, int LPT, bool IS_K>
+template <int D, int LPT, bool IS_K, bool ROPE>
 __global__ void __launch_bounds__(256) quant_block_kernel(const _Float16* __restrict__ x,
                                                           int8_t* __restrict__ xq,
                                                           float* __restrict__ scale,
                                                           float* __restrict__ k_mean,
                                                           const long long* __restrict__ sums,
-                                                          int N, int block, float sm_scale) {
+                                                          int N, int block, float sm_scale,
+                                                          const float* __restrict__ cs, const float* __restrict__ sn) {
     constexpr int VPR = D / 8;
     constexpr int RSTEP = 256 / VPR;
     const int t = threadIdx.x, c8 = t % VPR, rbase = t / VPR;
@@ -112,7 +149,8 @@ __global__ void __launch_bounds__(256) quant_block_kernel(const _Float16* __rest
     for (int i = 0; i < LPT; ++i) {
         int r = rbase + i * RSTEP;
         if (r < rows) {
-            raw[i] = *(const h8*)(x + slab + (size_t)r * D);
+            raw[i] = load_row8<D, ROPE>(x + slab - c8 * 8 + (size_t)r * D, c8, cs + (size_t)(row0 + r) * (D / 2),
+                                        sn + (size_t)(row0 + r) * (D / 2));
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 float f = (float)raw[i][e];
@@ -148,13 +186,14 @@ __global__ void __launch_bounds__(256) quant_block_kernel(const _Float16* __rest
 // (16 bytes each); the row's absmax is a butterfly over those lanes.  A workgroup covers
 // TOK_ROWS consecutive tokens, TOK_LPT rows per thread, all loads issued before the first use.
 constexpr int TOK_LPT = 8;
-template <int D, bool IS_K>
+template <int D, bool IS_K, bool ROPE>
 __global__ void __launch_bounds__(256) quant_token_kernel(const _Float16* __restrict__ x,
                                                           int8_t* __restrict__ xq,
                                                           float* __restrict__ scale,
                                                           float* __restrict__ k_mean,
                                                           const long long* __restrict__ sums,
-                                                          int N, float sm_scale) {
+                                                          int N, float sm_scale,
+                                                          const float* __restrict__ cs, const float* __restrict__ sn) {
     constexpr int VPR = D / 8;
     constexpr int RSTEP = 256 / VPR;
     constexpr int ROWS = RSTEP * TOK_LPT;
@@ -183,7 +222,9 @@ __global__ void __launch_bounds__(256) quant_token_kernel(const _Float16* __rest
     for (int i = 0; i < TOK_LPT; ++i) {
         int r = rbase + i * RSTEP;
         raw[i] = (h8){0, 0, 0, 0, 0, 0, 0, 0};
-        if (row0 + r < N) raw[i] = *(const h8*)(x + slab + (size_t)r * D);
+        if (row0 + r < N)
+            raw[i] = load_row8<D, ROPE>(x + slab - c8 * 8 + (size_t)r * D, c8, cs + (size_t)(row0 + r) * (D / 2),
+                                        sn + (size_t)(row0 + r) * (D / 2));
     }
 #pragma unroll
     for (int i = 0; i < TOK_LPT; ++i) {
@@ -214,49 +255,67 @@ __global__ void __launch_bounds__(256) quant_token_kernel(const _Float16* __rest
     }
 }
 
-template <int D, bool IS_K>
+template <int D, bool IS_K, bool ROPE>
 static hipError_t launch_quant(const void* x, int8_t* xq, float* scale, float* mean, const long long* sums,
-                               int BH, int N, int block, float sm_scale, hipStream_t st) {
+                               int BH, int N, int block, float sm_scale, const float* cs, const float* sn,
+                               hipStream_t st) {
     const _Float16* xp = (const _Float16*)x;
     if (block == 1) {
         constexpr int ROWS = (256 / (D / 8)) * TOK_LPT;
-        quant_token_kernel<D, IS_K><<<dim3((N + ROWS - 1) / ROWS, BH), 256, 0, st>>>(xp, xq, scale, mean, sums, N, sm_scale);
+        quant_token_kernel<D, IS_K, ROPE><<<dim3((N + ROWS - 1) / ROWS, BH), 256, 0, st>>>(xp, xq, scale, mean, sums, N, sm_scale, cs, sn);
         return hipGetLastError();
     }
     dim3 grid((N + block - 1) / block, BH);
+#define SAGE_QUANT(LPT) quant_block_kernel<D, LPT, IS_K, ROPE><<<grid, 256, 0, st>>>(xp, xq, scale, mean, sums, N, block, sm_scale, cs, sn)
     switch (block * D / 2048) {
-        case 1: quant_block_kernel<D, 1, IS_K><<<grid, 256, 0, st>>>(xp, xq, scale, mean, sums, N, block, sm_scale); break;
-        case 2: quant_block_kernel<D, 2, IS_K><<<grid, 256, 0, st>>>(xp, xq, scale, mean, sums, N, block, sm_scale); break;
-        case 4: quant_block_kernel<D, 4, IS_K><<<grid, 256, 0, st>>>(xp, xq, scale, mean, sums, N, block, sm_scale); break;
-        case 8: quant_block_kernel<D, 8, IS_K><<<grid, 256, 0, st>>>(xp, xq, scale, mean, sums, N, block, sm_scale); break;
+        case 1: SAGE_QUANT(1); break;
+        case 2: SAGE_QUANT(2); break;
+        case 4: SAGE_QUANT(4); break;
+        case 8: SAGE_QUANT(8); break;
         default: return hipErrorInvalidValue;
     }
+#undef SAGE_QUANT
     return hipGetLastError();
 }
 
+template <int D, bool ROPE>
+static hipError_t quant_q_d(const void* q, int8_t* qq, float* qscale, int BH, int N, float sm_scale, int block,
+                            const float* cs, const float* sn, hipStream_t st) {
+    return launch_quant<D, false, ROPE>(q, qq, qscale, nullptr, nullptr, BH, N, block, sm_scale, cs, sn, st);
+}
+
+// cs, sn: RoPE tables [N, D/2] (both null: no rotation)
 hipError_t launch_quant_q(const void* q, int8_t* qq, float* qscale, int BH, int N, int D,
-                          float sm_scale, int block, hipStream_t st) {
-    if (D == 64) return launch_quant<64, false>(q, qq, qscale, nullptr, nullptr, BH, N, block, sm_scale, st);
-    return launch_quant<128, false>(q, qq, qscale, nullptr, nullptr, BH, N, block, sm_scale, st);
+                          float sm_scale, int block, const float* cs, const float* sn, hipStream_t st) {
+    const bool rope = cs != nullptr;
+    if (D == 64) return rope ? quant_q_d<64, true>(q, qq, qscale, BH, N, sm_scale, block, cs, sn, st)
+                             : quant_q_d<64, false>(q, qq, qscale, BH, N, sm_scale, block, cs, sn, st);
+    return rope ? quant_q_d<128, true>(q, qq, qscale, BH, N, sm_scale, block, cs, sn, st)
+                : quant_q_d<128, false>(q, qq, qscale, BH, N, sm_scale, block, cs, sn, st);
+}
+
+template <int D, bool ROPE>
+static hipError_t smooth_quant_k_d(const void* k, int8_t* kq, float* kscale, float* kmean, long long* sums,
+                                   int BH, int N, int block, const float* cs, const float* sn, hipStream_t st) {
+    constexpr int CHUNK = (256 / (D / 8)) * 32;
+    k_colsum_kernel<D, ROPE><<<dim3((N + CHUNK - 1) / CHUNK, BH), 256, 0, st>>>((const _Float16*)k, sums, N, cs, sn);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    return launch_quant<D, true, ROPE>(k, kq, kscale, kmean, sums, BH, N, block, 1.0f, cs, sn, st);
 }
 
 hipError_t launch_smooth_quant_k(const void* k, int8_t* kq, float* kscale, float* kmean,
-                                 long long* sums, int BH, int N, int D, int block, hipStream_t st) {
+                                 long long* sums, int BH, int N, int D, int block,
+                                 const float* cs, const float* sn, hipStream_t st) {
     int n = BH * D;
     zero_sums_kernel<<<(n + 255) / 256, 256, 0, st>>>(sums, n);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    if (D == 64) {
-        constexpr int CHUNK = (256 / 8) * 32;
-        k_colsum_kernel<64><<<dim3((N + CHUNK - 1) / CHUNK, BH), 256, 0, st>>>((const _Float16*)k, sums, N);
-    } else {
-        constexpr int CHUNK = (256 / 16) * 32;
-        k_colsum_kernel<128><<<dim3((N + CHUNK - 1) / CHUNK, BH), 256, 0, st>>>((const _Float16*)k, sums, N);
-    }
-    e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    if (D == 64) return launch_quant<64, true>(k, kq, kscale, kmean, sums, BH, N, block, 1.0f, st);
-    return launch_quant<128, true>(k, kq, kscale, kmean, sums, BH, N, block, 1.0f, st);
+    const bool rope = cs != nullptr;
+    if (D == 64) return rope ? smooth_quant_k_d<64, true>(k, kq, kscale, kmean, sums, BH, N, block, cs, sn, st)
+                             : smooth_quant_k_d<64, false>(k, kq, kscale, kmean, sums, BH, N, block, cs, sn, st);
+    return rope ? smooth_quant_k_d<128, true>(k, kq, kscale, kmean, sums, BH, N, block, cs, sn, st)
+                : smooth_quant_k_d<128, false>(k, kq, kscale, kmean, sums, BH, N, block, cs, sn, st);
 }
 
 }  // namespace sage

@@ -70,3 +70,10 @@ def test_host_validation_rejects_bad_arguments_before_any_launch(lib):
     assert lib.sage_smooth_quant_k(good, good, good, good, good, 8, 1, 1, 64, 64, 64, None) == 4
     assert lib.sage_quant_q(odd, good, good, 1, 1, 64, 64, f(0.125), 64, None) == 5
     assert lib.sage_attn_qk_i32_debug(good, odd, good, 1, 1, 64, 64, None) == 5
+    # the fused-RoPE calls: tables required and 16-byte aligned, everything else as the unfused calls
+    assert lib.sage_rope_quant_q(good, None, good, good, good, 1, 1, 64, 64, f(0.125), 64, None) == 1
+    assert lib.sage_rope_quant_q(good, good, odd, good, good, 1, 1, 64, 64, f(0.125), 64, None) == 5
+    assert lib.sage_rope_quant_q(good, good, good, good, good, 1, 1, 64, 64, f(0.125), 48, None) == 3
+    assert lib.sage_rope_smooth_quant_k(good, good, None, good, good, good, good, 1 << 20, 1, 1, 64, 64, 64, None) == 1
+    assert lib.sage_rope_smooth_quant_k(good, good, good, good, good, good, good, 8, 1, 1, 64, 64, 64, None) == 4
+    assert lib.sage_rope_smooth_quant_k(good, odd, good, good, good, good, good, 1 << 20, 1, 1, 64, 64, 64, None) == 5
