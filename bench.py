@@ -95,6 +95,9 @@ def main():
     ap.add_argument("--rope", action="store_true",
                     help="the pre-pass applies RoPE to Q and K on the fly (the fused calls of Section 4.6's "
                          "fusion trick); not the headline configuration")
+    ap.add_argument("--graph", action="store_true",
+                    help="time replays of a HIP graph that holds one step (the library's calls only enqueue "
+                         "kernels, so they can be captured); for the short-sequence shapes, where launches dominate")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one plain elementwise copy kernel of 1 GiB before the warm-up, so that a "
                          "hardware-counter run holds a kernel of known HBM traffic beside the library's kernels")
@@ -137,7 +140,7 @@ def main():
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
           for _ in range(args.steps)]
 
-    def step(i=None):
+    def step(i=None, stream=stream):
         if i is not None:
             ev[i][0].record(stream)
         if args.rope:
@@ -163,11 +166,31 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
+    if args.graph:
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            step(stream=side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step(stream=side)
+        for _ in range(args.warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for i in range(args.steps):      # untimed eager steps: per-kernel durations for the roofline object
+            step(i)
+        torch.cuda.synchronize()
+    else:
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            step(i)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     attn_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / args.steps
     pre_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / args.steps
@@ -193,6 +216,7 @@ def main():
                                + ("one scale per token of Q and K (SAGEAttn-T)" if per_token else
                                   f"block_q={w.block_q} block_k={w.block_k}")
                                + ("; RoPE applied inside the pre-pass" if args.rope else "")
+                               + ("; timed as replays of a HIP graph of one step" if args.graph else "")
                                + "; step = K pre-pass + Q pre-pass + attention"},
         "attn_kernel_ms": attn_ms,
         "prepass_ms": pre_ms,

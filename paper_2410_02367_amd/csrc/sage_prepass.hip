@@ -255,6 +255,125 @@ __global__ void __launch_bounds__(256) quant_token_kernel(const _Float16* __rest
     }
 }
 
+// Short sequences (N <= SMALL_N): the whole K pre-pass of one (batch, head) slab in ONE workgroup
+// and one launch -- exact column sums, mean, then the quantization blocks one after the other
+// (the slab is re-read from cache).  Three launches of a few microseconds each become one; the
+// results are the same bits (the integer sum does not depend on how it is split).  Beyond a few
+// blocks per slab the serial loop over blocks loses against the three wide launches (measured:
+// faster at N = 197, slower at N = 1105), hence the low limit.
+constexpr int SMALL_N = 512;
+template <int D, bool ROPE>
+__global__ void __launch_bounds__(256) k_small_kernel(const _Float16* __restrict__ k,
+                                                      int8_t* __restrict__ kq,
+                                                      float* __restrict__ scale,
+                                                      float* __restrict__ k_mean,
+                                                      int N, int block,
+                                                      const float* __restrict__ cs, const float* __restrict__ sn) {
+    constexpr int VPR = D / 8;
+    constexpr int RG = 256 / VPR;
+    constexpr int HALF = D / 2;
+    const int t = threadIdx.x, c8 = t % VPR, rg = t / VPR;
+    const int bh = blockIdx.x;
+    const _Float16* base = k + ((size_t)bh * N) * D;
+
+    __shared__ long long part[RG][D];
+    __shared__ float s_mean[D];
+    __shared__ float s_red[2][4];
+
+    // ---- exact column sums: at most SMALL_N / RG = 32 rows per thread, in two int32 parts each
+    // (|integer part| <= 65504, fraction * 2^24 < 2^24: 32 of either stay far below 2^31)
+    int acc_hi[8], acc_lo[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { acc_hi[e] = 0; acc_lo[e] = 0; }
+    for (int r = rg; r < N; r += RG) {
+        const h8 x = load_row8<D, ROPE>(base + (size_t)r * D, c8, cs + (size_t)r * HALF, sn + (size_t)r * HALF);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float f = (float)x[e];
+            const float hi = __builtin_truncf(f);
+            const float lo = f - hi;
+            acc_hi[e] += (int)hi;
+            acc_lo[e] += (int)(lo * 16777216.0f);
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+        part[rg][c8 * 8 + e] = (long long)acc_hi[e] * 16777216ll + (long long)acc_lo[e];
+    __syncthreads();
+    if (t < D) {
+        long long sum = 0;
+#pragma unroll 4
+        for (int g = 0; g < RG; ++g) sum += part[g][t];
+        const double avg = (double)sum / (double)N;
+        const float m = (float)(avg * 0x1p-24);
+        s_mean[t] = m;
+        k_mean[(size_t)bh * D + t] = m;
+    }
+    __syncthreads();
+    float mean[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) mean[e] = s_mean[c8 * 8 + e];
+
+    int8_t* qbase = kq + ((size_t)bh * N) * D + c8 * 8;
+    auto quantize_row = [&](const h8& raw, float rcp, int r) {
+        unsigned w[2] = {0u, 0u};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float q = __builtin_rintf(((float)raw[e] - mean[e]) * rcp);     // round half to even
+            q = __builtin_fminf(__builtin_fmaxf(q, -127.0f), 127.0f);
+            w[e >> 2] |= ((unsigned)((int)q) & 0xffu) << (8 * (e & 3));
+        }
+        *(uint2*)(qbase + (size_t)r * D) = make_uint2(w[0], w[1]);
+    };
+
+    if (block == 1) {
+        // per-token scales: the VPR lanes of a row reduce among themselves
+        for (int r0 = 0; r0 < N; r0 += RG) {
+            const int r = r0 + rg;
+            h8 raw = (h8){0, 0, 0, 0, 0, 0, 0, 0};
+            if (r < N) raw = load_row8<D, ROPE>(base + (size_t)r * D, c8, cs + (size_t)r * HALF, sn + (size_t)r * HALF);
+            float amax = 0.0f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) amax = __builtin_fmaxf(amax, __builtin_fabsf((float)raw[e] - mean[e]));
+#pragma unroll
+            for (int off = VPR / 2; off >= 1; off >>= 1) amax = __builtin_fmaxf(amax, __shfl_xor(amax, off, 64));
+            if (r < N) {
+                if (c8 == 0) scale[(size_t)bh * N + r] = amax / 127.0f;
+                quantize_row(raw, amax > 0.0f ? 127.0f / amax : 0.0f, r);
+            }
+        }
+        return;
+    }
+
+    // per-block scales: block * D = 2048 * lpt elements, lpt <= 8 rows per thread
+    const int nblk = (N + block - 1) / block;
+    const int lpt = block / RG;
+    for (int g = 0; g < nblk; ++g) {
+        const int row0 = g * block;
+        const int rows = (N - row0 < block) ? (N - row0) : block;
+        h8 raw[8];
+        float amax = 0.0f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int r = rg + i * RG;
+            if (i < lpt && r < rows) {
+                raw[i] = load_row8<D, ROPE>(base + (size_t)(row0 + r) * D, c8, cs + (size_t)(row0 + r) * HALF,
+                                            sn + (size_t)(row0 + r) * HALF);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) amax = __builtin_fmaxf(amax, __builtin_fabsf((float)raw[i][e] - mean[e]));
+            }
+        }
+        amax = wg_max(amax, s_red[g & 1]);       // alternating buffers: one barrier per block is enough
+        if (t == 0) scale[(size_t)bh * nblk + g] = amax / 127.0f;
+        const float rcp = amax > 0.0f ? 127.0f / amax : 0.0f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int r = rg + i * RG;
+            if (i < lpt && r < rows) quantize_row(raw[i], rcp, row0 + r);
+        }
+    }
+}
+
 template <int D, bool IS_K, bool ROPE>
 static hipError_t launch_quant(const void* x, int8_t* xq, float* scale, float* mean, const long long* sums,
                                int BH, int N, int block, float sm_scale, const float* cs, const float* sn,
@@ -307,6 +426,18 @@ static hipError_t smooth_quant_k_d(const void* k, int8_t* kq, float* kscale, flo
 hipError_t launch_smooth_quant_k(const void* k, int8_t* kq, float* kscale, float* kmean,
                                  long long* sums, int BH, int N, int D, int block,
                                  const float* cs, const float* sn, hipStream_t st) {
+    if (N <= SMALL_N) {
+        const _Float16* kp = (const _Float16*)k;
+        const bool rope = cs != nullptr;
+        if (D == 64) {
+            if (rope) k_small_kernel<64, true><<<BH, 256, 0, st>>>(kp, kq, kscale, kmean, N, block, cs, sn);
+            else k_small_kernel<64, false><<<BH, 256, 0, st>>>(kp, kq, kscale, kmean, N, block, cs, sn);
+        } else {
+            if (rope) k_small_kernel<128, true><<<BH, 256, 0, st>>>(kp, kq, kscale, kmean, N, block, cs, sn);
+            else k_small_kernel<128, false><<<BH, 256, 0, st>>>(kp, kq, kscale, kmean, N, block, cs, sn);
+        }
+        return hipGetLastError();
+    }
     int n = BH * D;
     zero_sums_kernel<<<(n + 255) / 256, 256, 0, st>>>(sums, n);
     hipError_t e = hipGetLastError();

@@ -27,6 +27,8 @@ SMALL = [
     si.custom("whole_tiles", 2, 2, 512, 128, False, 128, 64, seed=si.BASE_SEED + 19),
     si.custom("one_short_of_a_tile", 1, 2, 255, 64, True, 128, 64, seed=si.BASE_SEED + 21),
     si.custom("one_past_a_tile", 1, 2, 257, 128, True, 128, 64, seed=si.BASE_SEED + 22),
+    # 512 tokens is the last size whose K pre-pass runs as a single launch, 513 the first that does not
+    si.custom("single_launch_limit", 1, 3, 513, 64, False, 128, 64, seed=si.BASE_SEED + 23),
 ]
 
 
