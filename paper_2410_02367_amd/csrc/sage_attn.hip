@@ -144,9 +144,18 @@ __device__ __forceinline__ void l_mfma(const v16f& acc, const v4i& ones, const v
 // tell which LDS bytes such a load writes, makes every later LDS read wait for it (vmcnt(0)) and
 // so turns the asynchronous load into a synchronous one.  Completion is tracked by hand: the
 // issuing wavefront waits with s_waitcnt vmcnt before the barrier that publishes the tile.
-__device__ __forceinline__ void load_to_lds16(const void* gbase, unsigned goff, unsigned lds_addr) {
-    // address = wave-uniform 64-bit base (scalar registers) + per-lane 32-bit byte offset
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(goff), "s"(gbase), "s"(lds_addr) : "memory");
+//
+// The load is a raw-buffer load: the descriptor (four scalar registers) carries the base address
+// and the byte size of the (batch, head) slab, the per-lane offset is checked against that size by
+// the hardware and a lane beyond it reads zero instead of memory.  The ragged last tile therefore
+// needs no clamping code at all (its rows are masked or multiplied by P~ = 0 anyway).
+__device__ __forceinline__ v4i slab_descriptor(const void* base, unsigned bytes) {
+    const unsigned long long p = (unsigned long long)base;
+    // dword 0-1: 48-bit base, stride 0 (raw buffer); dword 2: size in bytes; dword 3: 32-bit data format
+    return (v4i){(int)(unsigned)p, (int)((unsigned)(p >> 32) & 0xffffu), (int)bytes, 0x00020000};
+}
+__device__ __forceinline__ void load_to_lds16(const v4i& rsrc, unsigned goff, unsigned lds_addr) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %1, 0 offen lds" : : "v"(goff), "s"(rsrc), "s"(lds_addr) : "memory");
 }
 // Tells the compiler that an accumulator changed, 12 wait states after the last matrix instruction
 // that wrote it (all of these statements are volatile, so their order is kept).
@@ -251,9 +260,10 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
     // ---- global -> LDS tile loads without staging registers (the load unit writes LDS directly).
     // Instruction i of wavefront w fills the 16-byte vectors (NTHREADS*i + 64*w) .. +63 of the
     // (linear, unpadded) LDS tile, one per lane; the global chunk a lane fetches is the swizzled
-    // one.  Rows past N are clamped to the last row: their scores are masked, so the values never
-    // matter.  The loads are asynchronous: a wavefront waits for its own (vmcnt) before the barrier
-    // that publishes the tile.
+    // one.  Rows past N lie beyond the slab's descriptor and are not fetched: their scores are masked
+    // and their P~ is zero, so the values never matter (as long as the V rows are finite: see the
+    // prologue).  The loads are asynchronous: a wavefront waits for its own (vmcnt) before the
+    // barrier that publishes the tile.
     int k_goff[KL], v_goff[VL];          // byte offsets inside a full tile (row * pitch + swizzled chunk)
 #pragma unroll
     for (int i = 0; i < KL; ++i) {
@@ -265,38 +275,24 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
         int vidx = t + NTHREADS * i, row = vidx / VCH, c = (vidx % VCH) ^ v_swz<D>(row);
         v_goff[i] = row * 2 * D + c * 16;
     }
-    const unsigned char* k_slab = (const unsigned char*)(ki + slab * D);
-    const unsigned char* v_slab = (const unsigned char*)(vg + slab * D);
+    const v4i k_rsrc = slab_descriptor(ki + slab * D, (unsigned)N * D);
+    const v4i v_rsrc = slab_descriptor(vg + slab * D, (unsigned)N * 2 * D);
     const unsigned lds_base = (unsigned)(size_t)LDS_PTR(unsigned char, lds);     // LDS byte address of the tile area
     auto load_k = [&](int j, int buf) {
-        const int kv0 = j * KTILE, lim = N - 1 - kv0;
-        const unsigned char* kt = k_slab + (size_t)kv0 * D;
+        const unsigned tile = (unsigned)j * (KTILE * D);           // byte offset of the tile in the slab
 #pragma unroll
         for (int i = 0; i < KL; ++i) {
             if (NTHREADS * (i + 1) > KVEC && NTHREADS * i + wave * 64 >= KVEC) continue;   // piece beyond the tile for this wavefront
-            int off = k_goff[i];
-            if (kv0 + KTILE > N) {       // last tile only; the empty statement keeps this a branch instead of a select
-                asm volatile("");
-                int row = k_goff[i] / D, rc = row < lim ? row : lim;
-                off += (rc - row) * D;
-            }
-            load_to_lds16(kt, off, lds_base + buf * KB + (NTHREADS * i + wave * 64) * 16);
+            load_to_lds16(k_rsrc, tile + k_goff[i], lds_base + buf * KB + (NTHREADS * i + wave * 64) * 16);
         }
     };
     auto load_v = [&](int j, int buf) {
         if (DUMP) return;                 // the score dump never touches V
-        const int kv0 = j * KTILE, lim = N - 1 - kv0;
-        const unsigned char* vt = v_slab + (size_t)kv0 * 2 * D;
+        const unsigned tile = (unsigned)j * (KTILE * 2 * D);
 #pragma unroll
         for (int i = 0; i < VL; ++i) {
             if (NTHREADS * (i + 1) > VVEC && NTHREADS * i + wave * 64 >= VVEC) continue;
-            int off = v_goff[i];
-            if (kv0 + KTILE > N) {
-                asm volatile("");
-                int row = v_goff[i] / (2 * D), rc = row < lim ? row : lim;
-                off += (rc - row) * 2 * D;
-            }
-            load_to_lds16(vt, off, lds_base + 2 * KB + buf * VB + (NTHREADS * i + wave * 64) * 16);
+            load_to_lds16(v_rsrc, tile + v_goff[i], lds_base + 2 * KB + buf * VB + (NTHREADS * i + wave * 64) * 16);
         }
     };
     // own tile loads landed (vmcnt(0)), then the workgroup barrier
@@ -692,11 +688,15 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
         }
     };
 
-    // ---- prologue: K^(0), K^(1) into LDS, the V buffer that step 0 reads zero-filled; S_0
+    // ---- prologue: K^(0), K^(1) into LDS; S_0.  Both V buffers start zero-filled: step 0 reads
+    // buffer 1 before any tile has arrived (its P~ is zero, but 0 * NaN would not be), and rows of a
+    // ragged last tile that lie beyond the slab must hold finite values whatever the load leaves there.
     if (!DUMP) {
 #pragma unroll
-        for (int i = 0; i < VL; ++i)
-            if (NTHREADS * i + wave * 64 < VVEC) *(v4i*)(lds + 2 * KB + VB + (t + NTHREADS * i) * 16) = (v4i){0, 0, 0, 0};
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int i = 0; i < VL; ++i)
+                if (NTHREADS * i + wave * 64 < VVEC) *(v4i*)(lds + 2 * KB + b * VB + (t + NTHREADS * i) * 16) = (v4i){0, 0, 0, 0};
     }
     load_k(0, 0);
     if (T > 1) load_k(1, 1);
