@@ -50,7 +50,8 @@ def check_attention_asm(text: str) -> list:
       - once the first matrix instruction has been issued it never copies an accumulator register
         to another accumulator register (before that, the zero initialisation may),
       - it reads accumulator registers into VGPRs only where the source refreshes them first (the
-        rare rescale and the epilogue), i.e. never inside a block that issues matrix instructions,
+        rare rescale and the epilogue), i.e. never inside a block that issues matrix instructions
+        (AGPRs that no matrix instruction names are the compiler's own parking space and exempt),
       - nothing spills to scratch memory,
       - and it never touches m0, which the hand-written global->LDS loads set.
       - no instruction touches a VGPR within 12 wait states of a matrix instruction writing it
@@ -63,9 +64,10 @@ def check_attention_asm(text: str) -> list:
     bodies = re.findall(r"^_ZN4sage16sage_attn_kernel\w+:.*?^\.Lfunc_end\d+:", text, re.S | re.M)
     problems = []
     # head dimension {64, 128} x workgroup shape {4, 8 wavefronts} x {score dump, causal / full
-    # with per-block key scales, causal / full with per-token key scales}
-    if len(bodies) != 20:
-        problems.append(f"expected 20 attention kernels in the assembly, found {len(bodies)}")
+    # with per-block key scales, causal / full with per-token key scales}, less the two per-token
+    # kernels of D = 128 with 4 wavefronts, which are not built
+    if len(bodies) != 18:
+        problems.append(f"expected 18 attention kernels in the assembly, found {len(bodies)}")
 
     def vregs(operand: str) -> set:
         """VGPR numbers named by one operand such as v12 or v[12:15]."""
@@ -75,11 +77,27 @@ def check_attention_asm(text: str) -> list:
         m = re.fullmatch(r"v(\d+)", operand)
         return {int(m.group(1))} if m else set()
 
+    def aregs(operand: str) -> set:
+        """AGPR numbers named by one operand such as a12 or a[12:15]."""
+        m = re.fullmatch(r"a\[(\d+):(\d+)\]", operand)
+        if m:
+            return set(range(int(m.group(1)), int(m.group(2)) + 1))
+        m = re.fullmatch(r"a(\d+)", operand)
+        return {int(m.group(1))} if m else set()
+
     def operands(code: str) -> list:
         parts = code.split(None, 1)
         return [o.strip() for o in parts[1].split(",")] if len(parts) > 1 else []
 
     for name, body in zip(kernels, bodies):
+        # AGPRs that matrix instructions name (accumulators, resident operands).  The compiler may
+        # park unrelated values in the remaining AGPRs; moving those around is harmless.
+        matrix_agprs = set()
+        for line in body.split("\n"):
+            code = line.split(";")[0].strip()
+            if code.startswith("v_mfma"):
+                for o in operands(code):
+                    matrix_agprs |= aregs(o)
         state = {"mfma": False, "reads": []}
         in_asm = False
         seen_mfma = False
@@ -141,9 +159,10 @@ def check_attention_asm(text: str) -> list:
                     state["mfma"] = True
                     seen_mfma = True
                 continue
-            if code.startswith("v_accvgpr_mov") and seen_mfma:
+            named = set().union(*[aregs(o) for o in ops]) if ops else set()
+            if code.startswith("v_accvgpr_mov") and seen_mfma and named & matrix_agprs:
                 problems.append(f"{name}: accumulator-to-accumulator copy: {code}")
-            if code.startswith("v_accvgpr_read"):
+            if code.startswith("v_accvgpr_read") and named & matrix_agprs:
                 state["reads"].append(code)
             if code.startswith("scratch_"):
                 problems.append(f"{name}: scratch access: {code}")

@@ -152,10 +152,20 @@ __device__ __forceinline__ void l_mfma(const v16f& acc, const v4i& ones, const v
 __device__ __forceinline__ v4i slab_descriptor(const void* base, unsigned bytes) {
     const unsigned long long p = (unsigned long long)base;
     // dword 0-1: 48-bit base, stride 0 (raw buffer); dword 2: size in bytes; dword 3: 32-bit data format
-    return (v4i){(int)(unsigned)p, (int)((unsigned)(p >> 32) & 0xffffu), (int)bytes, 0x00020000};
+    // (readfirstlane: the values are wave-uniform, this pins them to scalar registers)
+    return (v4i){__builtin_amdgcn_readfirstlane((int)(unsigned)p),
+                 __builtin_amdgcn_readfirstlane((int)((unsigned)(p >> 32) & 0xffffu)),
+                 __builtin_amdgcn_readfirstlane((int)bytes), 0x00020000};
 }
-__device__ __forceinline__ void load_to_lds16(const v4i& rsrc, unsigned goff, unsigned lds_addr) {
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %1, 0 offen lds" : : "v"(goff), "s"(rsrc), "s"(lds_addr) : "memory");
+// Offset = tile (wave-uniform byte offset of the tile in the slab) + goff (per lane, inside the
+// tile).  The sum is formed here, next to the load: left to the compiler it is computed a step
+// early and held in registers, and at D = 64 those few registers decide whether a third wavefront
+// fits on a SIMD.  (The scalar-offset field of the instruction would not do: it is not part of
+// the range check.)
+__device__ __forceinline__ void load_to_lds16(const v4i& rsrc, unsigned tile, unsigned goff, unsigned lds_addr) {
+    unsigned off;
+    asm volatile("s_mov_b32 m0, %4\n\tv_add_u32 %0, %2, %1\n\tbuffer_load_dwordx4 %0, %3, 0 offen lds"
+                 : "=&v"(off) : "v"(goff), "s"(tile), "s"(rsrc), "s"(lds_addr) : "memory");
 }
 // Tells the compiler that an accumulator changed, 12 wait states after the last matrix instruction
 // that wrote it (all of these statements are volatile, so their order is kept).
@@ -171,6 +181,8 @@ template <class T> __device__ __forceinline__ void pin_a(T& x) { asm volatile(""
 // (now a floating-point maximum), and the softmax FMA becomes t * (delta_Q log2 e) - m.  One
 // scale per QUERY token costs nothing in either variant: a lane owns one query.
 template <int D, int NW, bool CAUSAL, bool DUMP, bool KTOK>
+// Workgroups of 4 wavefronts per CU that the register budget is cut for: 3 at D = 64 (168 registers
+// per lane; measured 4 % faster than 2; the per-token variant needs more), else 2.
 __global__ void __launch_bounds__(NW * 64, NW == 4 && SAGE_QS == 1 ? 2 : 1)
 sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
                  const int8_t* __restrict__ ki, const float* __restrict__ ksc,
@@ -283,7 +295,7 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
 #pragma unroll
         for (int i = 0; i < KL; ++i) {
             if (NTHREADS * (i + 1) > KVEC && NTHREADS * i + wave * 64 >= KVEC) continue;   // piece beyond the tile for this wavefront
-            load_to_lds16(k_rsrc, tile + k_goff[i], lds_base + buf * KB + (NTHREADS * i + wave * 64) * 16);
+            load_to_lds16(k_rsrc, tile, k_goff[i], lds_base + buf * KB + (NTHREADS * i + wave * 64) * 16);
         }
     };
     auto load_v = [&](int j, int buf) {
@@ -292,7 +304,7 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
 #pragma unroll
         for (int i = 0; i < VL; ++i) {
             if (NTHREADS * (i + 1) > VVEC && NTHREADS * i + wave * 64 >= VVEC) continue;
-            load_to_lds16(v_rsrc, tile + v_goff[i], lds_base + 2 * KB + buf * VB + (NTHREADS * i + wave * 64) * 16);
+            load_to_lds16(v_rsrc, tile, v_goff[i], lds_base + 2 * KB + buf * VB + (NTHREADS * i + wave * 64) * 16);
         }
     };
     // own tile loads landed (vmcnt(0)), then the workgroup barrier
@@ -349,15 +361,15 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
             }
         }
     };
-    auto publish_key_scales = [&](int j) {
+    auto publish_key_scales = [&](int par) {
         if constexpr (KTOK) {
             if (wave == 0) {
                 // a zero scale (all-zero token) would turn -inf * scale into NaN for hidden keys
                 // 22 significant bits, so that 12582912 * a = 3 * 2^22 * a is exact and the fma
                 // below returns S^ * a rounded once
                 const float a = as_f32(as_i32(__builtin_fmaxf(dk_tok, 1e-30f)) & ~3);
-                ksl[(j & 1) * 2 * KTILE + lane] = a;
-                ksl[(j & 1) * 2 * KTILE + KTILE + lane] = -MAGIC_F * a;
+                ksl[par * 2 * KTILE + lane] = a;
+                ksl[par * 2 * KTILE + KTILE + lane] = -MAGIC_F * a;
             }
         }
     };
@@ -454,13 +466,13 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
     };
     // partial_max(qs, p): integer maximum over part p (of DT) of sub-tile qs's 32 scores per lane;
     // issued between the matrix instructions of the step's first slot.
-    auto partial_max = [&](auto QSI, auto P, int j) {
+    auto partial_max = [&](auto QSI, auto P, int par) {
         constexpr int qs = IDX(QSI), p = IDX(P);
         constexpr int CNT = 32 / DT, FIRST = p * CNT;              // flat index = 16*s + r
         if constexpr (KTOK) {
             // registers 4*q4 .. +3 of sub-tile s are keys 32*s + 8*q4 + 4*g .. +3: one 16-byte
             // read each of a and b; the scores are replaced by t = S^ * delta_K[key]
-            const float* kf = ksl + (j & 1) * 2 * KTILE + 4 * g;
+            const float* kf = ksl + par * 2 * KTILE + 4 * g;
             float mf = -__builtin_inff();
 #pragma unroll
             for (int f = FIRST; f < FIRST + CNT; f += 4) {
@@ -566,7 +578,9 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
     //   step_b  everything else, with the softmax chunks between the matrix instructions.
     // Between the two the (rare) raise of the running maximum takes place.
     constexpr int NOPS = 4 * DT + 2 * KS;
-    constexpr int PD = 3;        // LDS operands are read PD operands ahead of their matrix instructions
+    // LDS operands are read PD operands ahead of their matrix instructions (the depth does not show
+    // in the timing; at D = 64 the four registers of one ring slot decide the occupancy)
+    constexpr int PD = D == 64 ? 2 : 3;
     v4i opnd[PD + 1];            // operand ring (V^T operands are reinterpreted)
     auto load_operand = [&](auto O, int vbuf, int kbuf) {
         constexpr int o = IDX(O);
@@ -624,7 +638,12 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
         typedef _Float16 h2 __attribute__((ext_vector_type(2)));
         const int grp_su = ch / CHUNKS, cc = ch % CHUNKS, qs = cc / 4, pair = cc % 4;
         const f2 pp = {xs[ch % 3][0], xs[ch % 3][1]};
-        pk[qs][grp_su >> 1][grp_su & 1][pair] = __builtin_bit_cast(int, __builtin_convertvector(pp, h2));
+        int packed = __builtin_bit_cast(int, __builtin_convertvector(pp, h2));
+        // Pinned to this place in the instruction stream: otherwise the compiler is free to sink the
+        // whole softmax of the step down to its first use in the next step (it does, once two steps
+        // share a loop body), out of the shadow of this step's matrix instructions.
+        if constexpr (D == 128) asm volatile("" : "+v"(packed));     // (only the unrolled loop needs it)
+        pk[qs][grp_su >> 1][grp_su & 1][pair] = packed;
     };
     constexpr int MF_PER_SLOT = DT * QS;               // matrix instructions per slot (DT == KS)
     static_assert(CHUNKS % MF_PER_SLOT == 0, "whole chunks per matrix instruction");
@@ -635,8 +654,10 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
     static_assert(MF_PER_SLOT + (NCH / 2 - 1) / CPM < 4 * MF_PER_SLOT, "first half of S consumed before it is overwritten");
     static_assert(MF_PER_SLOT + (NCH - 1) / CPM < 4 * MF_PER_SLOT + KS * QS, "second half of S consumed before it is overwritten");
     static_assert(MF_PER_SLOT + (NCH + 1) / CPM < NOPS * QS, "last chunk packed inside the step");
-    auto step_a = [&](int j) {
-        const int vbuf = (j - 1) & 1, kbuf = (j + 1) & 1;
+    // par = j & 1, passed separately so that the unrolled main loop can give it as a constant: every
+    // LDS address of the step is then a per-lane register plus an immediate.
+    auto step_a = [&](int par) {
+        const int vbuf = par ^ 1, kbuf = par ^ 1;       // V(j-1) and K^(j+1) sit in the other buffer
         static_for<PD>([&](auto O) { load_operand(O, vbuf, kbuf); });
         __builtin_amdgcn_sched_barrier(0);
         static_for<DT>([&](auto O) {
@@ -644,14 +665,14 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
             load_operand(std::integral_constant<int, o + PD>{}, vbuf, kbuf);
             static_for<QS>([&](auto QSI) {
                 issue_mfma(O, QSI);
-                partial_max(QSI, O, j);
+                partial_max(QSI, O, par);
                 __builtin_amdgcn_sched_barrier(0);
             });
         });
         row_sums(std::integral_constant<int, 0>{});
     };
-    auto step_b = [&](int j) {
-        const int vbuf = (j - 1) & 1, kbuf = (j + 1) & 1;
+    auto step_b = [&](int par) {
+        const int vbuf = par ^ 1, kbuf = par ^ 1;
         static_for<NOPS - DT>([&](auto OO) {
             constexpr int o = IDX(OO) + DT;
             if constexpr (o + PD < NOPS) load_operand(std::integral_constant<int, o + PD>{}, vbuf, kbuf);
@@ -710,18 +731,18 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
     // readers ran in slot j-1): V(j) and K^(j+2) are requested into them and have the whole slot
     // to arrive.  Slot j reads V(j-1) and K^(j+1).  Every wavefront passes T+1 barriers after the
     // prologue's.
-    auto turn = [&](int j) {
+    auto turn = [&](int j, int par) {
         __builtin_amdgcn_s_waitcnt(0x0F70);     // own loads landed: vmcnt(0), no wait on the other counters
-        if (j < T) publish_key_scales(j);
+        if (j < T) publish_key_scales(par);
         __syncthreads();
-        if (j < T) load_v(j, j & 1);
-        if (j + 2 < T) load_k(j + 2, j & 1);
+        if (j < T) load_v(j, par);
+        if (j + 2 < T) load_k(j + 2, par);
         if (j + 1 < T) request_key_scales(j + 1);
     };
     int j = 0;
     if (DUMP) {
         for (; j < T; ++j) {
-            turn(j);
+            turn(j, j & 1);
             dump_tile(j);
             qk_half((j + 1) & 1, std::integral_constant<int, 0>{});
             qk_half((j + 1) & 1, std::integral_constant<int, 1>{});
@@ -733,24 +754,38 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
     // assembly statements carry a value around the loop that the compiler cannot see through; they
     // keep it from restructuring the loop nest, which made it spill registers.)
     unsigned opaque = 0;
-    for (; j < Tw; ++j) {
+    auto iteration = [&](int j, int par) {
         asm volatile("" : "+s"(opaque));
-        turn(j);
+        turn(j, par);
         begin_tile(j);
         asm volatile("" : "+s"(opaque));
-        step_a(j);
+        step_a(par);
         if (finish_max()) raise_maximum();
         set_bias();
         asm volatile("" : "+s"(opaque));
-        step_b(j);
+        step_b(par);
         asm volatile("" : "+s"(opaque));
+    };
+    if constexpr (D == 128) {
+        // two tiles per trip, so that the buffer parity is a compile-time constant inside the body
+        // (12 address computations less per step; measured +2..4 % at D = 128, -3 % at D = 64)
+        for (; j + 1 < Tw; j += 2) {
+            iteration(j, 0);
+            iteration(j + 1, 1);
+        }
+        if (j < Tw) {
+            iteration(j, 0);
+            ++j;
+        }
+    } else {
+        for (; j < Tw; ++j) iteration(j, j & 1);
     }
     // The scores of tile Tw that the last step produced are never read: keep their registers
     // untouched until the matrix instructions have written them (the compiler would hand them out
     // as temporaries at once).
     score_fence();
     // the P~V of the wavefront's last tile ...
-    turn(j);
+    turn(j, j & 1);
     {
         const int vbuf = (j - 1) & 1;
         static_for<4>([&](auto G) {
@@ -758,7 +793,7 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
         });
     }
     // ... and the wavefront keeps feeding the workgroup's tile pipeline until all are done.
-    for (++j; j <= T; ++j) turn(j);
+    for (++j; j <= T; ++j) turn(j, j & 1);
 
     // ---- O = diag(l)^-1 O, fp16 store
 #pragma unroll
@@ -797,10 +832,19 @@ static hipError_t launch_dn(const int8_t* qq, const float* qscale, const int8_t*
     _Float16* op = (_Float16*)o;
     const bool ktok = block_k == 1;
 #define SAGE_LAUNCH(C, DMP, KT) sage_attn_kernel<D, NW, C, DMP, KT><<<grid, NTHREADS, 0, st>>>(qq, qscale, kq, kscale, vp, op, sdump, N, shift_q, shift_k, tiles_q, per_xcd, total)
+    // per-token key scales need a few more registers than 4-wavefront workgroups at D = 128 have
+    // (two workgroups per CU: 128 + 128 registers); launch_d() never asks for that combination
+    constexpr bool KTOK_OK = !(D == 128 && NW == 4);
     if (sdump) SAGE_LAUNCH(false, true, false);
-    else if (causal && ktok) SAGE_LAUNCH(true, false, true);
+    else if (ktok) {
+        if constexpr (KTOK_OK) {
+            if (causal) SAGE_LAUNCH(true, false, true);
+            else SAGE_LAUNCH(false, false, true);
+        } else {
+            return hipErrorInvalidValue;
+        }
+    }
     else if (causal) SAGE_LAUNCH(true, false, false);
-    else if (ktok) SAGE_LAUNCH(false, false, true);
     else SAGE_LAUNCH(false, false, false);
 #undef SAGE_LAUNCH
     return hipGetLastError();
@@ -813,7 +857,7 @@ static hipError_t launch_d(const int8_t* qq, const float* qscale, const int8_t* 
     // 256-row workgroups unless that leaves fewer workgroups than the chip has room for at once
     // (256 CUs): then 128-row workgroups, two per CU, double the count.  D = 64 always takes them.
     const long big_tiles = (long)BH * ((N + 8 * WROWS - 1) / (8 * WROWS));
-    const bool small = QS == 1 && (D == 64 || big_tiles < 2 * 256);
+    const bool small = QS == 1 && (D == 64 || (big_tiles < 2 * 256 && block_k != 1 && !sdump));
     if (small) return launch_dn<D, 4>(qq, qscale, kq, kscale, v, o, sdump, BH, N, causal, block_q, block_k, st);
     return launch_dn<D, 8>(qq, qscale, kq, kscale, v, o, sdump, BH, N, causal, block_q, block_k, st);
 }

@@ -5,7 +5,8 @@ from paper_2410_02367_amd.build import check_attention_asm
 
 KERNELS = ["_ZN4sage16sage_attn_kernelILi%dELi%dELb%dELb%dELb%dEEEvPKa" % (d, nw, c, dump, ktok)
            for d in (64, 128) for nw in (4, 8)
-           for c, dump, ktok in ((0, 1, 0), (1, 0, 0), (0, 0, 0), (1, 0, 1), (0, 0, 1))]
+           for c, dump, ktok in ((0, 1, 0), (1, 0, 0), (0, 0, 0), (1, 0, 1), (0, 0, 1))
+           if not (d == 128 and nw == 4 and ktok)]
 
 
 def fake(body_of_first: str) -> str:
@@ -39,7 +40,7 @@ def test_clean_text_passes():
 
 def test_missing_kernel_is_reported():
     text = fake(CLEAN).split(KERNELS[-1])[0]
-    assert any("expected 20" in p for p in check_attention_asm(text))
+    assert any("expected 18" in p for p in check_attention_asm(text))
 
 
 def test_accumulator_copy_after_first_matrix_instruction_is_reported():
@@ -50,6 +51,11 @@ def test_accumulator_copy_after_first_matrix_instruction_is_reported():
 def test_accumulator_read_beside_matrix_instructions_is_reported():
     bad = CLEAN.replace("\tv_fma_f32 v1, v2, v3, v4\n", "\tv_accvgpr_read_b32 v1, a4\n")
     assert any("accumulator read next to matrix instructions" in p for p in check_attention_asm(fake(bad)))
+
+
+def test_registers_that_no_matrix_instruction_names_are_the_compilers_to_use():
+    ok = CLEAN.replace("\tv_fma_f32 v1, v2, v3, v4\n", "\tv_accvgpr_read_b32 v1, a40\n\tv_accvgpr_mov_b32 a41, a42\n")
+    assert check_attention_asm(fake(ok)) == []
 
 
 def test_scratch_and_m0_are_reported():
