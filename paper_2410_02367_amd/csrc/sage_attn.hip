@@ -61,9 +61,10 @@
 //     12582912 + S^ (|S^| <= 127*127*128 < 2^22), so no int->float conversion is issued and the
 //     dequantization, the log2(e) factor and the subtraction of the running maximum are one FMA;
 //   - the row maximum is taken on the raw accumulators with integer max;
-//   - P~ is packed to FP16 with the packed round-to-nearest-even convert; the row sum l is one more
-//     matrix instruction per 16 keys (a ones operand against P~^T), so l is exactly the sum of the
-//     FP16 P~ that multiplies V, and costs no VALU issue slots.  (Dot-product instructions such as
+//   - P~ is packed to FP16 with the packed round-to-nearest-even convert; the row sum l comes from
+//     two small (4x4x4, quarter-length) matrix instructions per 16 keys with an all-ones operand,
+//     each adding four of a lane's own FP16 P~ values in fp32: l is exactly the sum of the FP16 P~
+//     that multiplies V, and costs no VALU issue slots.  (Dot-product instructions such as
 //     v_dot2c run on the matrix pipe as well, but block it for VALU work -- measured.)
 #include "sage_internal.h"
 #include <type_traits>
@@ -77,6 +78,7 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 typedef _Float16 v4h __attribute__((ext_vector_type(4)));
 typedef float v4f __attribute__((ext_vector_type(4)));
+typedef int v2i __attribute__((ext_vector_type(2)));
 typedef short v4s __attribute__((ext_vector_type(4)));
 
 #define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
@@ -135,9 +137,13 @@ __device__ __forceinline__ void qk_mfma_next(v16i& acc, const v4i& a, const v4i&
 __device__ __forceinline__ void pv_mfma(const v16f& acc, const v8h& a, const v8h& b) {
     asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : : "a"(acc), "v"(a), "v"(b));
 }
-// row sums acc += ones x P~^T operand, same convention
-__device__ __forceinline__ void l_mfma(const v16f& acc, const v4i& ones, const v8h& b) {
-    asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : : "a"(acc), "a"(ones), "v"(b));
+// Row sums: the 4x4x4 instruction (16 independent 4x4 blocks, one per group of four lanes) with
+// an all-ones A operand leaves, in each of a lane's four result registers, the sum of the lane's
+// OWN four B values (checked on hardware) -- a per-lane fp32 sum of four FP16 numbers that costs
+// no VALU slot and a quarter of the matrix-pipe time of a 32x32x16 instruction.  acc += that sum;
+// same in-place convention as pv_mfma.
+__device__ __forceinline__ void l_mfma(const v4f& acc, const v2i& ones, const v2i& b) {
+    asm volatile("v_mfma_f32_4x4x4_16b_f16 %0, %1, %2, %0" : : "a"(acc), "a"(ones), "v"(b));
 }
 // One 16-byte-per-lane load from global memory straight into LDS: lane l lands at LDS byte address
 // lds_addr + 16*l (lds_addr wave-uniform).  Written as assembly because the compiler, which cannot
@@ -170,6 +176,7 @@ __device__ __forceinline__ void load_to_lds16(const v4i& rsrc, unsigned tile, un
 // Tells the compiler that an accumulator changed, 12 wait states after the last matrix instruction
 // that wrote it (all of these statements are volatile, so their order is kept).
 __device__ __forceinline__ void refresh(v16f& acc) { asm volatile("s_nop 11" : "+a"(acc)); }
+__device__ __forceinline__ void refresh(v4f& acc) { asm volatile("s_nop 11" : "+a"(acc)); }
 // Makes a value opaque and resident in the accumulator file.
 template <class T> __device__ __forceinline__ void pin_a(T& x) { asm volatile("" : "+a"(x)); }
 
@@ -241,7 +248,10 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
         }
     }
     v16f acc_o[QS][DT];      // O^T accumulators
-    v16f acc_l[QS];          // row sums l, accumulated on the matrix pipe (every register of a lane holds its query's l)
+    // Row sums l, accumulated on the matrix pipe.  A lane sums the P~ of its own 16 keys per
+    // 32-key block (the other 16 are with lane +-32: added in the epilogue); two accumulators take
+    // turns so that two row-sum instructions issued back to back do not depend on each other.
+    v4f acc_l[QS][2];
 #pragma unroll
     for (int qs = 0; qs < QS; ++qs) {
 #pragma unroll
@@ -251,11 +261,13 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
             pin_a(acc_o[qs][dt]);
         }
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc_l[qs][r] = 0.0f;
-        pin_a(acc_l[qs]);
+        for (int e = 0; e < 2; ++e) {
+            acc_l[qs][e] = (v4f){0.0f, 0.0f, 0.0f, 0.0f};
+            pin_a(acc_l[qs][e]);
+        }
     }
-    v4i ones4 = {0x3C003C00, 0x3C003C00, 0x3C003C00, 0x3C003C00};     // FP16 (1, 1) pairs
-    pin_a(ones4);
+    v2i ones2 = {0x3C003C00, 0x3C003C00};     // FP16 (1, 1) pairs
+    pin_a(ones2);
     const float* __restrict__ ksc_bh = ksc + (size_t)bh * nbk;
 
     // kv tiles visited by the workgroup (T) and by this wavefront (Tw <= T: tiles above the
@@ -420,7 +432,8 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
         });
         static_for<QS>([&](auto QSI) {
             constexpr int qs = IDX(QSI);
-            l_mfma(acc_l[qs], ones4, __builtin_bit_cast(v8h, pk[qs][s][u]));
+            l_mfma(acc_l[qs][0], ones2, __builtin_shufflevector(pk[qs][s][u], pk[qs][s][u], 0, 1));
+            l_mfma(acc_l[qs][1], ones2, __builtin_shufflevector(pk[qs][s][u], pk[qs][s][u], 2, 3));
         });
     };
 
@@ -528,7 +541,8 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
     auto raise_maximum = [&]() {
 #pragma unroll
         for (int qs = 0; qs < QS; ++qs) {
-            refresh(acc_l[qs]);
+            refresh(acc_l[qs][0]);
+            refresh(acc_l[qs][1]);
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt) refresh(acc_o[qs][dt]);
         }
@@ -539,8 +553,10 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
             const float alpha = __builtin_amdgcn_exp2f(m_run[qs] - m_new);
             m_run[qs] = m_new;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc_l[qs][r] *= alpha;
-            pin_a(acc_l[qs]);
+            for (int e = 0; e < 2; ++e) {
+                acc_l[qs][e] *= alpha;
+                pin_a(acc_l[qs][e]);
+            }
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt) {
 #pragma unroll
@@ -611,7 +627,9 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
         constexpr int grp_su = IDX(G);
         static_for<QS>([&](auto QSI) {
             constexpr int qs = IDX(QSI);
-            l_mfma(acc_l[qs], ones4, __builtin_bit_cast(v8h, pk[qs][grp_su >> 1][grp_su & 1]));
+            const v4i& p = pk[qs][grp_su >> 1][grp_su & 1];
+            l_mfma(acc_l[qs][0], ones2, __builtin_shufflevector(p, p, 0, 1));
+            l_mfma(acc_l[qs][1], ones2, __builtin_shufflevector(p, p, 2, 3));
         });
         __builtin_amdgcn_sched_barrier(0);
     };
@@ -799,10 +817,12 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
 #pragma unroll
     for (int qs = 0; qs < QS; ++qs) {
         const int q_row = qrow0 + 32 * qs + ql;
-        refresh(acc_l[qs]);
+        refresh(acc_l[qs][0]);
+        refresh(acc_l[qs][1]);
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) refresh(acc_o[qs][dt]);
-        const float inv = 1.0f / acc_l[qs][0];
+        const float l_half = acc_l[qs][0][0] + acc_l[qs][1][0];            // this lane's keys
+        const float inv = 1.0f / (l_half + as_f32(swap32i(as_i32(l_half))));   // + those of the lane 32 away
         if (q_row < N) {
             _Float16* orow = og + (slab + q_row) * D;
 #pragma unroll
