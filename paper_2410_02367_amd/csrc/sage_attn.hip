@@ -693,10 +693,14 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
         const int vbuf = par ^ 1, kbuf = par ^ 1;
         static_for<NOPS - DT>([&](auto OO) {
             constexpr int o = IDX(OO) + DT;
-            if constexpr (o + PD < NOPS) load_operand(std::integral_constant<int, o + PD>{}, vbuf, kbuf);
             static_for<QS>([&](auto QSI) {
                 constexpr int qs = IDX(QSI);
                 issue_mfma(std::integral_constant<int, o>{}, QSI);
+                if constexpr (qs == 0 && o + PD < NOPS) {
+                    // the next operand read goes out in the shadow of the matrix instruction
+                    load_operand(std::integral_constant<int, o + PD>{}, vbuf, kbuf);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
                 constexpr int mm = o * QS + qs;            // index of the matrix instruction in the step
 #pragma unroll
                 for (int c = 0; c < CPM; ++c) {
