@@ -486,7 +486,7 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
             // registers 4*q4 .. +3 of sub-tile s are keys 32*s + 8*q4 + 4*g .. +3: one 16-byte
             // read each of a and b; the scores are replaced by t = S^ * delta_K[key]
             const float* kf = ksl + par * 2 * KTILE + 4 * g;
-            float mf = -__builtin_inff();
+            float mf = p == 0 ? -__builtin_inff() : pmaxf[qs][0];       // the maximum is carried from part to part
 #pragma unroll
             for (int f = FIRST; f < FIRST + CNT; f += 4) {
                 const int s_ = f >> 4, r = f & 15;
@@ -500,14 +500,23 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
                 mf = __builtin_fmaxf(__builtin_fmaxf(mf, tv[0]), tv[1]);
                 mf = __builtin_fmaxf(__builtin_fmaxf(mf, tv[2]), tv[3]);
             }
-            pmaxf[qs][p] = mf;
+            pmaxf[qs][0] = mf;
             return;
         }
+        // the maximum is carried from part to part: CNT new values and the carry are CNT/2
+        // three-way maxima (the first part, without a carry, ends on a two-way one)
         auto val = [&](int f) { return acc_s[qs][f >> 4][f & 15]; };
-        int mi = val(FIRST);
+        if constexpr (p == 0) {
+            int mi = val(FIRST);
 #pragma unroll
-        for (int f = FIRST + 1; f + 1 < FIRST + CNT; f += 2) mi = imax3(mi, val(f), val(f + 1));
-        pmax[qs][p] = max(mi, val(FIRST + CNT - 1));
+            for (int f = FIRST + 1; f + 1 < FIRST + CNT; f += 2) mi = imax3(mi, val(f), val(f + 1));
+            pmax[qs][0] = max(mi, val(FIRST + CNT - 1));
+        } else {
+            int mi = pmax[qs][0];
+#pragma unroll
+            for (int f = FIRST; f < FIRST + CNT; f += 2) mi = imax3(mi, val(f), val(f + 1));
+            pmax[qs][0] = mi;
+        }
     };
     // finish_max: row maximum of the tile; returns whether some row of the wavefront must raise
     // its running maximum.
@@ -515,18 +524,17 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
         bool want = false;
 #pragma unroll
         for (int qs = 0; qs < QS; ++qs) {
+            // the other 32 keys of the query are with the lane 32 away: after the swap one result
+            // holds the own value and the other the partner's, in either half of the wavefront
             if constexpr (KTOK) {
-                float mf = pmaxf[qs][0];
-#pragma unroll
-                for (int p = 1; p < DT; ++p) mf = __builtin_fmaxf(mf, pmaxf[qs][p]);
-                mf = __builtin_fmaxf(mf, as_f32(swap32i(as_i32(mf))));
-                m_cand[qs] = mf * sc[qs];               // -inf stays -inf: sc > 0
+                const int mb = as_i32(pmaxf[qs][0]);
+                auto r = __builtin_amdgcn_permlane32_swap(mb, mb, false, false);
+                m_cand[qs] = __builtin_fmaxf(as_f32(r[0]), as_f32(r[1])) * sc[qs];     // -inf stays -inf: sc > 0
             } else {
-                int mi = pmax[qs][0];
-#pragma unroll
-                for (int p = 1; p < DT; ++p) mi = max(mi, pmax[qs][p]);
-                mi = max(mi, swap32i(mi));
-                m_cand[qs] = (mi < 0) ? -__builtin_inff() : (as_f32(mi) - MAGIC_F) * sc[qs];
+                auto r = __builtin_amdgcn_permlane32_swap(pmax[qs][0], pmax[qs][0], false, false);
+                const int mi = max((int)r[0], (int)r[1]);      // signed: the hidden pattern is negative
+                // a row whose keys are all hidden holds the pattern of -inf, and stays -inf here
+                m_cand[qs] = (as_f32(mi) - MAGIC_F) * sc[qs];
                 // the maximum that this tile's bias would really subtract; it differs from m_run
                 // when m_run is not on the grid of this tile's (larger) scale
                 const float m_eff = (seed_sc[qs] + m_run[qs]) - seed_sc[qs];
