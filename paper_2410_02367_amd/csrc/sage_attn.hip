@@ -92,6 +92,12 @@ typedef short v4s __attribute__((ext_vector_type(4)));
 #ifndef SAGE_QS
 #define SAGE_QS 1
 #endif
+// SAGE_SA: P~V groups issued ahead of the softmax, beside the row maximum (see "Schedule of a step"
+// in the kernel).  2 gives the maximum more matrix instructions to hide behind and packs the softmax
+// chunks denser afterwards; it measured equal at D = 128 and 1 % slower at D = 64.
+#ifndef SAGE_SA
+#define SAGE_SA 1
+#endif
 constexpr int QS = SAGE_QS;            // 32-row query sub-tiles per wavefront
 constexpr int WROWS = 32 * QS;         // query rows per wavefront
 constexpr int KTILE = 64;              // keys per LDS tile
@@ -121,6 +127,16 @@ __device__ __forceinline__ int swap32i(int v) {
 __device__ __forceinline__ float as_f32(int v) { return __builtin_bit_cast(float, v); }
 __device__ __forceinline__ int as_i32(float v) { return __builtin_bit_cast(int, v); }
 __device__ __forceinline__ int imax3(int a, int b, int c) { return max(max(a, b), c); }
+
+// Which softmax pipeline ticks run behind matrix instruction i of a step's second part: the first
+// MB instructions share the NCH chunk entries as evenly as they divide, the two after them take
+// the two ticks that drain the three-stage chunk pipeline.
+template <int NCH, int MB>
+struct TickPlan {
+    static constexpr int first(int i) { return i < MB ? i * NCH / MB : NCH + (i - MB); }
+    static constexpr int end(int i) { return i < MB ? (i + 1) * NCH / MB : (i - MB < 2 ? NCH + (i - MB) + 1 : NCH + (i - MB)); }
+    static constexpr int slot_of(int n) { int i = 0; while (end(i) <= n) ++i; return i; }
+};
 
 // ---- matrix instructions, register files chosen by hand
 // S^T block: scores in VGPRs (the softmax reads them with VALU instructions); the destination and
@@ -347,6 +363,10 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
     float seed_sc[QS];       // 12582912 * sc, exact (sc carries 22 significant bits)
     int pmax[QS][DT];        // partial integer row maxima of the current tile
     float pmaxf[QS][DT];     // ... floating-point ones when every key has its own scale
+    // P~V groups (of DT matrix instructions) that a step issues before the softmax starts, i.e.
+    // while the row maximum is being taken
+    constexpr int SA = SAGE_SA;
+    constexpr int NA = SA * DT;
 #pragma unroll
     for (int qs = 0; qs < QS; ++qs) {
 #pragma unroll
@@ -481,7 +501,8 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
     // issued between the matrix instructions of the step's first slot.
     auto partial_max = [&](auto QSI, auto P, int par) {
         constexpr int qs = IDX(QSI), p = IDX(P);
-        constexpr int CNT = 32 / DT, FIRST = p * CNT;              // flat index = 16*s + r
+        constexpr int CNT = 32 / NA, FIRST = p * CNT;              // flat index = 16*s + r
+        static_assert(CNT % 4 == 0, "whole groups of four registers per part");
         if constexpr (KTOK) {
             // registers 4*q4 .. +3 of sub-tile s are keys 32*s + 8*q4 + 4*g .. +3: one 16-byte
             // read each of a and b; the scores are replaced by t = S^ * delta_K[key]
@@ -671,22 +692,33 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
         if constexpr (D == 128) asm volatile("" : "+v"(packed));     // (only the unrolled loop needs it)
         pk[qs][grp_su >> 1][grp_su & 1][pair] = packed;
     };
-    constexpr int MF_PER_SLOT = DT * QS;               // matrix instructions per slot (DT == KS)
-    static_assert(CHUNKS % MF_PER_SLOT == 0, "whole chunks per matrix instruction");
-    constexpr int CPM = CHUNKS / MF_PER_SLOT;          // pipeline ticks per matrix instruction
-    // Chunk c enters the pipeline at tick c, right after matrix instruction MF_PER_SLOT + c/CPM:
-    // its P~ group is packed after the group's P~V of tile j-1 has been issued, and each half of
-    // S_j is consumed before the K^Q^^T of that half is issued.
-    static_assert(MF_PER_SLOT + (NCH / 2 - 1) / CPM < 4 * MF_PER_SLOT, "first half of S consumed before it is overwritten");
-    static_assert(MF_PER_SLOT + (NCH - 1) / CPM < 4 * MF_PER_SLOT + KS * QS, "second half of S consumed before it is overwritten");
-    static_assert(MF_PER_SLOT + (NCH + 1) / CPM < NOPS * QS, "last chunk packed inside the step");
+    // Schedule of a step (QS = 1 in the formulas):
+    //   step_a  the first SA P~V groups (NA matrix instructions); the row maximum of tile j is
+    //           taken between them -- nothing of tile j's softmax can start before it is known;
+    //   step_b  the other P~V groups and the first half of K^Q^^T (MB matrix instructions) carry
+    //           the NCH softmax chunks, as evenly as they divide; the second half of K^Q^^T
+    //           follows (it overwrites the half of S that the last chunks read) and takes the two
+    //           ticks that drain the chunk pipeline.
+    // Chunk c enters at tick c (fma), is exponentiated at tick c+1 and packed at tick c+2.
+    static_assert(QS == 1 || SA == 1, "the generalized schedule is written for one query sub-tile");
+    constexpr int MB = ((4 - SA) * DT + KS) * QS;
+    constexpr int NB = (NOPS - NA) * QS;                // matrix instructions of step_b
+    using Plan = TickPlan<NCH, MB>;
+    static_assert(KS * QS >= 2, "two drain ticks need two matrix instructions after the last fma");
+    // a P~ group is packed only after its P~V of tile j-1 has been issued ...
+    static_assert(SA >= 2 || Plan::slot_of(CHUNKS * 1 + 2) >= (2 - SA) * DT * QS - 1, "group 1 packed after its matrix instructions");
+    static_assert(SA >= 3 || Plan::slot_of(CHUNKS * 2 + 2) >= (3 - SA) * DT * QS - 1, "group 2 packed after its matrix instructions");
+    static_assert(SA >= 4 || Plan::slot_of(CHUNKS * 3 + 2) >= (4 - SA) * DT * QS - 1, "group 3 packed after its matrix instructions");
+    // ... and each half of S_j is consumed before the K^Q^^T of that half is issued
+    static_assert(Plan::slot_of(NCH / 2 - 1) < (4 - SA) * DT * QS, "first half of S consumed before it is overwritten");
+    static_assert(Plan::slot_of(NCH - 1) < MB, "second half of S consumed before it is overwritten");
     // par = j & 1, passed separately so that the unrolled main loop can give it as a constant: every
     // LDS address of the step is then a per-lane register plus an immediate.
     auto step_a = [&](int par) {
         const int vbuf = par ^ 1, kbuf = par ^ 1;       // V(j-1) and K^(j+1) sit in the other buffer
         static_for<PD>([&](auto O) { load_operand(O, vbuf, kbuf); });
         __builtin_amdgcn_sched_barrier(0);
-        static_for<DT>([&](auto O) {
+        static_for<NA>([&](auto O) {
             constexpr int o = IDX(O);
             load_operand(std::integral_constant<int, o + PD>{}, vbuf, kbuf);
             static_for<QS>([&](auto QSI) {
@@ -694,13 +726,13 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
                 partial_max(QSI, O, par);
                 __builtin_amdgcn_sched_barrier(0);
             });
+            if constexpr (o % DT == DT - 1) row_sums(std::integral_constant<int, o / DT>{});
         });
-        row_sums(std::integral_constant<int, 0>{});
     };
     auto step_b = [&](int par) {
         const int vbuf = par ^ 1, kbuf = par ^ 1;
-        static_for<NOPS - DT>([&](auto OO) {
-            constexpr int o = IDX(OO) + DT;
+        static_for<NOPS - NA>([&](auto OO) {
+            constexpr int o = IDX(OO) + NA;
             static_for<QS>([&](auto QSI) {
                 constexpr int qs = IDX(QSI);
                 issue_mfma(std::integral_constant<int, o>{}, QSI);
@@ -709,10 +741,9 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
                     load_operand(std::integral_constant<int, o + PD>{}, vbuf, kbuf);
                     __builtin_amdgcn_sched_barrier(0);
                 }
-                constexpr int mm = o * QS + qs;            // index of the matrix instruction in the step
+                constexpr int i = (o - NA) * QS + qs;       // index of the matrix instruction in step_b
 #pragma unroll
-                for (int c = 0; c < CPM; ++c) {
-                    const int n = (mm - MF_PER_SLOT) * CPM + c;   // pipeline tick
+                for (int n = Plan::first(i); n < Plan::end(i); ++n) {
                     if (n - 2 >= 0 && n - 2 < NCH) chunk_pack(n - 2);
                     if (n - 1 >= 0 && n - 1 < NCH) chunk_exp(n - 1);
                     if (n >= 0 && n < NCH) chunk_fma(n);
