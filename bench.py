@@ -82,6 +82,43 @@ def cpu_baseline(w, seconds_budget=20.0, per_token=False):
     }
 
 
+def sweep(per_token: bool):
+    """Attention-kernel speed over sequence length, head dimension and mask (the axes of the paper's
+    kernel-speed figures): N(0,1) inputs, H = 32, B = max(1, 16384 / N).  Prints one table row per
+    shape; not part of the one-line benchmark contract."""
+    import torch
+
+    import paper_2410_02367_amd as sage
+
+    torch.cuda.set_device(0)
+    bq, bk = (1, 1) if per_token else (128, 64)
+    print("scales: " + ("one per token" if per_token else "per block 128 x 64"))
+    print("%7s %4s %7s %3s  %10s %9s" % ("N", "D", "causal", "B", "attn ms", "TOPS"))
+    for D in (64, 128):
+        for causal in (False, True):
+            for N in (1024, 2048, 4096, 8192, 16384, 32768):
+                B, H = max(1, 16384 // N), 32
+                g = torch.Generator(device="cuda").manual_seed(N + D)
+                q, k, v = (torch.randn((B, H, N, D), generator=g, device="cuda", dtype=torch.float32).half() for _ in range(3))
+                sm = float(D) ** -0.5
+                k_i8, k_scale, _ = sage.sage_smooth_quant_k(k, bk)
+                q_i8, q_scale = sage.sage_quant_q(q, sm, bq)
+                out = torch.empty_like(v)
+                ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+                for _ in range(3):
+                    sage.sage_attn_fwd(q_i8, q_scale, k_i8, k_scale, v, causal, sm, bq, bk, out)
+                reps = 10
+                ev[0].record()
+                for _ in range(reps):
+                    sage.sage_attn_fwd(q_i8, q_scale, k_i8, k_scale, v, causal, sm, bq, bk, out)
+                ev[1].record()
+                torch.cuda.synchronize()
+                ms = ev[0].elapsed_time(ev[1]) / reps
+                ops = 4.0 * B * H * N * N * D / (2 if causal else 1)
+                print("%7d %4d %7s %3d  %10.3f %9.0f" % (N, D, causal, B, ms, ops / (ms * 1e-3) / 1e12), flush=True)
+                del q, k, v, k_i8, q_i8, out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -98,6 +135,9 @@ def main():
     ap.add_argument("--graph", action="store_true",
                     help="time replays of a HIP graph that holds one step (the library's calls only enqueue "
                          "kernels, so they can be captured); for the short-sequence shapes, where launches dominate")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the benchmark line, print the attention kernel's speed over N = 1K..32K, "
+                         "D = 64/128, with and without the causal mask")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one plain elementwise copy kernel of 1 GiB before the warm-up, so that a "
                          "hardware-counter run holds a kernel of known HBM traffic beside the library's kernels")
@@ -115,6 +155,9 @@ def main():
         print("bench.py: no GPU visible; the library has no CPU path", file=sys.stderr)
         sys.exit(2)
     sage.load()
+    if args.sweep:
+        sweep(args.scales == "token")
+        return
     w = si.WORKLOADS[args.workload]
     torch.cuda.set_device(0)
     q, k, v = si.full(w)
