@@ -85,10 +85,12 @@ typedef short v4s __attribute__((ext_vector_type(4)));
 
 // Shape of a workgroup: NW wavefronts (a template parameter of the kernel, 8 or 4) of WROWS rows.
 //   8 wavefronts, one workgroup per CU  -- two wavefronts per SIMD share one set of LDS tiles;
-//   4 wavefronts, two workgroups per CU -- chosen by the launcher for D = 64 (4 % faster there)
-//                                          and whenever the larger tile would leave CUs without work.
-// QS = 2 (64 rows per wavefront, every LDS operand feeding two matrix instructions) is a build
-// option for one wavefront per SIMD; it measured 2-3 % slower than the default.
+//   4 wavefronts, two or three workgroups per CU -- chosen by the launcher for D = 64, for short
+//                                          sequences and whenever the larger tile would leave CUs
+//                                          without work (see launch_d()).
+// QS = 2 (64 rows per wavefront, every LDS operand feeding two matrix instructions, one wavefront
+// per SIMD) is what the QS loops in the kernel are for; an earlier version measured it 2-3 % slower
+// than QS = 1, and the build and the tests cover QS = 1 only.
 #ifndef SAGE_QS
 #define SAGE_QS 1
 #endif
