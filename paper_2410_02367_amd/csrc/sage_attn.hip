@@ -625,9 +625,10 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
     //   step_b  everything else, with the softmax chunks between the matrix instructions.
     // Between the two the (rare) raise of the running maximum takes place.
     constexpr int NOPS = 4 * DT + 2 * KS;
-    // LDS operands are read PD operands ahead of their matrix instructions (the depth does not show
-    // in the timing; at D = 64 the four registers of one ring slot decide the occupancy)
-    constexpr int PD = D == 64 ? 2 : 3;
+    // LDS operands are read PD operands ahead of their matrix instructions.  The depth does not show
+    // in the timing, but at D = 64 the four registers of a ring slot decide whether a third
+    // wavefront fits on a SIMD (168 registers): worth 4-5 %, hence the shallower rings there.
+    constexpr int PD = D == 64 ? (KTOK ? 1 : 2) : 3;
     v4i opnd[PD + 1];            // operand ring (V^T operands are reinterpreted)
     auto load_operand = [&](auto O, int vbuf, int kbuf) {
         constexpr int o = IDX(O);
