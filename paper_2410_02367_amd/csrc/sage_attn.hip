@@ -2,10 +2,11 @@
 //
 // Work decomposition
 //   One workgroup = 8 wavefronts (two per SIMD, 256 registers each) = 256 query rows, 32 per
-//   wavefront; for D = 64 and for small problems 4 wavefronts = 128 rows, two workgroups per CU.
+//   wavefront; for D = 64, for short sequences and for small problems 4 wavefronts = 128 rows,
+//   two or three workgroups per CU.
 //   Key/value tiles of 64 tokens are double-buffered in LDS and shared by all wavefronts of the
-//   workgroup; they are brought in by asynchronous global->LDS loads that bypass the
-//   register file.
+//   workgroup; they are brought in by asynchronous, range-checked buffer loads that write LDS
+//   directly and bypass the register file.
 //   Scores are computed TRANSPOSED, S^T = K^ Q^^T, with the 32x32x32 INT8 matrix instruction: each
 //   lane then owns one query column and 16 keys per 32-key sub-tile, so
 //     - row max / row sum need one cross-lane step (lane <-> lane+32),
@@ -15,9 +16,10 @@
 //   V^T operands come from the row-major V tile in LDS through the transposing LDS read.
 //
 // Schedule (software pipeline inside every wavefront)
-//   A wavefront issues its instructions in order, about one per 5 cycles whatever its kind, and a
-//   matrix instruction overlaps only with what follows it in the same stream or with the other
-//   wavefront of the SIMD.  Every wavefront therefore runs three tiles at once: the softmax of
+//   A wavefront issues its instructions in order, and VALU work hides behind a matrix instruction
+//   only in the stream that issued it: a probe with one wavefront of a SIMD issuing matrix
+//   instructions and the other the softmax takes the sum of both times.  Every wavefront therefore
+//   runs three tiles at once: the softmax of
 //   tile j (VALU) is spread between the matrix instructions of P~V of tile j-1 and K^Q^^T of tile
 //   j+1.  A step is a flat sequence of LDS operands, each feeding one matrix instruction per query
 //   sub-tile, with VALU work after every matrix instruction, fenced so the order survives:
@@ -30,6 +32,9 @@
 //   of S_j.
 //   The running maximum is only raised when a row's tile maximum exceeds it by more than 2^8
 //   (P~ <= 256 fits FP16 comfortably); the rescale of O is then a rare branch between slots A and B.
+//   Inside a softmax slot the order is: matrix instruction, the LDS reads of the operand three
+//   instructions ahead, the chunk's VALU work.  At D = 128 two steps share one loop body, so that the
+//   buffer parity is a constant and every LDS address is a register plus an immediate.
 //
 // Register files
 //   The matrix instructions are written as inline assembly so that the register file of every
@@ -60,6 +65,9 @@
 //   - the int32 accumulators start at 0x4B400000; reinterpreted as fp32 the result is exactly
 //     12582912 + S^ (|S^| <= 127*127*128 < 2^22), so no int->float conversion is issued and the
 //     dequantization, the log2(e) factor and the subtraction of the running maximum are one FMA;
+//     that FMA rounds once only if its bias -(12582912 * sc + m) is exact, which holds because sc
+//     carries 22 significant bits and m is kept on the grid of 12582912 * sc (see begin_tile(),
+//     finish_max(), raise_maximum());
 //   - the row maximum is taken on the raw accumulators with integer max;
 //   - P~ is packed to FP16 with the packed round-to-nearest-even convert; the row sum l comes from
 //     two small (4x4x4, quarter-length) matrix instructions per 16 keys with an all-ones operand,
