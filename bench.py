@@ -31,7 +31,7 @@ HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 ATTN_TRAFFIC_BYTES = {"cfg3_prefill16k": 511.9e6}
 
 
-def cpu_baseline(w, seconds_budget=20.0, per_token=False):
+def cpu_baseline(w, seconds_budget=20.0, per_token=False, gpu_out_head0=None):
     """Oracle (Algorithm-1 level, as it stands) on one head of the workload: the full pre-pass of that
     head plus a spread of Q blocks, scaled to the head's block-pair count."""
     import numpy as np
@@ -67,8 +67,22 @@ def cpu_baseline(w, seconds_budget=20.0, per_token=False):
     n_blocks = max(threads, (n_blocks // threads) * threads)
     blocks = sorted(set(np.linspace(0, Tm - 1, n_blocks).round().astype(int).tolist()))
     t0 = time.perf_counter()
-    oracle.attn_l2_slab(qq[0, 0], qs[0, 0], kq[0, 0], ks[0, 0], v, w.causal, w.block_q, w.block_k, q_blocks=blocks, **gran)
+    o_l2 = oracle.attn_l2_slab(qq[0, 0], qs[0, 0], kq[0, 0], ks[0, 0], v, w.causal, w.block_q, w.block_k, q_blocks=blocks, **gran)
     t_blocks = time.perf_counter() - t0
+    # accuracy of the method (not timed): the GPU's rows of three Q blocks of this head against exact
+    # fp64 attention on the fp16 inputs, with the paper's three metrics; the oracle's rows beside them
+    accuracy = None
+    if gpu_out_head0 is not None:
+        acc_blocks = sorted({blocks[0], blocks[len(blocks) // 2], blocks[-1]})
+        rows = np.concatenate([np.arange(i * w.block_q, min(w.N, (i + 1) * w.block_q)) for i in acc_blocks])
+        exact = np.concatenate([oracle.attn_l0_slab(q, k, v, w.causal, w.sm_scale, int(i * w.block_q),
+                                                    int(min(w.N, (i + 1) * w.block_q) - i * w.block_q)) for i in acc_blocks])
+        mg = oracle.accuracy_metrics(exact, gpu_out_head0[rows])
+        mo = oracle.accuracy_metrics(exact, o_l2[rows])
+        accuracy = {"reference": "exact fp64 attention on the fp16 inputs, %d rows of head 0" % len(rows),
+                    "gpu": {key: float(mg[key]) for key in ("cos", "rel_l1", "rmse")},
+                    "oracle": {key: float(mo[key]) for key in ("cos", "rel_l1", "rmse")},
+                    "gpu_vs_oracle_max_abs": float(np.abs(gpu_out_head0[rows].astype(np.float64) - o_l2[rows].astype(np.float64)).max())}
     sampled_pairs = sum(pairs(i) for i in blocks)
     t_head = t_pre + t_blocks * total_pairs / sampled_pairs
     ops_head = w.ops / (w.B * w.H)
@@ -79,6 +93,7 @@ def cpu_baseline(w, seconds_budget=20.0, per_token=False):
         "kind": "oracle",
         "sample": (f"1 of {w.B * w.H} heads: full pre-pass ({t_pre:.2f}s) + {len(blocks)} of {Tm} Q blocks "
                    f"({t_blocks:.2f}s, {sampled_pairs} of {total_pairs} block pairs), scaled to the head"),
+        "accuracy": accuracy,
     }
 
 
@@ -292,7 +307,7 @@ def main():
     }
     if not args.no_cpu_baseline and not args.rope:      # the oracle leg times the headline path only
         del qd, kd, vd
-        result["cpu_baseline"] = cpu_baseline(w, per_token=per_token)
+        result["cpu_baseline"] = cpu_baseline(w, per_token=per_token, gpu_out_head0=out[0, 0].cpu().numpy())
     print(json.dumps(result))
 
 
