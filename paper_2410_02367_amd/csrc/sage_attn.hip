@@ -371,6 +371,7 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
     v4i pk[QS][2][2];        // P~^T as FP16 pairs: [sub-tile][32-key half][16-key group]
     float m_run[QS], sc[QS], bias[QS], m_cand[QS];
     float seed_sc[QS];       // 12582912 * sc, exact (sc carries 22 significant bits)
+    float thr[QS];           // a lane's own tile maximum above this value means: raise the running maximum
     int pmax[QS][DT];        // partial integer row maxima of the current tile
     float pmaxf[QS][DT];     // ... floating-point ones when every key has its own scale
     // P~V groups (of DT matrix instructions) that a step issues before the softmax starts, i.e.
@@ -384,7 +385,7 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
 #pragma unroll
             for (int b = 0; b < 2; ++b) pk[qs][a][b] = (v4i){0, 0, 0, 0};
         m_run[qs] = -__builtin_inff();
-        sc[qs] = 0.0f; bias[qs] = 0.0f; m_cand[qs] = 0.0f; seed_sc[qs] = 0.0f;
+        sc[qs] = 0.0f; bias[qs] = 0.0f; m_cand[qs] = 0.0f; seed_sc[qs] = 0.0f; thr[qs] = 0.0f;
     }
     v16i magic;
 #pragma unroll
@@ -494,6 +495,24 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
                 sc[qs] = as_f32(as_i32(sc[qs]) & ~3);
                 seed_sc[qs] = MAGIC_F * sc[qs];
             }
+            // Everything the steady state needs from the running maximum is prepared here, ahead
+            // of the matrix instructions of step_a, so that between the two parts of a step only
+            // one compare and one branch stand (a chain of dependent VALU instructions there stalls
+            // the in-order stream and, with it, the matrix pipe: measured 15 % of the kernel):
+            //   bias  for the softmax FMA, valid as long as the maximum is not raised;
+            //   thr   the own tile maximum (raw seeded score as fp32, or t when every key has its
+            //         scale) above which the running maximum must rise: MAX_SLACK above it in the
+            //         exp2 domain.  -inf, i.e. "always", on the first tile and when the running
+            //         maximum is off the grid on which this tile's bias is exact.
+            const float lim = (m_run[qs] + MAX_SLACK) * __builtin_amdgcn_rcpf(sc[qs]);
+            if constexpr (KTOK) {
+                bias[qs] = -m_run[qs];
+                thr[qs] = lim;
+            } else {
+                const float sum = seed_sc[qs] + m_run[qs];
+                bias[qs] = -sum;
+                thr[qs] = (sum - seed_sc[qs] != m_run[qs]) ? -__builtin_inff() : MAGIC_F + lim;
+            }
             if (need_mask) {
                 const int q_row = qrow0 + 32 * qs + ql;
 #pragma unroll
@@ -549,14 +568,21 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
             pmax[qs][0] = mi;
         }
     };
-    // finish_max: row maximum of the tile; returns whether some row of the wavefront must raise
-    // its running maximum.
-    auto finish_max = [&]() -> bool {
+    // must_raise: does some row of the wavefront need a higher running maximum?  A lane looks at
+    // the maximum over its own 32 keys only; the query's other 32 keys are with the lane 32 away,
+    // which takes part in the same vote.
+    auto must_raise = [&]() -> bool {
         bool want = false;
 #pragma unroll
+        for (int qs = 0; qs < QS; ++qs) want = want || ((KTOK ? pmaxf[qs][0] : as_f32(pmax[qs][0])) > thr[qs]);
+        return __builtin_amdgcn_ballot_w64(want) != 0ull;
+    };
+    // finish_max (rare path only): the row maximum of the tile in the exp2 domain.
+    auto finish_max = [&]() {
+#pragma unroll
         for (int qs = 0; qs < QS; ++qs) {
-            // the other 32 keys of the query are with the lane 32 away: after the swap one result
-            // holds the own value and the other the partner's, in either half of the wavefront
+            // after the swap one result holds the own value and the other the partner's, in
+            // either half of the wavefront
             if constexpr (KTOK) {
                 const int mb = as_i32(pmaxf[qs][0]);
                 auto r = __builtin_amdgcn_permlane32_swap(mb, mb, false, false);
@@ -566,18 +592,13 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
                 const int mi = max((int)r[0], (int)r[1]);      // signed: the hidden pattern is negative
                 // a row whose keys are all hidden holds the pattern of -inf, and stays -inf here
                 m_cand[qs] = (as_f32(mi) - MAGIC_F) * sc[qs];
-                // the maximum that this tile's bias would really subtract; it differs from m_run
-                // when m_run is not on the grid of this tile's (larger) scale
-                const float m_eff = (seed_sc[qs] + m_run[qs]) - seed_sc[qs];
-                want = want || (m_eff != m_run[qs]);
             }
-            want = want || (m_cand[qs] > m_run[qs] + MAX_SLACK);
         }
-        return __builtin_amdgcn_ballot_w64(want) != 0ull;
     };
     // The rare path: new running maximum; O^T, l and the P~ still waiting for its matrix
     // instructions are rescaled.
     auto raise_maximum = [&]() {
+        finish_max();
 #pragma unroll
         for (int qs = 0; qs < QS; ++qs) {
             refresh(acc_l[qs][0]);
@@ -832,8 +853,10 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
         begin_tile(j);
         asm volatile("" : "+s"(opaque));
         step_a(par);
-        if (finish_max()) raise_maximum();
-        set_bias();
+        if (must_raise()) {
+            raise_maximum();
+            set_bias();
+        }
         asm volatile("" : "+s"(opaque));
         step_b(par);
         asm volatile("" : "+s"(opaque));
