@@ -189,15 +189,19 @@ __device__ __forceinline__ v4i slab_descriptor(const void* base, unsigned bytes)
                  __builtin_amdgcn_readfirstlane((int)((unsigned)(p >> 32) & 0xffffu)),
                  __builtin_amdgcn_readfirstlane((int)bytes), 0x00020000};
 }
-// Offset = tile (wave-uniform byte offset of the tile in the slab) + goff (per lane, inside the
-// tile).  The sum is formed here, next to the load: left to the compiler it is computed a step
-// early and held in registers, and at D = 64 those few registers decide whether a third wavefront
-// fits on a SIMD.  (The scalar-offset field of the instruction would not do: it is not part of
-// the range check.)
-__device__ __forceinline__ void load_to_lds16(const v4i& rsrc, unsigned tile, unsigned goff, unsigned lds_addr) {
-    unsigned off;
-    asm volatile("s_mov_b32 m0, %4\n\tv_add_u32 %0, %2, %1\n\tbuffer_load_dwordx4 %0, %3, 0 offen lds"
-                 : "=&v"(off) : "v"(goff), "s"(tile), "s"(rsrc), "s"(lds_addr) : "memory");
+// The descriptor of a slab moved forward to one of its tiles: base + tile bytes, size - tile bytes
+// (scalar arithmetic).  The per-lane offset inside the tile then goes into the load as it is, and
+// the range check still ends at the end of the slab.  (Adding the tile offset to the per-lane
+// offset instead costs a VALU instruction per load; the scalar-offset field of the instruction
+// would not do: it is not part of the range check.)
+__device__ __forceinline__ v4i tile_descriptor(const v4i& slab, unsigned tile) {
+    const unsigned lo = (unsigned)slab[0] + tile;
+    const unsigned hi = (unsigned)slab[1] + (lo < tile ? 1u : 0u);
+    return (v4i){(int)lo, (int)hi, (int)((unsigned)slab[2] - tile), slab[3]};
+}
+__device__ __forceinline__ void load_to_lds16(const v4i& rsrc, unsigned goff, unsigned lds_addr) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %1, 0 offen lds"
+                 : : "v"(goff), "s"(rsrc), "s"(lds_addr) : "memory");
 }
 // Tells the compiler that an accumulator changed, 12 wait states after the last matrix instruction
 // that wrote it (all of these statements are volatile, so their order is kept).
@@ -329,20 +333,20 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
     const v4i v_rsrc = slab_descriptor(vg + slab * D, (unsigned)N * 2 * D);
     const unsigned lds_base = (unsigned)(size_t)LDS_PTR(unsigned char, lds);     // LDS byte address of the tile area
     auto load_k = [&](int j, int buf) {
-        const unsigned tile = (unsigned)j * (KTILE * D);           // byte offset of the tile in the slab
+        const v4i rsrc = tile_descriptor(k_rsrc, (unsigned)j * (KTILE * D));
 #pragma unroll
         for (int i = 0; i < KL; ++i) {
             if (NTHREADS * (i + 1) > KVEC && NTHREADS * i + wave * 64 >= KVEC) continue;   // piece beyond the tile for this wavefront
-            load_to_lds16(k_rsrc, tile, k_goff[i], lds_base + buf * KB + (NTHREADS * i + wave * 64) * 16);
+            load_to_lds16(rsrc, k_goff[i], lds_base + buf * KB + (NTHREADS * i + wave * 64) * 16);
         }
     };
     auto load_v = [&](int j, int buf) {
         if (DUMP) return;                 // the score dump never touches V
-        const unsigned tile = (unsigned)j * (KTILE * 2 * D);
+        const v4i rsrc = tile_descriptor(v_rsrc, (unsigned)j * (KTILE * 2 * D));
 #pragma unroll
         for (int i = 0; i < VL; ++i) {
             if (NTHREADS * (i + 1) > VVEC && NTHREADS * i + wave * 64 >= VVEC) continue;
-            load_to_lds16(v_rsrc, tile, v_goff[i], lds_base + 2 * KB + buf * VB + (NTHREADS * i + wave * 64) * 16);
+            load_to_lds16(rsrc, v_goff[i], lds_base + 2 * KB + buf * VB + (NTHREADS * i + wave * 64) * 16);
         }
     };
     // own tile loads landed (vmcnt(0)), then the workgroup barrier
@@ -371,7 +375,7 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
     v4i pk[QS][2][2];        // P~^T as FP16 pairs: [sub-tile][32-key half][16-key group]
     float m_run[QS], sc[QS], bias[QS], m_cand[QS];
     float seed_sc[QS];       // 12582912 * sc, exact (sc carries 22 significant bits)
-    float thr[QS];           // a lane's own tile maximum above this value means: raise the running maximum
+    bool off_grid[QS];       // the running maximum is not on the grid on which this tile's bias is exact
     int pmax[QS][DT];        // partial integer row maxima of the current tile
     float pmaxf[QS][DT];     // ... floating-point ones when every key has its own scale
     // P~V groups (of DT matrix instructions) that a step issues before the softmax starts, i.e.
@@ -385,7 +389,7 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
 #pragma unroll
             for (int b = 0; b < 2; ++b) pk[qs][a][b] = (v4i){0, 0, 0, 0};
         m_run[qs] = -__builtin_inff();
-        sc[qs] = 0.0f; bias[qs] = 0.0f; m_cand[qs] = 0.0f; seed_sc[qs] = 0.0f; thr[qs] = 0.0f;
+        sc[qs] = 0.0f; bias[qs] = 0.0f; m_cand[qs] = 0.0f; seed_sc[qs] = 0.0f; off_grid[qs] = false;
     }
     v16i magic;
 #pragma unroll
@@ -499,19 +503,17 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
             // of the matrix instructions of step_a, so that between the two parts of a step only
             // one compare and one branch stand (a chain of dependent VALU instructions there stalls
             // the in-order stream and, with it, the matrix pipe: measured 15 % of the kernel):
-            //   bias  for the softmax FMA, valid as long as the maximum is not raised;
-            //   thr   the own tile maximum (raw seeded score as fp32, or t when every key has its
-            //         scale) above which the running maximum must rise: MAX_SLACK above it in the
-            //         exp2 domain.  -inf, i.e. "always", on the first tile and when the running
-            //         maximum is off the grid on which this tile's bias is exact.
-            const float lim = (m_run[qs] + MAX_SLACK) * __builtin_amdgcn_rcpf(sc[qs]);
+            //   bias      for the softmax FMA, valid as long as the maximum is not raised -- the same
+            //             FMA applied to the own tile maximum tells whether it must be (must_raise());
+            //   off_grid  whether the running maximum is off the grid on which this tile's bias is
+            //             exact (then it is re-rounded in the rare path as well).
             if constexpr (KTOK) {
                 bias[qs] = -m_run[qs];
-                thr[qs] = lim;
+                off_grid[qs] = false;
             } else {
                 const float sum = seed_sc[qs] + m_run[qs];
                 bias[qs] = -sum;
-                thr[qs] = (sum - seed_sc[qs] != m_run[qs]) ? -__builtin_inff() : MAGIC_F + lim;
+                off_grid[qs] = sum - seed_sc[qs] != m_run[qs];
             }
             if (need_mask) {
                 const int q_row = qrow0 + 32 * qs + ql;
@@ -574,7 +576,11 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
     auto must_raise = [&]() -> bool {
         bool want = false;
 #pragma unroll
-        for (int qs = 0; qs < QS; ++qs) want = want || ((KTOK ? pmaxf[qs][0] : as_f32(pmax[qs][0])) > thr[qs]);
+        for (int qs = 0; qs < QS; ++qs) {
+            // the exp2 argument of the own maximum; on the first tile the bias is +inf and so is this
+            const float top = __builtin_fmaf(KTOK ? pmaxf[qs][0] : as_f32(pmax[qs][0]), sc[qs], bias[qs]);
+            want = want || off_grid[qs] || (top > MAX_SLACK);
+        }
         return __builtin_amdgcn_ballot_w64(want) != 0ull;
     };
     // finish_max (rare path only): the row maximum of the tile in the exp2 domain.
