@@ -30,15 +30,19 @@ def build(verbose: bool = False, extra=()) -> str:
     """Compile every kernel for gfx950 (cross-compiles without a GPU) and return the library path."""
     tmp = LIB + ".tmp.%d" % os.getpid()
     cmd = [hipcc(), *HIPCC_FLAGS, *extra, "-o", tmp, *[os.path.join(CSRC, s) for s in SOURCES]]
-    res = subprocess.run(cmd, capture_output=True, text=True)
-    noise = "packed-fp32-ops"
-    err = "\n".join(l for l in res.stderr.splitlines() if noise not in l)
-    if res.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + err)
-    if verbose and err.strip():
-        print(err, file=sys.stderr)
-    verify_attention_isa(extra)
-    os.replace(tmp, LIB)
+    try:
+        res = subprocess.run(cmd, capture_output=True, text=True)
+        noise = "packed-fp32-ops"
+        err = "\n".join(l for l in res.stderr.splitlines() if noise not in l)
+        if res.returncode != 0:
+            raise RuntimeError("hipcc failed:\n" + err)
+        if verbose and err.strip():
+            print(err, file=sys.stderr)
+        verify_attention_isa(extra)
+        os.replace(tmp, LIB)
+    finally:
+        if os.path.exists(tmp):         # a failed build or a failed assembly check leaves nothing behind
+            os.remove(tmp)
     return LIB
 
 
