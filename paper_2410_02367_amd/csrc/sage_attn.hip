@@ -374,7 +374,6 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
     v16i acc_s[QS][2];       // S^T of the current tile, two 32-key halves per sub-tile (raw int32 + seed)
     v4i pk[QS][2][2];        // P~^T as FP16 pairs: [sub-tile][32-key half][16-key group]
     float m_run[QS], sc[QS], bias[QS], m_cand[QS];
-    float seed_sc[QS];       // 12582912 * sc, exact (sc carries 22 significant bits)
     bool off_grid[QS];       // the running maximum is not on the grid on which this tile's bias is exact
     int pmax[QS][DT];        // partial integer row maxima of the current tile
     float pmaxf[QS][DT];     // ... floating-point ones when every key has its own scale
@@ -389,7 +388,7 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
 #pragma unroll
             for (int b = 0; b < 2; ++b) pk[qs][a][b] = (v4i){0, 0, 0, 0};
         m_run[qs] = -__builtin_inff();
-        sc[qs] = 0.0f; bias[qs] = 0.0f; m_cand[qs] = 0.0f; seed_sc[qs] = 0.0f; off_grid[qs] = false;
+        sc[qs] = 0.0f; bias[qs] = 0.0f; m_cand[qs] = 0.0f; off_grid[qs] = false;
     }
     v16i magic;
 #pragma unroll
@@ -495,9 +494,8 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
                 // it equals S^ * sc - m rounded ONCE only if that bias is exact.  The product is
                 // exact once sc is cut to 22 significant bits (a relative change of 2^-22 in the
                 // scale); the sum is exact when m is a multiple of the product's ulp, which
-                // finish_max() checks and raise_maximum() establishes.
+                // the check below detects and raise_maximum() establishes.
                 sc[qs] = as_f32(as_i32(sc[qs]) & ~3);
-                seed_sc[qs] = MAGIC_F * sc[qs];
             }
             // Everything the steady state needs from the running maximum is prepared here, ahead
             // of the matrix instructions of step_a, so that between the two parts of a step only
@@ -511,9 +509,11 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
                 bias[qs] = -m_run[qs];
                 off_grid[qs] = false;
             } else {
-                const float sum = seed_sc[qs] + m_run[qs];
+                // 12582912 * sc is exact (22 bits), so both FMAs round their sum only: the first gives
+                // the bias, the second what the bias really subtracts besides the seed
+                const float sum = __builtin_fmaf(MAGIC_F, sc[qs], m_run[qs]);
                 bias[qs] = -sum;
-                off_grid[qs] = sum - seed_sc[qs] != m_run[qs];
+                off_grid[qs] = __builtin_fmaf(-MAGIC_F, sc[qs], sum) != m_run[qs];
             }
             if (need_mask) {
                 const int q_row = qrow0 + 32 * qs + ql;
@@ -615,7 +615,8 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
 #pragma unroll
         for (int qs = 0; qs < QS; ++qs) {
             float m_new = __builtin_fmaxf(m_run[qs], m_cand[qs]);
-            if constexpr (!KTOK) m_new = (seed_sc[qs] + m_new) - seed_sc[qs];    // onto the grid on which the bias is exact
+            if constexpr (!KTOK)        // onto the grid on which the bias is exact
+                m_new = __builtin_fmaf(-MAGIC_F, sc[qs], __builtin_fmaf(MAGIC_F, sc[qs], m_new));
             const float alpha = __builtin_amdgcn_exp2f(m_run[qs] - m_new);
             m_run[qs] = m_new;
 #pragma unroll
@@ -645,7 +646,7 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
     auto set_bias = [&]() {
 #pragma unroll
         for (int qs = 0; qs < QS; ++qs)       // exp2 argument = acc*sc + bias
-            bias[qs] = KTOK ? -m_run[qs] : -(seed_sc[qs] + m_run[qs]);
+            bias[qs] = KTOK ? -m_run[qs] : -__builtin_fmaf(MAGIC_F, sc[qs], m_run[qs]);
     };
 
     // ---- one pipeline step: softmax of tile j (scores in acc_s), P~V of tile j-1, K^Q^^T of tile
