@@ -195,6 +195,61 @@ def attn_l2_slab(qq, q_scale, kq, k_scale, v, causal: bool, block_q: int, block_
     return o
 
 
+def quant_v(v: np.ndarray):
+    """psi_V of Section 4.3: per-channel INT8 quantizer of V [..., N, D] (one scale per channel of every
+    (batch, head) slab, over all tokens) -> (V^ int8 [..., N, D], delta_V float32 [..., D])."""
+    v = _f16(v); N, D = v.shape[-2:]
+    lead = v.shape[:-2]; S = int(np.prod(lead)) if lead else 1
+    vq = np.zeros(v.shape, np.int8); sc = np.zeros(lead + (D,), np.float32)
+    _L().sage_oracle_quant_v(_p(v), ctypes.c_int(1), ctypes.c_int(S), ctypes.c_int(N), ctypes.c_int(D),
+                             _p(vq), _p(sc))
+    return vq, sc
+
+
+def attn_pv8(qq, q_scale, kq, k_scale, vq, v_scale, causal: bool, block_q: int, block_k: int,
+             gran_q: int | None = None, gran_k: int | None = None, return_l: bool = False):
+    """The kernels with an INT8 second product (Section 4.3; SAGEAttn-vB, or -vT with gran 1) on whole
+    [B, H, N, D] tensors -> fp16 output (and, if asked, the final row sums l [B, H, N])."""
+    gran_q = block_q if gran_q is None else gran_q
+    gran_k = block_k if gran_k is None else gran_k
+    vq = np.ascontiguousarray(vq, np.int8); B, H, N, D = vq.shape
+    qq = np.ascontiguousarray(qq, np.int8); kq = np.ascontiguousarray(kq, np.int8)
+    q_scale = np.ascontiguousarray(q_scale, np.float32); k_scale = np.ascontiguousarray(k_scale, np.float32)
+    v_scale = np.ascontiguousarray(v_scale, np.float32)
+    assert qq.shape == (B, H, N, D) and kq.shape == (B, H, N, D) and v_scale.shape == (B, H, D)
+    assert q_scale.shape == (B, H, nblocks(N, gran_q)) and k_scale.shape == (B, H, nblocks(N, gran_k))
+    o = np.zeros((B, H, N, D), np.float16)
+    lsum = np.zeros((B, H, N), np.float32)
+    _L().sage_oracle_attn_pv8_g(_p(qq), _p(q_scale), _p(kq), _p(k_scale), _p(vq), _p(v_scale),
+                                *map(ctypes.c_int, (B, H, N, D, int(causal), block_q, block_k, gran_q, gran_k)),
+                                _p(o), _p(lsum))
+    return (o, lsum) if return_l else o
+
+
+def attn_pv8_slab(qq, q_scale, kq, k_scale, vq, v_scale, causal: bool, block_q: int, block_k: int,
+                  q_blocks=None, gran_q: int | None = None, gran_k: int | None = None, return_l: bool = False):
+    """attn_pv8 on one slab [N, D] for the listed Q blocks (all if None); other rows stay zero."""
+    gran_q = block_q if gran_q is None else gran_q
+    gran_k = block_k if gran_k is None else gran_k
+    vq = np.ascontiguousarray(vq, np.int8); N, D = vq.shape
+    qq = np.ascontiguousarray(qq, np.int8); kq = np.ascontiguousarray(kq, np.int8)
+    q_scale = np.ascontiguousarray(q_scale, np.float32); k_scale = np.ascontiguousarray(k_scale, np.float32)
+    v_scale = np.ascontiguousarray(v_scale, np.float32)
+    assert q_scale.shape == (nblocks(N, gran_q),) and k_scale.shape == (nblocks(N, gran_k),)
+    assert v_scale.shape == (D,)
+    o = np.zeros((N, D), np.float16); lsum = np.zeros((N,), np.float32)
+    if q_blocks is None:
+        blocks, nb = None, -1
+    else:
+        blocks = np.ascontiguousarray(q_blocks, np.int32); nb = len(blocks)
+        assert nb == 0 or (blocks.min() >= 0 and blocks.max() < nblocks(N, block_q))
+    _L().sage_oracle_attn_pv8_slab_g(_p(qq), _p(q_scale), _p(kq), _p(k_scale), _p(vq), _p(v_scale),
+                                     *map(ctypes.c_int, (N, D, int(causal), block_q, block_k, gran_q, gran_k)),
+                                     _p(blocks) if blocks is not None else None, ctypes.c_int(nb),
+                                     _p(o), _p(lsum))
+    return (o, lsum) if return_l else o
+
+
 def attn_l1_slab(qq, q_scale, kq, k_scale, v, causal: bool, block_q: int, block_k: int,
                  row0: int = 0, nrows: int | None = None) -> np.ndarray:
     """Quantized scores, exact fp64 softmax and P V (Section 4.1 with P, V unquantized).

@@ -4,7 +4,7 @@
  * Plain, slow, readable C that follows the paper's definitions step by step:
  *   Section 3.1 (attention, FlashAttention-2 online softmax), Section 3.2 (dynamic
  *   quantizers), Section 4.1 (quantized-attention formulation), Section 4.2 (smoothing K),
- *   Section 4.4 (FP16 P~V), Section 4.6 (1/sqrt(d) folded into Q before quantizing) and
+ *   Section 4.3 (INT8 P~ and V, the -vB / -vT kernels), Section 4.4 (FP16 P~V), Section 4.6 (1/sqrt(d) folded into Q before quantizing) and
  *   Algorithm 1 (SAGEAttn-B).
  *
  * Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may call this file.
@@ -25,7 +25,8 @@
  *   L0  exact fp64 softmax(Q K^T sm_scale [+ causal mask]) V on the fp16 input values.
  *   L1  quantized S = dQ dK (Q^ K^^T), then exact fp64 two-pass softmax and fp64 P V.
  *   L2  Algorithm 1 as written: block loop, fp32 online softmax, P~ -> fp16, fp32 (or
- *       emulated fp16) accumulation, final division, fp16 output.
+ *       emulated fp16) accumulation, final division, fp16 output; and the same loop with the
+ *       INT8 second product of Section 4.3 (codes of P~ with the static scale 1/127, V per channel).
  *
  * Status of pins: every function here is pinned by tests/test_oracle_*.py against closed
  * forms, brute force, invariants and a hand-worked example (tests/golden/).  The output
@@ -366,6 +367,141 @@ void sage_oracle_attn_l2(const int8_t* qq, const float* q_scale, const int8_t* k
                          int block_q, int block_k, unsigned flags, uint16_t* o) {
     sage_oracle_attn_l2_g(qq, q_scale, kq, k_scale, v, B, H, N, D, causal, block_q, block_k,
                           block_q, block_k, flags, o);
+}
+
+/* ------------------------------------------------------------------ Section 4.3: INT8 P~ and V (SAGEAttn-vB / -vT) */
+
+/* psi_V, the per-channel quantizer of Section 3.2 applied to V (Section 4.3): one scale per channel
+ * c of one (batch, head) slab v[N,D], taken over ALL N tokens (also when the mask is causal: the
+ * scale belongs to the tensor, not to a query).  Same arithmetic as the per-block quantizer:
+ * delta[c] = fl32(amax_c / 127), V^[t,c] = clamp(rne(fl32(v[t,c] * fl32(127 / amax_c)))), an
+ * all-zero channel gives delta = 0 and V^ = 0.  vq is token-major [N,D] like v. */
+void sage_oracle_quant_v_slab(const uint16_t* v, int N, int D, int8_t* vq, float* v_scale) {
+    for (int c = 0; c < D; ++c) {
+        float amax = 0.0f;
+        for (int t = 0; t < N; ++t) {
+            float a = fabsf(f16_to_f32(v[(int64_t)t * D + c]));
+            if (a > amax) amax = a;
+        }
+        volatile float d = amax / 127.0f;
+        volatile float r = amax > 0.0f ? 127.0f / amax : 0.0f;
+        v_scale[c] = d;
+        for (int t = 0; t < N; ++t) {
+            volatile float scaled = f16_to_f32(v[(int64_t)t * D + c]) * r;
+            float rounded = nearbyintf(scaled);              /* ties to even */
+            if (rounded > 127.0f) rounded = 127.0f;
+            if (rounded < -127.0f) rounded = -127.0f;
+            vq[(int64_t)t * D + c] = (int8_t)rounded;
+        }
+    }
+}
+void sage_oracle_quant_v(const uint16_t* v, int B, int H, int N, int D, int8_t* vq, float* v_scale) {
+#pragma omp parallel for schedule(dynamic)
+    for (int s = 0; s < B * H; ++s)
+        sage_oracle_quant_v_slab(v + (int64_t)s * N * D, N, D, vq + (int64_t)s * N * D, v_scale + (int64_t)s * D);
+}
+
+/* One Q block of the kernels with an INT8 second product (Section 4.3, the -vB / -vT rows of the
+ * kernel table in Section 4.5).  Algorithm 1 with its P~V line replaced:
+ *   P^ = rne(fl32(P~ * 127))            psi_P: per-block with the static scale 1/127 (row maxima of
+ *                                       P~ are <= 1 because the running maximum is subtracted)
+ *   A  = P^ V^_j                        exact int32
+ *   O  = alpha * O + fl32(fl32((float)A * (1/127)) * delta_V[c])
+ * m, l and alpha are those of Algorithm 1: l sums the fp32 P~, not the codes.
+ * lsum (may be NULL) receives the final l of every row of the block (rows i*bq ...), which bounds
+ * what one code of P^ is worth in the output: delta_V[c] * |V^| / (127 l) * 127 <= delta_V[c] / l. */
+static void l2_pv8_q_block(const int8_t* qq, const float* q_scale, const int8_t* kq, const float* k_scale,
+                           const int8_t* vq, const float* v_scale, int N, int D, int causal,
+                           int bq, int bkv, int gq, int gk, int i, uint16_t* o, float* lsum) {
+    int r0 = i * bq, r1 = r0 + bq < N ? r0 + bq : N, nr = r1 - r0;
+    int Tn = (N + bkv - 1) / bkv;
+    float* m = (float*)malloc(sizeof(float) * nr);
+    float* l = (float*)malloc(sizeof(float) * nr);
+    float* O = (float*)calloc((size_t)nr * D, sizeof(float));
+    float* S = (float*)malloc(sizeof(float) * (size_t)nr * bkv);
+    int32_t* Pq = (int32_t*)malloc(sizeof(int32_t) * (size_t)bkv);
+    const float inv127 = 1.0f / 127.0f;
+    for (int a = 0; a < nr; ++a) { m[a] = -INFINITY; l[a] = 0.0f; }
+
+    for (int j = 0; j < Tn; ++j) {
+        int c0 = j * bkv, c1 = c0 + bkv < N ? c0 + bkv : N, nc = c1 - c0;
+        if (causal && c0 > r1 - 1) break;
+        for (int a = 0; a < nr; ++a)
+            for (int b = 0; b < nc; ++b) {
+                int32_t acc = 0;
+                for (int c = 0; c < D; ++c)
+                    acc += (int32_t)qq[(int64_t)(r0 + a) * D + c] * (int32_t)kq[(int64_t)(c0 + b) * D + c];
+                volatile float t1 = (float)acc * q_scale[(r0 + a) / gq];
+                volatile float t2 = t1 * k_scale[(c0 + b) / gk];
+                S[a * bkv + b] = (causal && (c0 + b) > (r0 + a)) ? -INFINITY : t2;
+            }
+        for (int a = 0; a < nr; ++a) {
+            float m_old = m[a], m_new = m_old;
+            for (int b = 0; b < nc; ++b) if (S[a * bkv + b] > m_new) m_new = S[a * bkv + b];
+            float alpha = (m_old == -INFINITY) ? 0.0f : expf(m_old - m_new);
+            float rowsum = 0.0f;
+            for (int b = 0; b < nc; ++b) {
+                float p = (S[a * bkv + b] == -INFINITY) ? 0.0f : expf(S[a * bkv + b] - m_new);
+                volatile float scaled = p * 127.0f;
+                Pq[b] = (int32_t)nearbyintf(scaled);             /* 0 .. 127 */
+                volatile float acc = rowsum + p;
+                rowsum = acc;
+            }
+            volatile float lnew = alpha * l[a];
+            lnew = lnew + rowsum;
+            l[a] = lnew;
+            m[a] = m_new;
+            for (int c = 0; c < D; ++c) {
+                int32_t A = 0;
+                for (int b = 0; b < nc; ++b) A += Pq[b] * (int32_t)vq[(int64_t)(c0 + b) * D + c];
+                volatile float t1 = (float)A * inv127;
+                volatile float t2 = t1 * v_scale[c];
+                volatile float oc = alpha * O[(int64_t)a * D + c];
+                volatile float sum = oc + t2;
+                O[(int64_t)a * D + c] = sum;
+            }
+        }
+    }
+    for (int a = 0; a < nr; ++a) {
+        for (int c = 0; c < D; ++c) {
+            volatile float q = O[(int64_t)a * D + c] / l[a];
+            o[(int64_t)(r0 + a) * D + c] = f32_to_f16(q, 0);
+        }
+        if (lsum) lsum[r0 + a] = l[a];
+    }
+    free(m); free(l); free(O); free(S); free(Pq);
+}
+
+/* One slab, a list of Q blocks (nblocks < 0: all).  gran_q / gran_k as in the FP16 variant:
+ * block sizes for -vB, 1 for -vT.  lsum [N] may be NULL. */
+void sage_oracle_attn_pv8_slab_g(const int8_t* qq, const float* q_scale, const int8_t* kq,
+                                 const float* k_scale, const int8_t* vq, const float* v_scale,
+                                 int N, int D, int causal, int block_q, int block_k, int gran_q, int gran_k,
+                                 const int* blocks, int nblocks, uint16_t* o, float* lsum) {
+    int Tm = (N + block_q - 1) / block_q;
+    int n = nblocks < 0 ? Tm : nblocks;
+#pragma omp parallel for schedule(dynamic)
+    for (int u = 0; u < n; ++u) {
+        int i = nblocks < 0 ? u : blocks[u];
+        l2_pv8_q_block(qq, q_scale, kq, k_scale, vq, v_scale, N, D, causal, block_q, block_k,
+                       gran_q, gran_k, i, o, lsum);
+    }
+}
+
+/* Whole tensors [B,H,N,D]; v_scale [B,H,D]; lsum [B,H,N] or NULL. */
+void sage_oracle_attn_pv8_g(const int8_t* qq, const float* q_scale, const int8_t* kq, const float* k_scale,
+                            const int8_t* vq, const float* v_scale, int B, int H, int N, int D, int causal,
+                            int block_q, int block_k, int gran_q, int gran_k, uint16_t* o, float* lsum) {
+    int Tm = (N + block_q - 1) / block_q;
+    int nsq = (N + gran_q - 1) / gran_q, nsk = (N + gran_k - 1) / gran_k;
+    int64_t units = (int64_t)B * H * Tm;
+#pragma omp parallel for schedule(dynamic)
+    for (int64_t u = 0; u < units; ++u) {
+        int64_t s = u / Tm; int i = (int)(u % Tm);
+        l2_pv8_q_block(qq + s * N * D, q_scale + s * nsq, kq + s * N * D, k_scale + s * nsk,
+                       vq + s * N * D, v_scale + s * D, N, D, causal, block_q, block_k, gran_q, gran_k,
+                       i, o + s * N * D, lsum ? lsum + s * N : NULL);
+    }
 }
 
 /* ------------------------------------------------------------------ L1: quantized S, exact softmax */

@@ -29,6 +29,11 @@ void sage_oracle_attn_l2_slab_g(const int8_t*, const float*, const int8_t*, cons
 void sage_oracle_attn_l1_slab(const int8_t*, const float*, const int8_t*, const float*, const uint16_t*, int, int, int,
                               int, int, int, int, double*);
 void sage_oracle_attn_l0_slab(const float*, const float*, const float*, int, int, int, double, int, int, double*);
+void sage_oracle_quant_v(const uint16_t*, int, int, int, int, int8_t*, float*);
+void sage_oracle_attn_pv8_g(const int8_t*, const float*, const int8_t*, const float*, const int8_t*, const float*, int, int,
+                            int, int, int, int, int, int, int, uint16_t*, float*);
+void sage_oracle_attn_pv8_slab_g(const int8_t*, const float*, const int8_t*, const float*, const int8_t*, const float*,
+                                 int, int, int, int, int, int, int, const int*, int, uint16_t*, float*);
 
 static uint32_t rng = 12345u;
 static float unit(void) { rng = rng * 1664525u + 1013904223u; return (float)(rng >> 8) / 16777216.0f * 4.0f - 2.0f; }
@@ -56,6 +61,13 @@ static void one_case(int B, int H, int N, int D, int bq, int bk, int gq, int gk,
     if (gq == bq && gk == bk) sage_oracle_attn_l2(qq, qs, kq, ks, v, B, H, N, D, causal, bq, bk, 2u, o);
     int Tm = (N + bq - 1) / bq, blocks[2] = {Tm - 1, 0};
     sage_oracle_attn_l2_slab_g(qq, qs, kq, ks, v, N, D, causal, bq, bk, gq, gk, 0, blocks, 2, o);
+    int8_t* vq = malloc(E);
+    float *vs = malloc(sizeof(float) * B * H * D), *ls = malloc(sizeof(float) * B * H * N);
+    sage_oracle_quant_v(v, B, H, N, D, vq, vs);
+    sage_oracle_attn_pv8_g(qq, qs, kq, ks, vq, vs, B, H, N, D, causal, bq, bk, gq, gk, o, ls);
+    sage_oracle_attn_pv8_slab_g(qq, qs, kq, ks, vq, vs, N, D, causal, bq, bk, gq, gk, blocks, 2, o, NULL);
+    *sum += ls[B * H * N - 1] + vs[0];
+    free(vq); free(vs); free(ls);
     int row0 = N / 3, nrows = N - row0;
     double* o1 = malloc(sizeof(double) * nrows * D);
     sage_oracle_attn_l1_slab(qq, qs, kq, ks, v, N, D, causal, gq, gk, row0, nrows, o1);
