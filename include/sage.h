@@ -134,6 +134,43 @@ int sage_attn_fwd(const int8_t* q_i8, const float* q_scale,
                   int block_q, int block_k, void* stream);
 
 /*
+ * psi_V of Section 4.3 for the kernels with an INT8 second product (SAGEAttn-vB / -vT, Section 4.5):
+ * the per-channel quantizer of Section 3.2, one scale per channel of every (batch, head) slab, taken
+ * over all N tokens; delta_V[c] = amax_c / 127, V^[t,c] = clamp(rne(V[t,c] * (127 / amax_c)), -127, 127);
+ * an all-zero channel gives delta_V = 0, V^ = 0.
+ *   v_f16    in  [B,H,N,D] fp16
+ *   v_i8t    out [B,H,D,Np] int8: V^ TRANSPOSED, channel-major, Np = sage_quant_v_pitch(N) =
+ *            64 * ceil(N / 64) tokens per channel row; tokens N .. Np-1 are written as 0
+ *   v_scale  out [B,H,D] fp32
+ *   workspace   device, >= sage_quant_v_workspace(B,H,N,D) bytes, 4-byte aligned; scratch, contents
+ *               undefined on entry and exit
+ * Same ownership, stream and error conventions as the calls above.
+ */
+size_t sage_quant_v_workspace(int B, int H, int N, int D);
+int sage_quant_v_pitch(int N);
+int sage_quant_v(const void* v_f16, int8_t* v_i8t, float* v_scale,
+                 void* workspace, size_t workspace_bytes,
+                 int B, int H, int N, int D, void* stream);
+
+/*
+ * The loop of Algorithm 1 with the second product of Section 4.3: P~ is quantized per block with
+ * the static scale 1/127 (its row maxima are 1), P^ V^ is an INT8 product with an int32 result,
+ * dequantized with 1/127 and delta_V[c].  m, l and the rescaling are those of Algorithm 1 (l sums the
+ * unrounded P~).  block_q / block_k as in sage_attn_fwd: block sizes give SAGEAttn-vB, 1 gives -vT.
+ *   q_i8, q_scale, k_i8, k_scale   as for sage_attn_fwd
+ *   v_i8t, v_scale                 from sage_quant_v (same N)
+ *   o_f16   out [B,H,N,D] fp16
+ * The codes of P~ depend on the last bits of the exponential, so two correct implementations can
+ * differ by one code in a few elements; one code of one key is worth at most delta_V[c] / l in the
+ * output (l = the row's softmax denominator relative to its maximum, >= 1).
+ */
+int sage_attn_pv_int8_fwd(const int8_t* q_i8, const float* q_scale,
+                          const int8_t* k_i8, const float* k_scale,
+                          const int8_t* v_i8t, const float* v_scale, void* o_f16,
+                          int B, int H, int N, int D, int causal, float sm_scale,
+                          int block_q, int block_k, void* stream);
+
+/*
  * Test hook: the raw int32 scores S^ = Q^ K^^T (Algorithm 1, the Matmul inside the S update)
  * produced by the same matrix-instruction code path as sage_attn_fwd, without mask.
  *   s_i32   out [B,H,N,N] int32 -- O(N^2) memory: meant for small N or for sub-problems.

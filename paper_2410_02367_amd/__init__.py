@@ -9,8 +9,12 @@ from .binding import (  # noqa: F401
     lib_path,
     load,
     sage_attn_fwd,
+    sage_attn_pv_int8_fwd,
     sage_attn_qk_i32_debug,
     sage_quant_q,
+    sage_quant_v,
+    sage_quant_v_pitch,
+    sage_quant_v_workspace,
     sage_rope_quant_q,
     sage_rope_smooth_quant_k,
     sage_smooth_quant_k,

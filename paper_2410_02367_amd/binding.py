@@ -12,7 +12,8 @@ _lib = None
 
 EXPORTS = ("sage_status_string", "sage_quant_q", "sage_smooth_quant_k_workspace",
            "sage_smooth_quant_k", "sage_rope_quant_q", "sage_rope_smooth_quant_k",
-           "sage_attn_fwd", "sage_attn_qk_i32_debug")
+           "sage_attn_fwd", "sage_attn_qk_i32_debug",
+           "sage_quant_v_workspace", "sage_quant_v_pitch", "sage_quant_v", "sage_attn_pv_int8_fwd")
 
 
 class SageError(RuntimeError):
@@ -55,6 +56,15 @@ def load() -> ctypes.CDLL:
                                   c_int, c_int, c_int, c_int, c_int, c_float, c_int, c_int, c_void_p]
     lib.sage_attn_qk_i32_debug.restype = c_int
     lib.sage_attn_qk_i32_debug.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_void_p]
+    lib.sage_quant_v_workspace.restype = c_size_t
+    lib.sage_quant_v_workspace.argtypes = [c_int, c_int, c_int, c_int]
+    lib.sage_quant_v_pitch.restype = c_int
+    lib.sage_quant_v_pitch.argtypes = [c_int]
+    lib.sage_quant_v.restype = c_int
+    lib.sage_quant_v.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_int, c_int, c_int, c_int, c_void_p]
+    lib.sage_attn_pv_int8_fwd.restype = c_int
+    lib.sage_attn_pv_int8_fwd.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                          c_int, c_int, c_int, c_int, c_int, c_float, c_int, c_int, c_void_p]
     _lib = lib
     return lib
 
@@ -183,6 +193,56 @@ def sage_attn_fwd(q_i8, q_scale, k_i8, k_scale, v, causal: bool, sm_scale: float
                               _stream(stream))
     if st != 0:
         raise SageError(st, "sage_attn_fwd")
+    return out
+
+
+def sage_quant_v_workspace(B: int, H: int, N: int, D: int) -> int:
+    return int(load().sage_quant_v_workspace(B, H, N, D))
+
+
+def sage_quant_v_pitch(N: int) -> int:
+    return int(load().sage_quant_v_pitch(N))
+
+
+def sage_quant_v(v: torch.Tensor, v_i8t=None, v_scale=None, workspace=None, stream=None):
+    """psi_V(V), per channel -> (v_i8t int8 [B,H,D,Np] (transposed, Np = sage_quant_v_pitch(N)), v_scale [B,H,D] fp32)."""
+    B, H, N, D = v.shape
+    Np = sage_quant_v_pitch(N)
+    if v_i8t is None:
+        v_i8t = torch.empty((B, H, D, Np), dtype=torch.int8, device=v.device)
+    if v_scale is None:
+        v_scale = torch.empty((B, H, D), dtype=torch.float32, device=v.device)
+    need = sage_quant_v_workspace(B, H, N, D)
+    if workspace is None:
+        workspace = torch.empty((max(need, 4) + 3) // 4, dtype=torch.int32, device=v.device)
+    ws_bytes = workspace.numel() * workspace.element_size()
+    if tuple(v_i8t.shape) != (B, H, D, Np):
+        raise TypeError(f"v_i8t: expected shape {(B, H, D, Np)}")
+    st = load().sage_quant_v(_dev(v, torch.float16, "v"), _dev(v_i8t, torch.int8, "v_i8t"),
+                             _dev(v_scale, torch.float32, "v_scale"), workspace.data_ptr(), ws_bytes,
+                             B, H, N, D, _stream(stream))
+    if st != 0:
+        raise SageError(st, "sage_quant_v")
+    return v_i8t, v_scale
+
+
+def sage_attn_pv_int8_fwd(q_i8, q_scale, k_i8, k_scale, v_i8t, v_scale, causal: bool, sm_scale: float,
+                          block_q: int = 128, block_k: int = 64, out=None, stream=None):
+    """Algorithm 1's loop with the INT8 second product of Section 4.3 (SAGEAttn-vB; block sizes 1: -vT)
+    on pre-quantized Q^, K^ and V^^T -> O [B,H,N,D] fp16."""
+    B, H, N, D = q_i8.shape
+    if tuple(v_i8t.shape) != (B, H, D, sage_quant_v_pitch(N)):
+        raise TypeError(f"v_i8t: expected shape {(B, H, D, sage_quant_v_pitch(N))}")
+    if out is None:
+        out = torch.empty((B, H, N, D), dtype=torch.float16, device=q_i8.device)
+    st = load().sage_attn_pv_int8_fwd(_dev(q_i8, torch.int8, "q_i8"), _dev(q_scale, torch.float32, "q_scale"),
+                                      _dev(k_i8, torch.int8, "k_i8"), _dev(k_scale, torch.float32, "k_scale"),
+                                      _dev(v_i8t, torch.int8, "v_i8t"), _dev(v_scale, torch.float32, "v_scale"),
+                                      _dev(out, torch.float16, "out"),
+                                      B, H, N, D, int(bool(causal)), float(sm_scale), int(block_q), int(block_k),
+                                      _stream(stream))
+    if st != 0:
+        raise SageError(st, "sage_attn_pv_int8_fwd")
     return out
 
 

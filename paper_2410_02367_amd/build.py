@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsage.so")
-SOURCES = ["sage_api.hip", "sage_prepass.hip", "sage_attn.hip"]
+SOURCES = ["sage_api.hip", "sage_prepass.hip", "sage_prepass_v.hip", "sage_attn.hip", "sage_attn_pv8.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

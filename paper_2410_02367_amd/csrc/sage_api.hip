@@ -118,6 +118,42 @@ int sage_attn_fwd(const int8_t* q_i8, const float* q_scale, const int8_t* k_i8, 
     return e == hipSuccess ? SAGE_OK : SAGE_ERR_LAUNCH;
 }
 
+size_t sage_quant_v_workspace(int B, int H, int N, int D) {
+    (void)N;
+    if (B <= 0 || H <= 0 || D <= 0) return 0;
+    return (size_t)B * H * D * sizeof(unsigned);
+}
+
+int sage_quant_v_pitch(int N) { return N <= 0 ? 0 : 64 * ((N + 63) / 64); }
+
+int sage_quant_v(const void* v_f16, int8_t* v_i8t, float* v_scale, void* workspace, size_t workspace_bytes,
+                 int B, int H, int N, int D, void* stream) {
+    if (!v_f16 || !v_i8t || !v_scale || !workspace) return SAGE_ERR_NULL;
+    if (int e = check_shape(B, H, N, D)) return e;
+    if (workspace_bytes < sage_quant_v_workspace(B, H, N, D)) return SAGE_ERR_WORKSPACE;
+    if (!aligned(v_f16, 16) || !aligned(v_i8t, 16) || !aligned(v_scale, 16) || !aligned(workspace, 4))
+        return SAGE_ERR_ALIGN;
+    hipError_t e = sage::launch_quant_v(v_f16, v_i8t, v_scale, (unsigned*)workspace, B * H, N, D, (hipStream_t)stream);
+    return e == hipSuccess ? SAGE_OK : SAGE_ERR_LAUNCH;
+}
+
+int sage_attn_pv_int8_fwd(const int8_t* q_i8, const float* q_scale, const int8_t* k_i8, const float* k_scale,
+                          const int8_t* v_i8t, const float* v_scale, void* o_f16,
+                          int B, int H, int N, int D, int causal, float sm_scale,
+                          int block_q, int block_k, void* stream) {
+    if (!q_i8 || !q_scale || !k_i8 || !k_scale || !v_i8t || !v_scale || !o_f16) return SAGE_ERR_NULL;
+    if (int e = check_shape(B, H, N, D)) return e;
+    if (!quant_block_ok(block_q)) return SAGE_ERR_UNSUPPORTED;
+    if (block_k != 1 && block_k != 64 && block_k != 128) return SAGE_ERR_UNSUPPORTED;
+    if (!std::isfinite(sm_scale) || !(sm_scale > 0.0f)) return SAGE_ERR_VALUE;
+    if (!aligned(q_i8, 16) || !aligned(k_i8, 16) || !aligned(v_i8t, 16) || !aligned(o_f16, 16) ||
+        !aligned(q_scale, 4) || !aligned(k_scale, 4) || !aligned(v_scale, 16))
+        return SAGE_ERR_ALIGN;
+    hipError_t e = sage::launch_attn_pv8(q_i8, q_scale, k_i8, k_scale, v_i8t, v_scale, o_f16, B * H, N, D,
+                                         causal ? 1 : 0, block_q, block_k, (hipStream_t)stream);
+    return e == hipSuccess ? SAGE_OK : SAGE_ERR_LAUNCH;
+}
+
 int sage_attn_qk_i32_debug(const int8_t* q_i8, const int8_t* k_i8, int32_t* s_i32,
                            int B, int H, int N, int D, void* stream) {
     if (!q_i8 || !k_i8 || !s_i32) return SAGE_ERR_NULL;

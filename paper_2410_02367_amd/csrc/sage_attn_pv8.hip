@@ -1,0 +1,297 @@
+// SageAttention forward kernel with an INT8 second product for gfx950 (Section 4.3: P~ quantized
+// per block with the static scale 1/127, V per channel; the SAGEAttn-vB / -vT kernels of Section 4.5).
+//
+// Same decomposition as the FP16-P~V kernel, in its plain form: a workgroup of 4 wavefronts owns 128
+// query rows (32 per wavefront), K^ and V^^T tiles of 64 keys are double-buffered in LDS, scores are
+// computed transposed (S^T = K^ Q^^T) so that a lane owns one query, and O^T = V^^T P^^T.  Both
+// products use the 32x32x32 INT8 matrix instruction.  What is specific to this variant:
+//
+//   - Key order.  A lane's 16 result registers of a 32-key score block are the rows
+//     8*(r/4) + 4*(lane/32) + r%4 of the instruction, but as the B operand of the second product
+//     a lane must hold 16 CONSECUTIVE contraction indices.  The rows of K^ are therefore fed in a
+//     permuted order (row 8g + 4h + b of the instruction is key 16h + 4g + b of the block): register
+//     r of lane half h then is key 16h + r, the 16 codes of a lane pack into the B operand as they
+//     are, and the matching A operand is 16 consecutive tokens of one channel -- one 16-byte read of
+//     the channel-major V^^T tile.  The permutation is applied where the K^ tile is written to LDS.
+//   - Exact running maximum.  The codes round(127 exp(S - m)) depend on m, so m is the exact
+//     running maximum of the dequantized scores as in the recursion of Section 3.1 (no lazy update, no
+//     grid rounding), and the largest code of a row is 127.
+//   - Integer accumulation between maximum changes.  An int32 accumulator cannot be rescaled, so it
+//     is flushed into an fp32 accumulator (O = (O + A) * alpha, A = 0) whenever a row of the wavefront
+//     raises its maximum (and every 1024 tiles, long before 64 * 127 * 127 * tiles reaches 2^31);
+//     between two flushes alpha = 1 and the tiles' products add exactly in the matrix instruction.
+//     The per-channel scale delta_V and the static 1/127 are constant over the row's whole loop and
+//     are applied once, in the epilogue; l is carried as the sum of 127 P~ (fp32, unrounded P~),
+//     which cancels the 1/127.
+//   - 127 P~ = exp2(S' - (m' - log2 127)) comes out of the exponential directly; adding 1.5 * 2^23
+//     rounds it to the nearest integer (ties to even) and leaves the code in the low byte.
+//
+// This variant is written with compiler builtins and compiler scheduling; it trades the second
+// product's instruction count (half) for more VALU work per score (conversion, rounding, packing,
+// flushes), which on this chip costs more than it saves -- see the measurements in the design notes.
+#include "sage_internal.h"
+
+namespace sage {
+
+typedef int p4i __attribute__((ext_vector_type(4)));
+typedef int p16i __attribute__((ext_vector_type(16)));
+typedef float p16f __attribute__((ext_vector_type(16)));
+typedef _Float16 p4h __attribute__((ext_vector_type(4)));
+
+namespace {
+constexpr float PV8_LOG2E = 1.4426950408889634f;
+constexpr float PV8_LOG2_127 = 6.988684686772166f;
+constexpr float PV8_ROUND = 12582912.0f;          // 1.5 * 2^23: x + this rounds x to an integer in the low mantissa bits
+constexpr int PV8_FLUSH_TILES = 1024;
+
+__device__ __forceinline__ float lane32_partner(float v) { return __shfl_xor(v, 32, 64); }
+__device__ __forceinline__ int k_perm(int row) {
+    // LDS row of key `row` of a tile: key 32kb + 16h + 4g + b  ->  32kb + 8g + 4h + b
+    return (row & 32) | ((row & 12) << 1) | ((row & 16) >> 2) | (row & 3);
+}
+template <int D> __device__ __forceinline__ int k_swz8(int row) { return D == 128 ? ((row >> 1) & 7) : ((row >> 2) & 3); }
+__device__ __forceinline__ int vt_swz(int ch) { return (ch >> 2) & 3; }
+}  // namespace
+
+template <int D, bool CAUSAL, bool KTOK>
+__global__ void __launch_bounds__(256, 2)
+sage_attn_pv8_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
+                     const int8_t* __restrict__ ki, const float* __restrict__ ksc,
+                     const int8_t* __restrict__ vt, const float* __restrict__ vsc,
+                     _Float16* __restrict__ og,
+                     int N, int Np, int shift_q, int shift_k, int tiles_q, int per_xcd, long total_tiles) {
+    constexpr int NT = 256, QTILE = 128, KT = 64;
+    constexpr int KS = D / 32, DT = D / 32;
+    constexpr int KB = KT * D, VB = D * KT;            // bytes per K^ tile / V^^T tile
+    constexpr int KCH = D / 16;                        // 16-byte chunks per K^ row
+    constexpr int KL = KB / 16 / NT, VL = VB / 16 / NT;
+    static_assert(KL >= 1 && VL >= 1, "tile loads cover whole workgroups");
+    __shared__ __attribute__((aligned(16))) unsigned char lds[2 * (KB + VB)];
+
+    // workgroup -> (slab, query tile): contiguous ranges per XCD, heaviest query tiles first
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const long gidx = (long)xcd * per_xcd + slot;
+    if (slot >= per_xcd || gidx >= total_tiles) return;
+    const int bh = (int)(gidx / tiles_q);
+    const int qt = tiles_q - 1 - (int)(gidx % tiles_q);
+
+    const int t = threadIdx.x, lane = t & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int ql = lane & 31, h = lane >> 5;
+    const int qrow0 = qt * QTILE + wave * 32;
+    const int q_row = qrow0 + ql;
+    const size_t slab = (size_t)bh * N;
+    const int nbq = (N + (1 << shift_q) - 1) >> shift_q, nbk = (N + (1 << shift_k) - 1) >> shift_k;
+
+    p4i qreg[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+        qreg[ks] = (p4i){0, 0, 0, 0};
+        if (q_row < N) qreg[ks] = *(const p4i*)(qi + (slab + q_row) * D + ks * 32 + h * 16);
+    }
+    const float dq = qsc[(size_t)bh * nbq + ((q_row < N ? q_row : N - 1) >> shift_q)] * PV8_LOG2E;
+    const float* __restrict__ ksc_bh = ksc + (size_t)bh * nbk;
+
+    const int kv_tiles_all = (N + KT - 1) / KT;
+    int T = kv_tiles_all, Tw = kv_tiles_all;
+    if (CAUSAL) {
+        int last = (qt * QTILE + QTILE - 1) / KT + 1;
+        T = last < kv_tiles_all ? last : kv_tiles_all;
+        last = (qrow0 + 31) / KT + 1;
+        Tw = last < T ? last : T;
+    }
+
+    // ---- tile staging: global -> registers (in flight during the previous tile's work) -> LDS
+    const int8_t* k_src[KL]; int k_row[KL], k_dst[KL];
+    const int8_t* v_src[VL]; int v_dst[VL];
+#pragma unroll
+    for (int i = 0; i < KL; ++i) {
+        const int vidx = t + NT * i, row = vidx / KCH, c = vidx % KCH, p = k_perm(row);
+        k_row[i] = row;
+        k_src[i] = ki + (slab + row) * D + c * 16;
+        k_dst[i] = p * D + ((c ^ k_swz8<D>(p)) * 16);
+    }
+#pragma unroll
+    for (int i = 0; i < VL; ++i) {
+        const int vidx = t + NT * i, ch = vidx >> 2, c = vidx & 3;
+        v_src[i] = vt + ((size_t)bh * D + ch) * Np + c * 16;
+        v_dst[i] = ch * KT + ((c ^ vt_swz(ch)) * 16);
+    }
+    p4i k_st[KL], v_st[VL];
+    auto fetch = [&](int j) {
+#pragma unroll
+        for (int i = 0; i < KL; ++i) {
+            k_st[i] = (p4i){0, 0, 0, 0};
+            if (j * KT + k_row[i] < N) k_st[i] = *(const p4i*)(k_src[i] + (size_t)j * KT * D);
+        }
+#pragma unroll
+        for (int i = 0; i < VL; ++i) v_st[i] = *(const p4i*)(v_src[i] + (size_t)j * KT);      // j * 64 + 63 < Np
+    };
+    auto stage = [&](int buf) {
+        unsigned char* kb = lds + buf * (KB + VB);
+#pragma unroll
+        for (int i = 0; i < KL; ++i) *(p4i*)(kb + k_dst[i]) = k_st[i];
+#pragma unroll
+        for (int i = 0; i < VL; ++i) *(p4i*)(kb + KB + v_dst[i]) = v_st[i];
+    };
+
+    // ---- operand read offsets (per lane, inside a buffer)
+    int k_rd[2][KS], v_rd[DT][2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const int p = 32 * kb + ql, c = 2 * ks + h;
+            k_rd[kb][ks] = p * D + ((c ^ k_swz8<D>(p)) * 16);
+        }
+#pragma unroll
+    for (int cb = 0; cb < DT; ++cb)
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+            const int ch = 32 * cb + ql, c = 2 * kb + h;
+            v_rd[cb][kb] = KB + ch * KT + ((c ^ vt_swz(ch)) * 16);
+        }
+
+    p16i acc[DT];          // int32 product since the last flush
+    p16f of[DT];           // fp32 accumulator, in units of (delta_V / 127) relative to the running maximum
+#pragma unroll
+    for (int cb = 0; cb < DT; ++cb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { acc[cb][r] = 0; of[cb][r] = 0.0f; }
+    float m_run = -__builtin_inff(), l127 = 0.0f;
+    int since = 0;
+
+    fetch(0);
+    stage(0);
+    __syncthreads();
+
+    for (int j = 0; j < T; ++j) {
+        const int buf = j & 1;
+        if (j + 1 < T) fetch(j + 1);
+        if (j < Tw) {
+            const unsigned char* tb = lds + buf * (KB + VB);
+            // S^T block kb: keys 64j + 32kb + 16h + r in register r
+            p16i s[2];
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s[kb][r] = 0;
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    const p4i a = *(const p4i*)(tb + k_rd[kb][ks]);
+                    s[kb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, qreg[ks], s[kb], 0, 0, 0);
+                }
+            }
+            // mask: keys past N, and keys after the lane's query when causal (edge tiles only)
+            const bool edge = (j * KT + KT > N) || (CAUSAL && j * KT + KT - 1 > qrow0);
+            // dequantized scores in log2 units, x = S^ * (delta_Q log2 e * delta_K); hidden ones -inf
+            float x[2][16];
+            float tmax = -__builtin_inff();
+            const float sc_tile = dq * ksc_bh[KTOK ? 0 : (j * KT) >> shift_k];
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int kidx = j * KT + 32 * kb + 16 * h + r;
+                    const float sc = KTOK ? dq * ksc_bh[kidx < N ? kidx : N - 1] : sc_tile;
+                    const bool hidden = edge && (kidx >= N || (CAUSAL && kidx > q_row));
+                    x[kb][r] = hidden ? -__builtin_inff() : (float)s[kb][r] * sc;
+                    tmax = __builtin_fmaxf(tmax, x[kb][r]);
+                }
+            tmax = __builtin_fmaxf(tmax, lane32_partner(tmax));
+            const float m_new = __builtin_fmaxf(m_run, tmax);
+            ++since;
+            if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0ull || since >= PV8_FLUSH_TILES) {
+                const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);      // 0 on the first tile (m_run = -inf)
+#pragma unroll
+                for (int cb = 0; cb < DT; ++cb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        of[cb][r] = (of[cb][r] + (float)acc[cb][r]) * alpha;
+                        acc[cb][r] = 0;
+                    }
+                l127 *= alpha;
+                m_run = m_new;
+                since = 0;
+            }
+            const float mb = m_run - PV8_LOG2_127;
+            p4i pk[2];
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    unsigned word = 0u;
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) {
+                        const int r = 4 * w + b;
+                        const float v = __builtin_amdgcn_exp2f(x[kb][r] - mb);          // 127 P~; 0 for hidden keys
+                        l127 += v;
+                        const unsigned code = __builtin_bit_cast(unsigned, v + PV8_ROUND) & 0xffu;
+                        word |= code << (8 * b);
+                    }
+                    pk[kb][w] = (int)word;
+                }
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int cb = 0; cb < DT; ++cb) {
+                    const p4i a = *(const p4i*)(tb + v_rd[cb][kb]);
+                    acc[cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, pk[kb], acc[cb], 0, 0, 0);
+                }
+        }
+        if (j + 1 < T) stage(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue: O = (O_fp32 + A) * delta_V[c] / sum(127 P~)
+    const float lt = l127 + lane32_partner(l127);
+    const float inv = 1.0f / lt;
+    if (q_row < N) {
+        _Float16* orow = og + (slab + q_row) * D;
+        const float* dv = vsc + (size_t)bh * D;
+#pragma unroll
+        for (int cb = 0; cb < DT; ++cb)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int ch = 32 * cb + 8 * g + 4 * h;
+                const float4 d4 = *(const float4*)(dv + ch);
+                const float dd[4] = {d4.x, d4.y, d4.z, d4.w};
+                p4h o4;
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    const float tot = of[cb][4 * g + b] + (float)acc[cb][4 * g + b];
+                    o4[b] = (_Float16)(tot * (dd[b] * inv));
+                }
+                *(p4h*)(orow + ch) = o4;
+            }
+    }
+}
+
+template <int D>
+static hipError_t launch_pv8_d(const int8_t* qq, const float* qscale, const int8_t* kq, const float* kscale,
+                               const int8_t* vt, const float* vscale, void* o, int BH, int N, int causal,
+                               int shift_q, int shift_k, bool ktok, hipStream_t st) {
+    const int tiles_q = (N + 127) / 128, Np = 64 * ((N + 63) / 64);
+    const long total = (long)BH * tiles_q;
+    const int per_xcd = (int)((total + 7) / 8);
+    const dim3 grid((unsigned)(per_xcd * 8)), block(256);
+#define SAGE_PV8(C, K) sage_attn_pv8_kernel<D, C, K><<<grid, block, 0, st>>>( \
+        qq, qscale, kq, kscale, vt, vscale, (_Float16*)o, N, Np, shift_q, shift_k, tiles_q, per_xcd, total)
+    if (causal) { if (ktok) SAGE_PV8(true, true); else SAGE_PV8(true, false); }
+    else        { if (ktok) SAGE_PV8(false, true); else SAGE_PV8(false, false); }
+#undef SAGE_PV8
+    return hipGetLastError();
+}
+
+hipError_t launch_attn_pv8(const int8_t* qq, const float* qscale, const int8_t* kq, const float* kscale,
+                           const int8_t* vt, const float* vscale, void* o, int BH, int N, int D, int causal,
+                           int block_q, int block_k, hipStream_t st) {
+    int shift_q = 0, shift_k = 0;
+    while ((1 << shift_q) < block_q) ++shift_q;
+    while ((1 << shift_k) < block_k) ++shift_k;
+    const bool ktok = block_k == 1;
+    if (D == 64) return launch_pv8_d<64>(qq, qscale, kq, kscale, vt, vscale, o, BH, N, causal, shift_q, shift_k, ktok, st);
+    return launch_pv8_d<128>(qq, qscale, kq, kscale, vt, vscale, o, BH, N, causal, shift_q, shift_k, ktok, st);
+}
+
+}  // namespace sage
