@@ -31,7 +31,7 @@ HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 ATTN_TRAFFIC_BYTES = {"cfg3_prefill16k": 511.7e6}
 
 
-def cpu_baseline(w, seconds_budget=20.0, per_token=False, gpu_out_head0=None):
+def cpu_baseline(w, seconds_budget=20.0, per_token=False, gpu_out_head0=None, pv_int8=False):
     """Oracle (Algorithm-1 level, as it stands) on one head of the workload: the full pre-pass of that
     head plus a spread of Q blocks, scaled to the head's block-pair count."""
     import numpy as np
@@ -44,6 +44,16 @@ def cpu_baseline(w, seconds_budget=20.0, per_token=False, gpu_out_head0=None):
     gran = dict(gran_q=1, gran_k=1) if per_token else {}
     kq, ks, km = oracle.smooth_quant_k(k[None, None], 1 if per_token else w.block_k)
     qq, qs = oracle.quant_q(q[None, None], w.sm_scale, 1 if per_token else w.block_q)
+    if pv_int8:
+        vq, vs = oracle.quant_v(v[None, None])
+
+        def run(blocks):
+            return oracle.attn_pv8_slab(qq[0, 0], qs[0, 0], kq[0, 0], ks[0, 0], vq[0, 0], vs[0, 0], w.causal,
+                                        w.block_q, w.block_k, q_blocks=blocks, **gran)
+    else:
+        def run(blocks):
+            return oracle.attn_l2_slab(qq[0, 0], qs[0, 0], kq[0, 0], ks[0, 0], v, w.causal, w.block_q, w.block_k,
+                                       q_blocks=blocks, **gran)
     t_pre = time.perf_counter() - t0
     Tm = (w.N + w.block_q - 1) // w.block_q
     Tn = (w.N + w.block_k - 1) // w.block_k
@@ -58,7 +68,7 @@ def cpu_baseline(w, seconds_budget=20.0, per_token=False, gpu_out_head0=None):
     # probe one block to size the sample
     mid = Tm // 2
     t0 = time.perf_counter()
-    oracle.attn_l2_slab(qq[0, 0], qs[0, 0], kq[0, 0], ks[0, 0], v, w.causal, w.block_q, w.block_k, q_blocks=[mid], **gran)
+    run([mid])
     t_one = time.perf_counter() - t0
     per_pair = t_one / pairs(mid)
     threads = oracle.num_threads()
@@ -67,7 +77,7 @@ def cpu_baseline(w, seconds_budget=20.0, per_token=False, gpu_out_head0=None):
     n_blocks = max(threads, (n_blocks // threads) * threads)
     blocks = sorted(set(np.linspace(0, Tm - 1, n_blocks).round().astype(int).tolist()))
     t0 = time.perf_counter()
-    o_l2 = oracle.attn_l2_slab(qq[0, 0], qs[0, 0], kq[0, 0], ks[0, 0], v, w.causal, w.block_q, w.block_k, q_blocks=blocks, **gran)
+    o_l2 = run(blocks)
     t_blocks = time.perf_counter() - t0
     # accuracy of the method (not timed): the GPU's rows of three Q blocks of this head against exact
     # fp64 attention on the fp16 inputs, with the paper's three metrics; the oracle's rows beside them
@@ -144,6 +154,9 @@ def main():
     ap.add_argument("--scales", choices=("block", "token"), default="block",
                     help="block: one scale per block_q / block_k tokens (Algorithm 1, the headline); "
                          "token: one scale per token of Q and K (the SAGEAttn-T kernel)")
+    ap.add_argument("--pv", choices=("fp16", "int8"), default="fp16",
+                    help="fp16: P~V in FP16 (Algorithm 1, the headline); int8: the INT8 second product of Section 4.3 "
+                         "(SAGEAttn-vB, or -vT with --scales token): the step gains the per-channel pre-pass of V")
     ap.add_argument("--rope", action="store_true",
                     help="the pre-pass applies RoPE to Q and K on the fly (the fused calls of Section 4.6's "
                          "fusion trick); not the headline configuration")
@@ -190,6 +203,11 @@ def main():
     ws = torch.empty(sage.sage_smooth_quant_k_workspace(B, H, N, D) // 8, dtype=torch.int64, device="cuda")
     out = torch.empty((B, H, N, D), dtype=torch.float16, device="cuda")
     stream = torch.cuda.current_stream()
+    pv_int8 = args.pv == "int8"
+    if pv_int8:
+        v_i8t = torch.empty((B, H, D, sage.sage_quant_v_pitch(N)), dtype=torch.int8, device="cuda")
+        v_scale = torch.empty((B, H, D), dtype=torch.float32, device="cuda")
+        ws_v = torch.empty(sage.sage_quant_v_workspace(B, H, N, D) // 4, dtype=torch.int32, device="cuda")
     if args.rope:
         pos = torch.arange(N, dtype=torch.float64, device="cuda")[:, None]
         freq = 10000.0 ** (-2.0 * torch.arange(D // 2, dtype=torch.float64, device="cuda") / D)[None, :]
@@ -207,9 +225,14 @@ def main():
         else:
             sage.sage_smooth_quant_k(kd, bk, k_i8, k_scale, k_mean, ws, stream)
             sage.sage_quant_q(qd, w.sm_scale, bq, q_i8, q_scale, stream)
+        if pv_int8:
+            sage.sage_quant_v(vd, v_i8t, v_scale, ws_v, stream)
         if i is not None:
             ev[i][1].record(stream)
-        sage.sage_attn_fwd(q_i8, q_scale, k_i8, k_scale, vd, w.causal, w.sm_scale, bq, bk, out, stream)
+        if pv_int8:
+            sage.sage_attn_pv_int8_fwd(q_i8, q_scale, k_i8, k_scale, v_i8t, v_scale, w.causal, w.sm_scale, bq, bk, out, stream)
+        else:
+            sage.sage_attn_fwd(q_i8, q_scale, k_i8, k_scale, vd, w.causal, w.sm_scale, bq, bk, out, stream)
         if i is not None:
             ev[i][2].record(stream)
 
@@ -268,14 +291,15 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "int8 QK^T (int32 acc) + fp16 PV (fp32 acc)",
+        "dtype": "int8 QK^T (int32 acc) + " + ("int8 PV (int32 acc)" if pv_int8 else "fp16 PV (fp32 acc)"),
         "data": "synthetic",
         "config": {"workload": f"{w.name}: B={B} H={H} N={N} D={D} causal={w.causal} fp16 in/out, "
                                + ("one scale per token of Q and K (SAGEAttn-T)" if per_token else
                                   f"block_q={w.block_q} block_k={w.block_k}")
                                + ("; RoPE applied inside the pre-pass" if args.rope else "")
                                + ("; timed as replays of a HIP graph of one step" if args.graph else "")
-                               + "; step = K pre-pass + Q pre-pass + attention"},
+                               + ("; INT8 P~V (SAGEAttn-v%s)" % ("T" if per_token else "B") if pv_int8 else "")
+                               + "; step = K pre-pass + Q pre-pass + " + ("V pre-pass + " if pv_int8 else "") + "attention"},
         "attn_kernel_ms": attn_ms,
         "prepass_ms": pre_ms,
         "attn_only_tops": attn_tops,
@@ -286,28 +310,32 @@ def main():
             "peak": INT8_PEAK_TOPS,
             "unit": "TFLOP/s",
             "frac": attn_tops / INT8_PEAK_TOPS,
-            "traffic": None if per_token else ATTN_TRAFFIC_BYTES.get(w.name),
-            "traffic_unit": "bytes per launch (algorithmic: %.1f MB)" % (6.0 * B * H * N * D / 1e6),
-            "kernel": "sage_attn_kernel",
-            "note": ("achieved = counted ops (half INT8 ops, half FP16 flops) / mean attention-kernel time from HIP "
+            "traffic": None if per_token or pv_int8 else ATTN_TRAFFIC_BYTES.get(w.name),
+            "traffic_unit": "bytes per launch (algorithmic: %.1f MB)" % ((5.0 if pv_int8 else 6.0) * B * H * N * D / 1e6),
+            "kernel": "sage_attn_pv8_kernel" if pv_int8 else "sage_attn_kernel",
+            "note": ("achieved = counted ops (all INT8) / mean attention-kernel time from HIP events on the launch "
+                     "stream; peak = dense INT8 MFMA" if pv_int8 else
+                     "achieved = counted ops (half INT8 ops, half FP16 flops) / mean attention-kernel time from HIP "
                      "events on the launch stream; peak = dense INT8 MFMA. Against the blended ceiling of this "
                      "algorithm (2/3 of the INT8 peak, because P~V runs at the FP16 rate) the fraction is "
                      f"{attn_tops / (INT8_PEAK_TOPS * 2 / 3):.4f}"),
         },
         "prepass_roofline": {
             "bound": "hbm",
-            "achieved": 8.0 * B * H * N * D / (pre_ms * 1e-3) / 1e9,
+            "achieved": (13.0 if pv_int8 else 8.0) * B * H * N * D / (pre_ms * 1e-3) / 1e9,
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
-            "frac": 8.0 * B * H * N * D / (pre_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "frac": (13.0 if pv_int8 else 8.0) * B * H * N * D / (pre_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
             "note": "algorithmic bytes: Q 2 read + 1 written, K 2 + 2 read (mean is a global dependency) + 1 written "
-                    "= 8 B per element pair; the inputs are not rotated, so part of K's second read hits the last-level cache",
+                    "= 8 B per element pair" + (", V 2 + 2 read (the channel maximum is a global dependency) + 1 written = 13"
+                                                if pv_int8 else "")
+                    + "; the inputs are not rotated, so part of the second reads hits the last-level cache",
         },
         "paper_context": "paper reports ~2.1x over FlashAttention2 and ~2.7x over xformers on RTX4090 (340 TOPS, 52% of its INT8 peak)",
     }
     if not args.no_cpu_baseline and not args.rope:      # the oracle leg times the headline path only
         del qd, kd, vd
-        result["cpu_baseline"] = cpu_baseline(w, per_token=per_token, gpu_out_head0=out[0, 0].cpu().numpy())
+        result["cpu_baseline"] = cpu_baseline(w, per_token=per_token, gpu_out_head0=out[0, 0].cpu().numpy(), pv_int8=pv_int8)
     print(json.dumps(result))
 
 

@@ -23,8 +23,9 @@
 //     The per-channel scale delta_V and the static 1/127 are constant over the row's whole loop and
 //     are applied once, in the epilogue; l is carried as the sum of 127 P~ (fp32, unrounded P~),
 //     which cancels the 1/127.
-//   - 127 P~ = exp2(S' - (m' - log2 127)) comes out of the exponential directly; adding 1.5 * 2^23
-//     rounds it to the nearest integer (ties to even) and leaves the code in the low byte.
+//   - 127 P~ = exp2(S' - (m' - log2 127)) comes out of the exponential directly; the packed
+//     float-to-byte conversion rounds it to the nearest integer, ties to even, and packs four codes
+//     into a register with one instruction per code.
 //
 // This variant is written with compiler builtins and compiler scheduling; it trades the second
 // product's instruction count (half) for more VALU work per score (conversion, rounding, packing,
@@ -41,7 +42,7 @@ typedef _Float16 p4h __attribute__((ext_vector_type(4)));
 namespace {
 constexpr float PV8_LOG2E = 1.4426950408889634f;
 constexpr float PV8_LOG2_127 = 6.988684686772166f;
-constexpr float PV8_ROUND = 12582912.0f;          // 1.5 * 2^23: x + this rounds x to an integer in the low mantissa bits
+constexpr float PV8_HIDDEN = -3.0e38f;            // stands for a masked score: finite, so that 0 * it is not NaN
 constexpr int PV8_FLUSH_TILES = 1024;
 
 __device__ __forceinline__ float lane32_partner(float v) { return __shfl_xor(v, 32, 64); }
@@ -160,6 +161,7 @@ sage_attn_pv8_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qs
         for (int r = 0; r < 16; ++r) { acc[cb][r] = 0; of[cb][r] = 0.0f; }
     float m_run = -__builtin_inff(), l127 = 0.0f;
     int since = 0;
+    bool fresh = false;
 
     fetch(0);
     stage(0);
@@ -184,20 +186,38 @@ sage_attn_pv8_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qs
             }
             // mask: keys past N, and keys after the lane's query when causal (edge tiles only)
             const bool edge = (j * KT + KT > N) || (CAUSAL && j * KT + KT - 1 > qrow0);
-            // dequantized scores in log2 units, x = S^ * (delta_Q log2 e * delta_K); hidden ones -inf
-            float x[2][16];
-            float tmax = -__builtin_inff();
-            const float sc_tile = dq * ksc_bh[KTOK ? 0 : (j * KT) >> shift_k];
+            // Per-block key scale: y = (float)S^, the maximum is taken on y and scaled once, and the
+            // softmax argument is one FMA, y * sc - m'.  Per-token key scales: y = (float)S^ * sc[key]
+            // is the dequantized score itself (log2 units).  Hidden scores become a huge negative
+            // number whose exponential is 0 (sc >= 1e-30 keeps the product far below any maximum).
+            const float sc = __builtin_fmaxf(dq * ksc_bh[KTOK ? 0 : (j * KT) >> shift_k], 1e-30f);
+            float y[2][16];
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    const int kidx = j * KT + 32 * kb + 16 * h + r;
-                    const float sc = KTOK ? dq * ksc_bh[kidx < N ? kidx : N - 1] : sc_tile;
-                    const bool hidden = edge && (kidx >= N || (CAUSAL && kidx > q_row));
-                    x[kb][r] = hidden ? -__builtin_inff() : (float)s[kb][r] * sc;
-                    tmax = __builtin_fmaxf(tmax, x[kb][r]);
+                    y[kb][r] = (float)s[kb][r];
+                    if (KTOK) {
+                        const int kidx = j * KT + 32 * kb + 16 * h + r;
+                        y[kb][r] *= dq * ksc_bh[kidx < N ? kidx : N - 1];
+                    }
                 }
+            if (edge) {          // wave-uniform: interior tiles skip the mask arithmetic
+                asm volatile("" ::: "memory");      // keeps this a branch (not 64 compare-and-select pairs on every tile)
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int kidx = j * KT + 32 * kb + 16 * h + r;
+                        if (kidx >= N || (CAUSAL && kidx > q_row)) y[kb][r] = PV8_HIDDEN;
+                    }
+            }
+            float tmax = PV8_HIDDEN;
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) tmax = __builtin_fmaxf(tmax, y[kb][r]);
+            if (!KTOK) tmax *= sc;
             tmax = __builtin_fmaxf(tmax, lane32_partner(tmax));
             const float m_new = __builtin_fmaxf(m_run, tmax);
             ++since;
@@ -208,11 +228,11 @@ sage_attn_pv8_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qs
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
                         of[cb][r] = (of[cb][r] + (float)acc[cb][r]) * alpha;
-                        acc[cb][r] = 0;
                     }
                 l127 *= alpha;
                 m_run = m_new;
                 since = 0;
+                fresh = true;          // the next product starts from zero inside the matrix instruction
             }
             const float mb = m_run - PV8_LOG2_127;
             p4i pk[2];
@@ -224,20 +244,34 @@ sage_attn_pv8_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qs
 #pragma unroll
                     for (int b = 0; b < 4; ++b) {
                         const int r = 4 * w + b;
-                        const float v = __builtin_amdgcn_exp2f(x[kb][r] - mb);          // 127 P~; 0 for hidden keys
+                        // 127 P~ (0 for hidden keys); the packed conversion rounds to the nearest
+                        // integer, ties to even (checked on hardware), and inserts byte b
+                        const float v = __builtin_amdgcn_exp2f(KTOK ? y[kb][r] - mb : __builtin_fmaf(y[kb][r], sc, -mb));
                         l127 += v;
-                        const unsigned code = __builtin_bit_cast(unsigned, v + PV8_ROUND) & 0xffu;
-                        word |= code << (8 * b);
+                        word = __builtin_amdgcn_cvt_pk_u8_f32(v, (unsigned)b, word);
                     }
                     pk[kb][w] = (int)word;
                 }
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
+            if (fresh) {
+                const p16i zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
                 for (int cb = 0; cb < DT; ++cb) {
-                    const p4i a = *(const p4i*)(tb + v_rd[cb][kb]);
-                    acc[cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, pk[kb], acc[cb], 0, 0, 0);
+                    const p4i a = *(const p4i*)(tb + v_rd[cb][0]);
+                    acc[cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, pk[0], zero, 0, 0, 0);
                 }
+                fresh = false;
+            } else {
+#pragma unroll
+                for (int cb = 0; cb < DT; ++cb) {
+                    const p4i a = *(const p4i*)(tb + v_rd[cb][0]);
+                    acc[cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, pk[0], acc[cb], 0, 0, 0);
+                }
+            }
+#pragma unroll
+            for (int cb = 0; cb < DT; ++cb) {
+                const p4i a = *(const p4i*)(tb + v_rd[cb][1]);
+                acc[cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, pk[1], acc[cb], 0, 0, 0);
+            }
         }
         if (j + 1 < T) stage(buf ^ 1);
         __syncthreads();
