@@ -46,9 +46,25 @@ constexpr float PV8_HIDDEN = -3.0e38f;            // stands for a masked score: 
 constexpr int PV8_FLUSH_TILES = 1024;
 
 __device__ __forceinline__ float lane32_partner(float v) { return __shfl_xor(v, 32, 64); }
-__device__ __forceinline__ int k_perm(int row) {
-    // LDS row of key `row` of a tile: key 32kb + 16h + 4g + b  ->  32kb + 8g + 4h + b
-    return (row & 32) | ((row & 12) << 1) | ((row & 16) >> 2) | (row & 3);
+// Raw-buffer descriptor of `bytes` bytes at `base` (wave-uniform, pinned to scalar registers): loads
+// through it are range-checked by the hardware, lanes past the end read zero.
+__device__ __forceinline__ p4i pv8_descriptor(const void* base, unsigned bytes) {
+    const unsigned long long a = (unsigned long long)base;
+    return (p4i){__builtin_amdgcn_readfirstlane((int)(unsigned)a),
+                 __builtin_amdgcn_readfirstlane((int)((unsigned)(a >> 32) & 0xffffu)),
+                 __builtin_amdgcn_readfirstlane((int)bytes), 0x00020000};
+}
+// 16 bytes per lane from global memory straight into LDS (no staging registers): lane l lands at
+// LDS byte lds_addr + 16 * l (lds_addr wave-uniform).  Asynchronous: the issuing wavefront waits
+// with s_waitcnt vmcnt(0) before the barrier that publishes the tile.
+__device__ __forceinline__ void pv8_load_to_lds16(const p4i& rsrc, unsigned goff, unsigned lds_addr) {
+    const unsigned uniform_addr = (unsigned)__builtin_amdgcn_readfirstlane((int)lds_addr);      // pins it to a scalar register
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %1, 0 offen lds"
+                 : : "v"(goff), "s"(rsrc), "s"(uniform_addr) : "memory");
+}
+__device__ __forceinline__ int k_unperm(int p) {
+    // key of a tile held by LDS row p: row 32kb + 8g + 4h + b holds key 32kb + 16h + 4g + b
+    return (p & 32) | ((p & 4) << 2) | ((p & 24) >> 1) | (p & 3);
 }
 template <int D> __device__ __forceinline__ int k_swz8(int row) { return D == 128 ? ((row >> 1) & 7) : ((row >> 2) & 3); }
 __device__ __forceinline__ int vt_swz(int ch) { return (ch >> 2) & 3; }
@@ -67,7 +83,8 @@ sage_attn_pv8_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qs
     constexpr int KCH = D / 16;                        // 16-byte chunks per K^ row
     constexpr int KL = KB / 16 / NT, VL = VB / 16 / NT;
     static_assert(KL >= 1 && VL >= 1, "tile loads cover whole workgroups");
-    __shared__ __attribute__((aligned(16))) unsigned char lds[2 * (KB + VB)];
+    constexpr int KSL = KTOK ? KT * 4 : 0;             // per-key scales of a tile (per-token variant)
+    __shared__ __attribute__((aligned(16))) unsigned char lds[3 * (KB + VB) + 3 * KSL];
 
     // workgroup -> (slab, query tile): contiguous ranges per XCD, heaviest query tiles first
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
@@ -102,38 +119,35 @@ sage_attn_pv8_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qs
         Tw = last < T ? last : T;
     }
 
-    // ---- tile staging: global -> registers (in flight during the previous tile's work) -> LDS
-    const int8_t* k_src[KL]; int k_row[KL], k_dst[KL];
-    const int8_t* v_src[VL]; int v_dst[VL];
+    // ---- tile loads: global -> LDS directly.  Instruction i of the workgroup fills the 16-byte
+    // vectors NT*i + t of the (linear) LDS tile, one per lane; the global chunk a lane fetches is the
+    // one that belongs there (row permutation and chunk swizzle inverted).  K^ rows past N lie beyond
+    // the slab's descriptor and read as zero; V^^T rows are padded to whole tiles.
+    unsigned k_goff[KL], v_goff[VL];
 #pragma unroll
     for (int i = 0; i < KL; ++i) {
-        const int vidx = t + NT * i, row = vidx / KCH, c = vidx % KCH, p = k_perm(row);
-        k_row[i] = row;
-        k_src[i] = ki + (slab + row) * D + c * 16;
-        k_dst[i] = p * D + ((c ^ k_swz8<D>(p)) * 16);
+        const int vidx = t + NT * i, p = vidx / KCH, slot = vidx % KCH;
+        k_goff[i] = (unsigned)(k_unperm(p) * D + ((slot ^ k_swz8<D>(p)) * 16));
     }
 #pragma unroll
     for (int i = 0; i < VL; ++i) {
-        const int vidx = t + NT * i, ch = vidx >> 2, c = vidx & 3;
-        v_src[i] = vt + ((size_t)bh * D + ch) * Np + c * 16;
-        v_dst[i] = ch * KT + ((c ^ vt_swz(ch)) * 16);
+        const int vidx = t + NT * i, ch = vidx >> 2, slot = vidx & 3;
+        v_goff[i] = (unsigned)(ch * Np + ((slot ^ vt_swz(ch)) * 16));
     }
-    p4i k_st[KL], v_st[VL];
-    auto fetch = [&](int j) {
+    const p4i k_desc = pv8_descriptor(ki + slab * D, (unsigned)N * D);
+    const p4i v_desc = pv8_descriptor(vt + (size_t)bh * D * Np, (unsigned)D * Np);
+    const p4i ks_desc = pv8_descriptor(ksc_bh, (unsigned)N * 4u);      // per-token variant: N scales; past the end reads 0
+    const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)lds;
+    auto fetch = [&](int j, int buf) {
+        if (KTOK && wave == 0 && lane < KT / 4)          // the tile's 64 key scales, 16 bytes per lane
+            pv8_load_to_lds16(ks_desc, (unsigned)lane * 16u + (unsigned)j * (KT * 4), lds_base + 3 * (KB + VB) + buf * KSL);
+        const unsigned kb_addr = lds_base + buf * (KB + VB) + wave * 1024;
 #pragma unroll
-        for (int i = 0; i < KL; ++i) {
-            k_st[i] = (p4i){0, 0, 0, 0};
-            if (j * KT + k_row[i] < N) k_st[i] = *(const p4i*)(k_src[i] + (size_t)j * KT * D);
-        }
+        for (int i = 0; i < KL; ++i)
+            pv8_load_to_lds16(k_desc, k_goff[i] + (unsigned)j * (KT * D), kb_addr + i * (NT * 16));
 #pragma unroll
-        for (int i = 0; i < VL; ++i) v_st[i] = *(const p4i*)(v_src[i] + (size_t)j * KT);      // j * 64 + 63 < Np
-    };
-    auto stage = [&](int buf) {
-        unsigned char* kb = lds + buf * (KB + VB);
-#pragma unroll
-        for (int i = 0; i < KL; ++i) *(p4i*)(kb + k_dst[i]) = k_st[i];
-#pragma unroll
-        for (int i = 0; i < VL; ++i) *(p4i*)(kb + KB + v_dst[i]) = v_st[i];
+        for (int i = 0; i < VL; ++i)
+            pv8_load_to_lds16(v_desc, v_goff[i] + (unsigned)j * KT, kb_addr + KB + i * (NT * 16));
     };
 
     // ---- operand read offsets (per lane, inside a buffer)
@@ -163,13 +177,35 @@ sage_attn_pv8_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qs
     int since = 0;
     bool fresh = false;
 
-    fetch(0);
-    stage(0);
+    p4i pk[2];             // codes of the tile in flight: B operands of the second product
+    bool pending = false;  // the second half (keys 32..63) of the previous tile's product is still to be issued
+    const unsigned char* pend_tb = lds;
+
+    // second product, one 32-key half: O^T blocks += V^^T operand (LDS) x codes
+    auto pv_half = [&](const unsigned char* tb, int kb, const p4i& codes, bool from_zero) {
+        const p16i zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+        if (from_zero) {          // wave-uniform
+#pragma unroll
+            for (int cb = 0; cb < DT; ++cb) {
+                const p4i a = *(const p4i*)(tb + v_rd[cb][kb]);
+                acc[cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, codes, zero, 0, 0, 0);
+            }
+        } else {
+#pragma unroll
+            for (int cb = 0; cb < DT; ++cb) {
+                const p4i a = *(const p4i*)(tb + v_rd[cb][kb]);
+                acc[cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, codes, acc[cb], 0, 0, 0);
+            }
+        }
+    };
+
+    fetch(0, 0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
     for (int j = 0; j < T; ++j) {
-        const int buf = j & 1;
-        if (j + 1 < T) fetch(j + 1);
+        const int buf = j % 3;                     // three buffers: the deferred half reads tile j-1 while tile j+1 is staged
+        if (j + 1 < T) fetch(j + 1, (j + 1) % 3);
         if (j < Tw) {
             const unsigned char* tb = lds + buf * (KB + VB);
             // S^T block kb: keys 64j + 32kb + 16h + r in register r
@@ -192,14 +228,16 @@ sage_attn_pv8_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qs
             // number whose exponential is 0 (sc >= 1e-30 keeps the product far below any maximum).
             const float sc = __builtin_fmaxf(dq * ksc_bh[KTOK ? 0 : (j * KT) >> shift_k], 1e-30f);
             float y[2][16];
+            // the previous tile's second half goes to the matrix pipe while this tile's scores are converted
+            if (pending) pv_half(pend_tb, 1, pk[1], false);
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     y[kb][r] = (float)s[kb][r];
                     if (KTOK) {
-                        const int kidx = j * KT + 32 * kb + 16 * h + r;
-                        y[kb][r] *= dq * ksc_bh[kidx < N ? kidx : N - 1];
+                        const float* kl = (const float*)(lds + 3 * (KB + VB) + buf * KSL);
+                        y[kb][r] *= dq * kl[32 * kb + 16 * h + r];
                     }
                 }
             if (edge) {          // wave-uniform: interior tiles skip the mask arithmetic
@@ -235,47 +273,39 @@ sage_attn_pv8_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qs
                 fresh = true;          // the next product starts from zero inside the matrix instruction
             }
             const float mb = m_run - PV8_LOG2_127;
-            p4i pk[2];
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
+            // codes of one 32-key half: 127 P~ (0 for hidden keys) out of the exponential; the packed
+            // conversion rounds to the nearest integer, ties to even (checked on hardware), and
+            // inserts byte b
+            auto softmax_half = [&](int kb) {
 #pragma unroll
                 for (int w = 0; w < 4; ++w) {
                     unsigned word = 0u;
 #pragma unroll
                     for (int b = 0; b < 4; ++b) {
                         const int r = 4 * w + b;
-                        // 127 P~ (0 for hidden keys); the packed conversion rounds to the nearest
-                        // integer, ties to even (checked on hardware), and inserts byte b
                         const float v = __builtin_amdgcn_exp2f(KTOK ? y[kb][r] - mb : __builtin_fmaf(y[kb][r], sc, -mb));
                         l127 += v;
                         word = __builtin_amdgcn_cvt_pk_u8_f32(v, (unsigned)b, word);
                     }
                     pk[kb][w] = (int)word;
                 }
-            if (fresh) {
-                const p16i zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-                for (int cb = 0; cb < DT; ++cb) {
-                    const p4i a = *(const p4i*)(tb + v_rd[cb][0]);
-                    acc[cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, pk[0], zero, 0, 0, 0);
-                }
-                fresh = false;
-            } else {
-#pragma unroll
-                for (int cb = 0; cb < DT; ++cb) {
-                    const p4i a = *(const p4i*)(tb + v_rd[cb][0]);
-                    acc[cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, pk[0], acc[cb], 0, 0, 0);
-                }
-            }
-#pragma unroll
-            for (int cb = 0; cb < DT; ++cb) {
-                const p4i a = *(const p4i*)(tb + v_rd[cb][1]);
-                acc[cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, pk[1], acc[cb], 0, 0, 0);
-            }
+            };
+            softmax_half(0);
+            // first half of the product on the matrix pipe, then the second half's codes; the first
+            // product after a flush starts from zero inside the matrix instruction
+            pv_half(tb, 0, pk[0], fresh);
+            fresh = false;
+            softmax_half(1);
+            pending = true;
+            pend_tb = tb;
+        } else if (pending) {
+            pv_half(pend_tb, 1, pk[1], false);
+            pending = false;
         }
-        if (j + 1 < T) stage(buf ^ 1);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // this wavefront's part of tile j + 1 has landed
         __syncthreads();
     }
+    if (pending) pv_half(pend_tb, 1, pk[1], false);
 
     // ---- epilogue: O = (O_fp32 + A) * delta_V[c] / sum(127 P~)
     const float lt = l127 + lane32_partner(l127);
