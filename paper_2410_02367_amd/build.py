@@ -176,17 +176,49 @@ def check_attention_asm(text: str) -> list:
     return problems
 
 
+def check_pv8_asm(text: str) -> list:
+    """Checks the assembly text of the INT8-P~V attention kernels (sage_attn_pv8.hip).  Their matrix
+    instructions are compiler builtins, so the compiler places the waits itself; what the source
+    relies on is only that nothing spills to scratch memory and that the compiler never touches m0,
+    which the hand-written global->LDS loads set."""
+    import re
+    bodies = re.findall(r"^(_ZN4sage20sage_attn_pv8_kernel\w+):(.*?)^\.Lfunc_end\d+:", text, re.S | re.M)
+    problems = []
+    if len(bodies) != 8:      # head dimension {64, 128} x {causal, full} x {per-block, per-token key scales}
+        problems.append(f"expected 8 INT8-P~V attention kernels in the assembly, found {len(bodies)}")
+    for name, body in bodies:
+        in_asm = False
+        for line in body.split("\n"):
+            if "#ASMSTART" in line:
+                in_asm = True
+                continue
+            if "#ASMEND" in line:
+                in_asm = False
+                continue
+            code = line.split(";")[0].strip()
+            if in_asm or not code:
+                continue
+            if code.startswith("scratch_"):
+                problems.append(f"{name}: scratch access: {code}")
+            if re.search(r"\bm0\b", code):
+                problems.append(f"{name}: compiler-generated use of m0: {code}")
+    return problems
+
+
 def verify_attention_isa(extra=()) -> None:
-    """Compiles sage_attn.hip to assembly and raises RuntimeError if check_attention_asm() objects."""
+    """Compiles the attention sources to assembly and raises RuntimeError if check_attention_asm() or
+    check_pv8_asm() objects."""
     import tempfile
     flags = [f for f in HIPCC_FLAGS if f not in ("-shared", "-fPIC")]
+    problems = []
     with tempfile.TemporaryDirectory() as tmp:
-        out = os.path.join(tmp, "sage_attn.s")
-        cmd = [hipcc(), *flags, *extra, "-S", "--cuda-device-only", "-o", out, os.path.join(CSRC, "sage_attn.hip")]
-        res = subprocess.run(cmd, capture_output=True, text=True)
-        if res.returncode != 0:
-            raise RuntimeError("hipcc -S failed:\n" + res.stderr)
-        problems = check_attention_asm(open(out).read())
+        for src, check in (("sage_attn.hip", check_attention_asm), ("sage_attn_pv8.hip", check_pv8_asm)):
+            out = os.path.join(tmp, src + ".s")
+            cmd = [hipcc(), *flags, *extra, "-S", "--cuda-device-only", "-o", out, os.path.join(CSRC, src)]
+            res = subprocess.run(cmd, capture_output=True, text=True)
+            if res.returncode != 0:
+                raise RuntimeError("hipcc -S failed:\n" + res.stderr)
+            problems += check(open(out).read())
     if problems:
         raise RuntimeError("attention kernel ISA check failed:\n  " + "\n  ".join(problems[:20]))
 

@@ -90,3 +90,37 @@ def test_matrix_instruction_reading_a_fresh_valu_result_is_reported():
     assert any("less than 2 wait states" in p for p in check_attention_asm(fake(bad)))
     ok = bad.replace("\tv_cvt_pk_f16_f32 v5, v20, v21\n", "\tv_cvt_pk_f16_f32 v5, v20, v21\n\tv_mov_b32_e32 v40, v41\n\tv_mov_b32_e32 v42, v41\n")
     assert check_attention_asm(fake(ok)) == []
+
+
+# ------------------------------------------------------------------ INT8-P~V kernels (compiler-scheduled)
+
+from paper_2410_02367_amd.build import check_pv8_asm  # noqa: E402
+
+PV8_KERNELS = ["_ZN4sage20sage_attn_pv8_kernelILi%dELb%dELb%dEEEvPKa" % (d, c, k)
+               for d in (64, 128) for c in (0, 1) for k in (0, 1)]
+
+
+def fake_pv8(body_of_first: str, kernels=PV8_KERNELS) -> str:
+    return "\n".join(f"{k}:\n{body_of_first if i == 0 else chr(9) + 's_endpgm' + chr(10)}.Lfunc_end{i}:\n"
+                     for i, k in enumerate(kernels))
+
+
+PV8_CLEAN = """\t;;#ASMSTART
+\ts_mov_b32 m0, s4
+\ts_nop 0
+\tbuffer_load_dwordx4 v1, s[8:11], 0 offen lds
+\t;;#ASMEND
+\tv_mfma_i32_32x32x32_i8 v[0:15], v[16:19], v[20:23], v[0:15]
+\ts_endpgm
+"""
+
+
+def test_pv8_clean_text_passes_and_a_missing_kernel_is_reported():
+    assert check_pv8_asm(fake_pv8(PV8_CLEAN)) == []
+    assert any("expected 8" in p for p in check_pv8_asm(fake_pv8(PV8_CLEAN, PV8_KERNELS[:-1])))
+
+
+def test_pv8_scratch_and_compiler_use_of_m0_are_reported():
+    bad = PV8_CLEAN.replace("\ts_endpgm\n", "\tscratch_load_dword v1, off, off\n\ts_mov_b32 m0, s9\n\ts_endpgm\n")
+    problems = check_pv8_asm(fake_pv8(bad))
+    assert any("scratch access" in p for p in problems) and any("use of m0" in p for p in problems)
