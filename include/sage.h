@@ -157,6 +157,9 @@ int sage_quant_v(const void* v_f16, int8_t* v_i8t, float* v_scale,
  * the static scale 1/127 (its row maxima are 1), P^ V^ is an INT8 product with an int32 result,
  * dequantized with 1/127 and delta_V[c].  m, l and the rescaling are those of Algorithm 1 (l sums the
  * unrounded P~).  block_q / block_k as in sage_attn_fwd: block sizes give SAGEAttn-vB, 1 gives -vT.
+ * The block of P~ that is quantized together is the loop's block of 64 keys (the paper's kernel
+ * setting), whatever the granularity of the K scales: a code is relative to the running maximum
+ * after its own 64-key block.
  *   q_i8, q_scale, k_i8, k_scale   as for sage_attn_fwd
  *   v_i8t, v_scale                 from sage_quant_v (same N)
  *   o_f16   out [B,H,N,D] fp16

@@ -10,6 +10,7 @@ import oracle
 import paper_2410_02367_amd as sage
 import sage_inputs as si
 from gpu_util import assert_output_close, bits, to_dev
+from test_gpu_pv_int8 import assert_pv8_close, assert_v_quant_bit_exact
 
 pytestmark = pytest.mark.gpu
 
@@ -59,3 +60,11 @@ def test_random_shape(i, B, H, N, D, causal, bq, bk, rope):
     lq, lk = max(bq, 64) if bq != 1 else 128, max(bk, 64) if bk != 1 else 64
     o_ref = oracle.attn_l2(qq, qs, kq, ks, v, causal, lq, lk, gran_q=bq, gran_k=bk)
     assert_output_close(o.cpu().numpy(), o_ref, f"sweep{i}")
+    # the same case with the INT8 second product (Section 4.3).  Its codes of P~ are relative to the
+    # running maximum after each 64-key block of the loop, so the oracle's kv block is the kernel's
+    # 64 whatever the granularity of the K scales.
+    (v_i8t, v_scale), (vq, vs) = assert_v_quant_bit_exact(v)
+    o8 = sage.sage_attn_pv_int8_fwd(q_i8, q_scale, k_i8, k_scale, v_i8t, v_scale, causal, w.sm_scale, bq, bk)
+    torch.cuda.synchronize()
+    o8_ref, l_ref = oracle.attn_pv8(qq, qs, kq, ks, vq, vs, causal, 128, 64, gran_q=bq, gran_k=bk, return_l=True)
+    assert_pv8_close(o8.cpu().numpy(), o8_ref, l_ref, vs, f"sweep{i} INT8 PV")

@@ -77,3 +77,23 @@ def test_host_validation_rejects_bad_arguments_before_any_launch(lib):
     assert lib.sage_rope_smooth_quant_k(good, good, None, good, good, good, good, 1 << 20, 1, 1, 64, 64, 64, None) == 1
     assert lib.sage_rope_smooth_quant_k(good, good, good, good, good, good, good, 8, 1, 1, 64, 64, 64, None) == 4
     assert lib.sage_rope_smooth_quant_k(good, odd, good, good, good, good, good, 1 << 20, 1, 1, 64, 64, 64, None) == 5
+
+
+def test_int8_second_product_calls_validate_like_the_others(lib):
+    f = ctypes.c_float
+    good = ctypes.c_void_p(0x1000)
+    odd = ctypes.c_void_p(0x1004)
+    assert lib.sage_quant_v_workspace(1, 2, 256, 64) == 2 * 64 * 4
+    assert lib.sage_quant_v_workspace(1, 0, 256, 64) == 0
+    assert [lib.sage_quant_v_pitch(n) for n in (0, 1, 64, 65, 17776)] == [0, 64, 64, 128, 17792]
+    assert lib.sage_quant_v(None, good, good, good, 1 << 20, 1, 1, 64, 64, None) == 1
+    assert lib.sage_quant_v(good, good, good, good, 1 << 20, 1, 1, 0, 64, None) == 2
+    assert lib.sage_quant_v(good, good, good, good, 1 << 20, 1, 1, 64, 96, None) == 3
+    assert lib.sage_quant_v(good, good, good, good, 8, 1, 1, 64, 64, None) == 4
+    assert lib.sage_quant_v(good, odd, good, good, 1 << 20, 1, 1, 64, 64, None) == 5
+    args = (1, 1, 64, 64, 0)
+    assert lib.sage_attn_pv_int8_fwd(good, good, good, good, None, good, good, *args, f(0.125), 128, 64, None) == 1
+    assert lib.sage_attn_pv_int8_fwd(good, good, good, good, good, good, good, 1, 1, 64, 96, 0, f(0.125), 128, 64, None) == 3
+    assert lib.sage_attn_pv_int8_fwd(good, good, good, good, good, good, good, *args, f(0.125), 128, 32, None) == 3
+    assert lib.sage_attn_pv_int8_fwd(good, good, good, good, good, good, good, *args, f(float("nan")), 128, 64, None) == 7
+    assert lib.sage_attn_pv_int8_fwd(good, good, good, good, good, odd, good, *args, f(0.125), 128, 64, None) == 5
