@@ -17,7 +17,8 @@
 //     running maximum of the dequantized scores as in the recursion of Section 3.1 (no lazy update, no
 //     grid rounding), and the largest code of a row is 127.
 //   - Integer accumulation between maximum changes.  An int32 accumulator cannot be rescaled, so it
-//     is flushed into an fp32 accumulator (O = (O + A) * alpha, A = 0) whenever a row of the wavefront
+//     is flushed into an fp32 accumulator (O = (O + A) * alpha, A = 0; carried with the rescaling
+//     factored out, so that a flush is a conversion and an FMA per element) whenever a row of the wavefront
 //     raises its maximum (and every 1024 tiles, long before 64 * 127 * 127 * tiles reaches 2^31);
 //     between two flushes alpha = 1 and the tiles' products add exactly in the matrix instruction.
 //     The per-channel scale delta_V and the static 1/127 are constant over the row's whole loop and
@@ -150,30 +151,24 @@ sage_attn_pv8_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qs
             pv8_load_to_lds16(v_desc, v_goff[i] + (unsigned)j * KT, kb_addr + KB + i * (NT * 16));
     };
 
-    // ---- operand read offsets (per lane, inside a buffer)
-    int k_rd[2][KS], v_rd[DT][2];
+    // ---- operand read offsets (per lane, inside a buffer).  The swizzle of a row depends on the
+    // row's low bits only, so the second 32-key block of K^ and the further 32-channel blocks of
+    // V^^T are the first ones plus a constant: KS + 2 registers, the rest immediates.
+    int k_rd0[KS], v_rd0[2];
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+    for (int ks = 0; ks < KS; ++ks) k_rd0[ks] = ql * D + (((2 * ks + h) ^ k_swz8<D>(ql)) * 16);
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            const int p = 32 * kb + ql, c = 2 * ks + h;
-            k_rd[kb][ks] = p * D + ((c ^ k_swz8<D>(p)) * 16);
-        }
-#pragma unroll
-    for (int cb = 0; cb < DT; ++cb)
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-            const int ch = 32 * cb + ql, c = 2 * kb + h;
-            v_rd[cb][kb] = KB + ch * KT + ((c ^ vt_swz(ch)) * 16);
-        }
+    for (int kb = 0; kb < 2; ++kb) v_rd0[kb] = KB + ql * KT + (((2 * kb + h) ^ vt_swz(ql)) * 16);
+    auto k_rd = [&](int kb, int ks) { return k_rd0[ks] + kb * (32 * D); };
+    auto v_rd = [&](int cb, int kb) { return v_rd0[kb] + cb * (32 * KT); };
 
     p16i acc[DT];          // int32 product since the last flush
-    p16f of[DT];           // fp32 accumulator, in units of (delta_V / 127) relative to the running maximum
+    p16f of[DT];           // fp32 accumulator in units of delta_V / 127; relative to the running maximum it counts g = 1 / ginv times
 #pragma unroll
     for (int cb = 0; cb < DT; ++cb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) { acc[cb][r] = 0; of[cb][r] = 0.0f; }
-    float m_run = -__builtin_inff(), l127 = 0.0f;
+    float m_run = -__builtin_inff(), l127 = 0.0f, ginv = 1.0f;
     int since = 0;
     bool fresh = false;
 
@@ -187,13 +182,13 @@ sage_attn_pv8_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qs
         if (from_zero) {          // wave-uniform
 #pragma unroll
             for (int cb = 0; cb < DT; ++cb) {
-                const p4i a = *(const p4i*)(tb + v_rd[cb][kb]);
+                const p4i a = *(const p4i*)(tb + v_rd(cb, kb));
                 acc[cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, codes, zero, 0, 0, 0);
             }
         } else {
 #pragma unroll
             for (int cb = 0; cb < DT; ++cb) {
-                const p4i a = *(const p4i*)(tb + v_rd[cb][kb]);
+                const p4i a = *(const p4i*)(tb + v_rd(cb, kb));
                 acc[cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, codes, acc[cb], 0, 0, 0);
             }
         }
@@ -216,7 +211,7 @@ sage_attn_pv8_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qs
                 for (int r = 0; r < 16; ++r) s[kb][r] = 0;
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
-                    const p4i a = *(const p4i*)(tb + k_rd[kb][ks]);
+                    const p4i a = *(const p4i*)(tb + k_rd(kb, ks));
                     s[kb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, qreg[ks], s[kb], 0, 0, 0);
                 }
             }
@@ -231,7 +226,7 @@ sage_attn_pv8_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qs
             // the previous tile's second half goes to the matrix pipe while this tile's scores are converted
             if (pending) pv_half(pend_tb, 1, pk[1], false);
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
+            for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     y[kb][r] = (float)s[kb][r];
@@ -240,6 +235,9 @@ sage_attn_pv8_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qs
                         y[kb][r] *= dq * kl[32 * kb + 16 * h + r];
                     }
                 }
+                // per-token variant: one half's 16 key scales in registers at a time
+                if (KTOK && kb == 0) __builtin_amdgcn_sched_barrier(0);
+            }
             if (edge) {          // wave-uniform: interior tiles skip the mask arithmetic
                 asm volatile("" ::: "memory");      // keeps this a branch (not 64 compare-and-select pairs on every tile)
 #pragma unroll
@@ -260,14 +258,26 @@ sage_attn_pv8_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qs
             const float m_new = __builtin_fmaxf(m_run, tmax);
             ++since;
             if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0ull || since >= PV8_FLUSH_TILES) {
-                const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);      // 0 on the first tile (m_run = -inf)
+                // O relative to the running maximum is g * of + A with a per-lane factor g that takes
+                // the rescaling: (g of + A) alpha = (g alpha) (of + A / g), so a flush is one conversion and
+                // one FMA per element, of += A * (1 / g), and then g *= alpha.  1 / g = 2^(rise of the
+                // maximum since the row began) is carried instead of g; the first tile (m_run = -inf,
+                // of = A = 0) leaves it at 1.
 #pragma unroll
                 for (int cb = 0; cb < DT; ++cb)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        of[cb][r] = (of[cb][r] + (float)acc[cb][r]) * alpha;
-                    }
-                l127 *= alpha;
+                    for (int r = 0; r < 16; ++r) of[cb][r] = __builtin_fmaf((float)acc[cb][r], ginv, of[cb][r]);
+                const bool first = m_run == -__builtin_inff();
+                l127 *= __builtin_amdgcn_exp2f(m_run - m_new);          // 0 on the first tile; l127 is 0 there
+                ginv = first ? 1.0f : ginv * __builtin_amdgcn_exp2f(m_new - m_run);
+                if (__builtin_amdgcn_ballot_w64(ginv > 0x1p60f) != 0ull) {      // rare: fold g into of before 1 / g overflows
+                    const float g = ginv > 0x1p60f ? 1.0f / ginv : 1.0f;
+#pragma unroll
+                    for (int cb = 0; cb < DT; ++cb)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) of[cb][r] *= g;
+                    ginv = ginv > 0x1p60f ? 1.0f : ginv;
+                }
                 m_run = m_new;
                 since = 0;
                 fresh = true;          // the next product starts from zero inside the matrix instruction
@@ -309,7 +319,7 @@ sage_attn_pv8_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qs
 
     // ---- epilogue: O = (O_fp32 + A) * delta_V[c] / sum(127 P~)
     const float lt = l127 + lane32_partner(l127);
-    const float inv = 1.0f / lt;
+    const float inv = 1.0f / lt, g_run = 1.0f / ginv;
     if (q_row < N) {
         _Float16* orow = og + (slab + q_row) * D;
         const float* dv = vsc + (size_t)bh * D;
@@ -323,7 +333,7 @@ sage_attn_pv8_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qs
                 p4h o4;
 #pragma unroll
                 for (int b = 0; b < 4; ++b) {
-                    const float tot = of[cb][4 * g + b] + (float)acc[cb][4 * g + b];
+                    const float tot = __builtin_fmaf(of[cb][4 * g + b], g_run, (float)acc[cb][4 * g + b]);
                     o4[b] = (_Float16)(tot * (dd[b] * inv));
                 }
                 *(p4h*)(orow + ch) = o4;
