@@ -217,11 +217,12 @@ sage_attn_pv8_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qs
             }
             // mask: keys past N, and keys after the lane's query when causal (edge tiles only)
             const bool edge = (j * KT + KT > N) || (CAUSAL && j * KT + KT - 1 > qrow0);
-            // Per-block key scale: y = (float)S^, the maximum is taken on y and scaled once, and the
-            // softmax argument is one FMA, y * sc - m'.  Per-token key scales: y = (float)S^ * sc[key]
-            // is the dequantized score itself (log2 units).  Hidden scores become a huge negative
-            // number whose exponential is 0 (sc >= 1e-30 keeps the product far below any maximum).
-            const float sc = __builtin_fmaxf(dq * ksc_bh[KTOK ? 0 : (j * KT) >> shift_k], 1e-30f);
+            // Per-block key scale: y = (float)S^ and sc = delta_Q log2(e) delta_K[tile]; per-token key
+            // scales: y = (float)S^ * delta_K[key] and sc = delta_Q log2(e).  Either way the maximum is
+            // taken on y and scaled once (sc > 0), and the softmax argument is one FMA, y * sc - m'.
+            // Hidden scores become a huge negative number whose exponential is 0 (sc >= 1e-30 keeps the
+            // product far below any maximum).
+            const float sc = __builtin_fmaxf(KTOK ? dq : dq * ksc_bh[(j * KT) >> shift_k], 1e-30f);
             float y[2][16];
             // the previous tile's second half goes to the matrix pipe while this tile's scores are converted
             if (pending) pv_half(pend_tb, 1, pk[1], false);
@@ -232,7 +233,7 @@ sage_attn_pv8_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qs
                     y[kb][r] = (float)s[kb][r];
                     if (KTOK) {
                         const float* kl = (const float*)(lds + 3 * (KB + VB) + buf * KSL);
-                        y[kb][r] *= dq * kl[32 * kb + 16 * h + r];
+                        y[kb][r] *= kl[32 * kb + 16 * h + r];
                     }
                 }
                 // per-token variant: one half's 16 key scales in registers at a time
@@ -253,7 +254,7 @@ sage_attn_pv8_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qs
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) tmax = __builtin_fmaxf(tmax, y[kb][r]);
-            if (!KTOK) tmax *= sc;
+            tmax *= sc;
             tmax = __builtin_fmaxf(tmax, lane32_partner(tmax));
             const float m_new = __builtin_fmaxf(m_run, tmax);
             ++since;
@@ -293,7 +294,7 @@ sage_attn_pv8_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qs
 #pragma unroll
                     for (int b = 0; b < 4; ++b) {
                         const int r = 4 * w + b;
-                        const float v = __builtin_amdgcn_exp2f(KTOK ? y[kb][r] - mb : __builtin_fmaf(y[kb][r], sc, -mb));
+                        const float v = __builtin_amdgcn_exp2f(__builtin_fmaf(y[kb][r], sc, -mb));
                         l127 += v;
                         word = __builtin_amdgcn_cvt_pk_u8_f32(v, (unsigned)b, word);
                     }
