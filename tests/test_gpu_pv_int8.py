@@ -18,7 +18,7 @@ import torch
 import oracle
 import paper_2410_02367_amd as sage
 import sage_inputs as si
-from gpu_util import ABS_TOL, COS_TOL, assert_prepass_bit_exact, bits, to_dev
+from gpu_util import ABS_TOL, COS_TOL, assert_prepass_bit_exact, bits, to_dev, with_token_outliers
 
 pytestmark = pytest.mark.gpu
 
@@ -73,8 +73,8 @@ def assert_pv8_close(o_gpu, o_ref, l_ref, vs, what):
     return float(diff.max()), cos, frac
 
 
-def run_and_compare(w, block_q, block_k, what, v_seed=None):
-    q, k, v = si.full(w)
+def run_and_compare(w, block_q, block_k, what, v_seed=None, qkv=None):
+    q, k, v = si.full(w) if qkv is None else qkv
     if v_seed is not None:
         v = channel_scaled(v, v_seed)
     (q_i8, q_scale, k_i8, k_scale, _), (qq, qs, kq, ks, _) = assert_prepass_bit_exact(q, k, w.sm_scale, block_q, block_k)
@@ -106,6 +106,16 @@ def test_channel_scaled_v_parity(D, causal):
     print(f"[case] INT8 PV, V channels spread over 1.5 decades D{D} causal={causal}", flush=True)
     w = si.custom("v_channels", 1, 2, 700, D, causal, 128, 64, seed=si.BASE_SEED + 70 + D)
     run_and_compare(w, 128, 64, w.name, v_seed=5 + D)
+
+
+@pytest.mark.parametrize("D,causal,bq,bk", [(128, False, 128, 64), (64, True, 128, 64), (128, True, 1, 1)])
+def test_token_outliers_parity(D, causal, bq, bk):
+    # a few tokens 12x larger: large block scales, so that one unit of an integer score is a large
+    # step of the softmax argument and rows are sharply peaked (small l: every code counts)
+    print(f"[case] INT8 PV, outlier tokens D{D} causal={causal} scales {bq}x{bk}", flush=True)
+    w = si.custom("outlier_tokens", 1, 2, 900, D, causal, 128, 64, seed=si.BASE_SEED + 80 + D)
+    err, cos, frac = run_and_compare(w, bq, bk, w.name, qkv=with_token_outliers(w))
+    print(f"  max_abs {err:.2e} cos {cos:.7f} within 2e-3: {frac:.5f}", flush=True)
 
 
 def test_causal_first_row_is_the_dequantized_v0():
