@@ -1,4 +1,4 @@
-"""The three library calls enqueue kernels only (no allocation, no memset, no synchronization), so a
+"""The library calls enqueue kernels only (no allocation, no memset, no synchronization), so a
 caller may capture them into a HIP graph.  Every replay must reproduce the eager result bit for bit,
 also after the inputs changed in place and with eager work between the replays."""
 import numpy as np
@@ -12,9 +12,10 @@ from gpu_util import to_dev
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("block_q,block_k,rope", [(128, 64, False), (1, 1, False), (128, 64, True)])
-def test_graph_replays_equal_eager_runs(block_q, block_k, rope):
-    print(f"[case] graph capture blocks {block_q}x{block_k} rope={rope}", flush=True)
+@pytest.mark.parametrize("block_q,block_k,rope,pv8", [(128, 64, False, False), (1, 1, False, False), (128, 64, True, False),
+                                                      (128, 64, False, True)])
+def test_graph_replays_equal_eager_runs(block_q, block_k, rope, pv8):
+    print(f"[case] graph capture blocks {block_q}x{block_k} rope={rope} int8_pv={pv8}", flush=True)
     w = si.custom("graph", 2, 3, 457, 128, True, 128, 64, seed=si.BASE_SEED + 80)
     B, H, N, D = w.B, w.H, w.N, w.D
     inputs = [si.full(si.custom("graph", B, H, N, D, True, 128, 64, seed=si.BASE_SEED + 80 + i)) for i in range(3)]
@@ -26,6 +27,9 @@ def test_graph_replays_equal_eager_runs(block_q, block_k, rope):
     k_mean = torch.empty((B, H, D), dtype=torch.float32, device="cuda")
     ws = torch.empty(sage.sage_smooth_quant_k_workspace(B, H, N, D) // 8, dtype=torch.int64, device="cuda")
     out = torch.empty((B, H, N, D), dtype=torch.float16, device="cuda")
+    v_i8t = torch.empty((B, H, D, sage.sage_quant_v_pitch(N)), dtype=torch.int8, device="cuda")
+    v_scale = torch.empty((B, H, D), dtype=torch.float32, device="cuda")
+    ws_v = torch.empty(sage.sage_quant_v_workspace(B, H, N, D) // 4, dtype=torch.int32, device="cuda")
     pos = torch.arange(N, dtype=torch.float64, device="cuda")[:, None]
     freq = 10000.0 ** (-2.0 * torch.arange(D // 2, dtype=torch.float64, device="cuda") / D)[None, :]
     cs, sn = torch.cos(pos * freq).float().contiguous(), torch.sin(pos * freq).float().contiguous()
@@ -37,7 +41,11 @@ def test_graph_replays_equal_eager_runs(block_q, block_k, rope):
         else:
             sage.sage_smooth_quant_k(kd, block_k, k_i8, k_scale, k_mean, ws)
             sage.sage_quant_q(qd, w.sm_scale, block_q, q_i8, q_scale)
-        sage.sage_attn_fwd(q_i8, q_scale, k_i8, k_scale, vd, True, w.sm_scale, block_q, block_k, out)
+        if pv8:
+            sage.sage_quant_v(vd, v_i8t, v_scale, ws_v)
+            sage.sage_attn_pv_int8_fwd(q_i8, q_scale, k_i8, k_scale, v_i8t, v_scale, True, w.sm_scale, block_q, block_k, out)
+        else:
+            sage.sage_attn_fwd(q_i8, q_scale, k_i8, k_scale, vd, True, w.sm_scale, block_q, block_k, out)
 
     def set_inputs(i):
         q, k, v = inputs[i]
@@ -48,7 +56,7 @@ def test_graph_replays_equal_eager_runs(block_q, block_k, rope):
         set_inputs(i)
         step()
         torch.cuda.synchronize()
-        eager.append([t.clone() for t in (k_i8, k_scale, k_mean, q_i8, q_scale, out)])
+        eager.append([t.clone() for t in (k_i8, k_scale, k_mean, q_i8, q_scale, out, v_i8t, v_scale)])
     assert not torch.equal(eager[0][5], eager[1][5])
 
     set_inputs(0)
@@ -63,10 +71,11 @@ def test_graph_replays_equal_eager_runs(block_q, block_k, rope):
         step()
     for i in (1, 2, 0, 1):
         set_inputs(i)
-        for t in (k_i8, k_scale, k_mean, q_i8, q_scale, out, ws):
+        for t in (k_i8, k_scale, k_mean, q_i8, q_scale, out, ws, v_i8t, v_scale, ws_v):
             t.fill_(1)                            # eager work between replays; stale outputs must not survive
         torch.cuda.synchronize()
         graph.replay()
         torch.cuda.synchronize()
-        for got, want in zip((k_i8, k_scale, k_mean, q_i8, q_scale, out), eager[i]):
+        outs = (k_i8, k_scale, k_mean, q_i8, q_scale, out) + ((v_i8t, v_scale) if pv8 else ())
+        for got, want in zip(outs, eager[i]):
             assert torch.equal(got.view(torch.uint8), want.view(torch.uint8)), f"replay with inputs {i} differs from the eager run"
