@@ -29,6 +29,7 @@ HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 # run each, scaled by what the same counter reads for a 1 GiB copy kernel); the profiler cannot run
 # inside this script, so the figure of the committed summary under profiles/ is carried here.
 ATTN_TRAFFIC_BYTES = {"cfg3_prefill16k": 511.7e6}
+ATTN_TRAFFIC_BYTES_INT8_PV = {"cfg3_prefill16k": 423.8e6}
 
 
 def cpu_baseline(w, seconds_budget=20.0, per_token=False, gpu_out_head0=None, pv_int8=False):
@@ -310,7 +311,7 @@ def main():
             "peak": INT8_PEAK_TOPS,
             "unit": "TFLOP/s",
             "frac": attn_tops / INT8_PEAK_TOPS,
-            "traffic": None if per_token or pv_int8 else ATTN_TRAFFIC_BYTES.get(w.name),
+            "traffic": None if per_token else (ATTN_TRAFFIC_BYTES_INT8_PV if pv_int8 else ATTN_TRAFFIC_BYTES).get(w.name),
             "traffic_unit": "bytes per launch (algorithmic: %.1f MB)" % ((5.0 if pv_int8 else 6.0) * B * H * N * D / 1e6),
             "kernel": "sage_attn_pv8_kernel" if pv_int8 else "sage_attn_kernel",
             "note": ("achieved = counted ops (all INT8) / mean attention-kernel time from HIP events on the launch "
