@@ -132,7 +132,43 @@ def test_causal_first_row_is_the_dequantized_v0():
     assert np.all(np.abs(got - want) <= 2.0 ** -11 * np.abs(want) + 1e-6)
 
 
-FULL = [("cfg3_prefill16k", 5), ("cfg4_video", 4)]
+def test_int32_accumulator_is_flushed_periodically_when_the_maximum_never_changes():
+    # key 0 wins every row by a margin (channel 0 of Q is a constant 16, of K it is 3 at token 0 and 0
+    # elsewhere), so no row raises its maximum after the first tile; with 1094 key tiles the kernel's
+    # periodic flush (every 1024 tiles, against int32 overflow) is the only flush that runs
+    w = si.custom("flat_max", 1, 1, 70000, 64, False, 128, 64, seed=si.BASE_SEED + 90)
+    print(f"[case] INT8 PV periodic flush N{w.N} D{w.D}", flush=True)
+    q, k, v = si.full(w)
+    g = np.random.default_rng(90)
+    k = (g.standard_normal(k.shape) * 0.5).astype(np.float16)
+    q[..., 0] = 16.0
+    k[..., 0] = 0.0
+    k[..., 0, 0] = 3.0
+    qd, kd, vd = to_dev(q), to_dev(k), to_dev(v)
+    k_i8, k_scale, _ = sage.sage_smooth_quant_k(kd, 64)
+    q_i8, q_scale = sage.sage_quant_q(qd, w.sm_scale, 128)
+    v_i8t, v_scale = sage.sage_quant_v(vd)
+    o = sage.sage_attn_pv_int8_fwd(q_i8, q_scale, k_i8, k_scale, v_i8t, v_scale, False, w.sm_scale, 128, 64)
+    torch.cuda.synchronize()
+    kq, ks, _ = oracle.smooth_quant_k(k, 64)
+    qq, qs = oracle.quant_q(q, w.sm_scale, 128)
+    vq, vs = oracle.quant_v(v)
+    Tm = (w.N + 127) // 128
+    blocks = [0, Tm // 2, Tm - 1]
+    ref, l_ref = oracle.attn_pv8_slab(qq[0, 0], qs[0, 0], kq[0, 0], ks[0, 0], vq[0, 0], vs[0, 0], False, 128, 64,
+                                      q_blocks=blocks, return_l=True)
+    rows = np.concatenate([np.arange(i * 128, min(w.N, (i + 1) * 128)) for i in blocks])
+    # the premise: the running maximum of these rows is the score of key 0 (first tile) -- then
+    # 127 P~ of key 0 is 127 and l >= 1 is small because every other key is far below
+    s0 = oracle.qk_i32(qq[0, 0], kq[0, 0], 0, 128)
+    assert np.all(s0.argmax(axis=1) == 0)
+    err, cos, frac = assert_pv8_close(o[0, 0].cpu().numpy()[rows], ref[rows], l_ref[rows], vs[0, 0], "flat_max")
+    print(f"  max_abs {err:.2e} cos {cos:.7f} within 2e-3: {frac:.5f}; l in [{l_ref[rows].min():.2f}, {l_ref[rows].max():.2f}]", flush=True)
+
+
+# cfg5 (2048 key tiles per row) also exercises the periodic flush of the int32 accumulator: late rows go
+# more than 1024 tiles without a new maximum
+FULL = [("cfg3_prefill16k", 5), ("cfg4_video", 4), ("cfg5_prefill128k", 4)]
 
 
 @pytest.mark.parametrize("name,n_blocks", FULL, ids=[c[0] for c in FULL])
