@@ -1,5 +1,5 @@
 /*
- * libsage -- SageAttention forward pass (SAGEAttn-B and SAGEAttn-T) for AMD gfx950, C ABI.
+ * libsage -- SageAttention forward pass (SAGEAttn-B, -T, -vB and -vT) for AMD gfx950, C ABI.
  *
  * The three calls are the three stages of Algorithm 1 of the SageAttention paper:
  *   sage_smooth_quant_k : "Preprocessing" K = K - mean(K) (Section 4.2) followed by the per-block
@@ -11,6 +11,8 @@
  * A block size of 1 selects Section 3.2's per-token quantizer (one scale per token) instead of the
  * per-block one; block_q = block_k = 1 in all three calls is the SAGEAttn-T kernel of Section 4.5's
  * table of kernels.  The two sides are independent: any block_q goes with any block_k.
+ * sage_quant_v and sage_attn_pv_int8_fwd are the same loop with Section 4.3's INT8 second product
+ * (the -vB / -vT kernels of that table); sage_rope_* fuse RoPE into the two pre-pass calls.
  *
  * Conventions shared by every call
  *   - All pointers are DEVICE pointers (HIP global memory) unless stated; the library never
