@@ -108,7 +108,7 @@ def cpu_baseline(w, seconds_budget=20.0, per_token=False, gpu_out_head0=None, pv
     }
 
 
-def sweep(per_token: bool):
+def sweep(per_token: bool, pv_int8: bool = False):
     """Attention-kernel speed over sequence length, head dimension and mask (the axes of the paper's
     kernel-speed figures): N(0,1) inputs, H = 32, B = max(1, 16384 / N).  Prints one table row per
     shape; not part of the one-line benchmark contract."""
@@ -118,7 +118,8 @@ def sweep(per_token: bool):
 
     torch.cuda.set_device(0)
     bq, bk = (1, 1) if per_token else (128, 64)
-    print("scales: " + ("one per token" if per_token else "per block 128 x 64"))
+    print("scales: " + ("one per token" if per_token else "per block 128 x 64")
+          + ("; INT8 second product" if pv_int8 else "; FP16 second product"))
     print("%7s %4s %7s %3s  %10s %9s" % ("N", "D", "causal", "B", "attn ms", "TOPS"))
     for D in (64, 128):
         for causal in (False, True):
@@ -130,13 +131,21 @@ def sweep(per_token: bool):
                 k_i8, k_scale, _ = sage.sage_smooth_quant_k(k, bk)
                 q_i8, q_scale = sage.sage_quant_q(q, sm, bq)
                 out = torch.empty_like(v)
+                if pv_int8:
+                    v_i8t, v_scale = sage.sage_quant_v(v)
+
+                    def attn():
+                        sage.sage_attn_pv_int8_fwd(q_i8, q_scale, k_i8, k_scale, v_i8t, v_scale, causal, sm, bq, bk, out)
+                else:
+                    def attn():
+                        sage.sage_attn_fwd(q_i8, q_scale, k_i8, k_scale, v, causal, sm, bq, bk, out)
                 ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
                 for _ in range(3):
-                    sage.sage_attn_fwd(q_i8, q_scale, k_i8, k_scale, v, causal, sm, bq, bk, out)
+                    attn()
                 reps = 10
                 ev[0].record()
                 for _ in range(reps):
-                    sage.sage_attn_fwd(q_i8, q_scale, k_i8, k_scale, v, causal, sm, bq, bk, out)
+                    attn()
                 ev[1].record()
                 torch.cuda.synchronize()
                 ms = ev[0].elapsed_time(ev[1]) / reps
@@ -185,7 +194,7 @@ def main():
         sys.exit(2)
     sage.load()
     if args.sweep:
-        sweep(args.scales == "token")
+        sweep(args.scales == "token", args.pv == "int8")
         return
     w = si.WORKLOADS[args.workload]
     torch.cuda.set_device(0)
