@@ -170,6 +170,25 @@ def attn_l2(qq, q_scale, kq, k_scale, v, causal: bool, block_q: int, block_k: in
     return o
 
 
+def attn_l2_cross(qq, q_scale, kq, k_scale, v, causal: bool, block_q: int, block_k: int, flags: int = 0,
+                  gran_q: int | None = None, gran_k: int | None = None):
+    """Algorithm 1 with Nq queries against Nk keys: Q^ [B, H, Nq, D], K^ and V [B, H, Nk, D] -> fp16
+    [B, H, Nq, D].  The causal mask is aligned at the end (query t is token t + Nk - Nq); it needs Nq <= Nk."""
+    gran_q = block_q if gran_q is None else gran_q
+    gran_k = block_k if gran_k is None else gran_k
+    v = _f16(v); B, H, Nk, D = v.shape
+    qq = np.ascontiguousarray(qq, np.int8); kq = np.ascontiguousarray(kq, np.int8)
+    Nq = qq.shape[2]
+    q_scale = np.ascontiguousarray(q_scale, np.float32); k_scale = np.ascontiguousarray(k_scale, np.float32)
+    assert qq.shape == (B, H, Nq, D) and kq.shape == (B, H, Nk, D) and (not causal or Nq <= Nk)
+    assert q_scale.shape == (B, H, nblocks(Nq, gran_q)) and k_scale.shape == (B, H, nblocks(Nk, gran_k))
+    o = np.zeros((B, H, Nq, D), np.float16)
+    _L().sage_oracle_attn_l2_cross_g(_p(qq), _p(q_scale), _p(kq), _p(k_scale), _p(v),
+                                     *map(ctypes.c_int, (B, H, Nq, Nk, D, int(causal), block_q, block_k, gran_q, gran_k)),
+                                     ctypes.c_uint(flags), _p(o))
+    return o
+
+
 def attn_l2_slab(qq, q_scale, kq, k_scale, v, causal: bool, block_q: int, block_k: int,
                  q_blocks=None, flags: int = 0, gran_q: int | None = None, gran_k: int | None = None):
     """Algorithm 1 on one slab [N, D] for the listed Q blocks (all if None).

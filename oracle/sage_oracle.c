@@ -245,12 +245,16 @@ void sage_oracle_qk_i32(const int8_t* qq, const int8_t* kq, int N, int D, int ro
  * are not visited.
  * gq / gk = tokens per scale of Q^ / K^: equal to bq / bkv for Algorithm 1 (one scale per block of
  * the loop), 1 for the per-token quantizer of Section 3.2 (SAGEAttn-T): query t is dequantized
- * with q_scale[t / gq], key j with k_scale[j / gk]. */
+ * with q_scale[t / gq], key j with k_scale[j / gk].
+ * Nq queries against N keys: the paper treats Nq = N only (Section 3.1); with Nq != N nothing in
+ * Algorithm 1 changes except the ranges, and the causal mask is aligned at the end (query t is the
+ * token at position t + N - Nq, as when the last Nq tokens of a sequence attend to all of it). */
 static void l2_q_block(const int8_t* qq, const float* q_scale, const int8_t* kq, const float* k_scale,
-                       const uint16_t* v, int N, int D, int causal, int bq, int bkv, int gq, int gk,
+                       const uint16_t* v, int Nq, int N, int D, int causal, int bq, int bkv, int gq, int gk,
                        unsigned flags, int i, uint16_t* o) {
-    int r0 = i * bq, r1 = r0 + bq < N ? r0 + bq : N, nr = r1 - r0;
+    int r0 = i * bq, r1 = r0 + bq < Nq ? r0 + bq : Nq, nr = r1 - r0;
     int Tn = (N + bkv - 1) / bkv;
+    int shift = N - Nq;          /* causal with Nq != N: query t sits at position t + (N - Nq) among the keys */
     float* m = (float*)malloc(sizeof(float) * nr);
     float* l = (float*)malloc(sizeof(float) * nr);
     float* O = (float*)calloc((size_t)nr * D, sizeof(float));
@@ -260,7 +264,7 @@ static void l2_q_block(const int8_t* qq, const float* q_scale, const int8_t* kq,
 
     for (int j = 0; j < Tn; ++j) {
         int c0 = j * bkv, c1 = c0 + bkv < N ? c0 + bkv : N, nc = c1 - c0;
-        if (causal && c0 > r1 - 1) break;
+        if (causal && c0 > r1 - 1 + shift) break;
         /* S = Matmul(Q^_i, K^_j^T) * dQ[i] * dK[j], then the mask */
         for (int a = 0; a < nr; ++a)
             for (int b = 0; b < nc; ++b) {
@@ -269,7 +273,7 @@ static void l2_q_block(const int8_t* qq, const float* q_scale, const int8_t* kq,
                     acc += (int32_t)qq[(int64_t)(r0 + a) * D + c] * (int32_t)kq[(int64_t)(c0 + b) * D + c];
                 volatile float t1 = (float)acc * q_scale[(r0 + a) / gq];
                 volatile float t2 = t1 * k_scale[(c0 + b) / gk];
-                S[a * bkv + b] = (causal && (c0 + b) > (r0 + a)) ? -INFINITY : t2;
+                S[a * bkv + b] = (causal && (c0 + b) > (r0 + a + shift)) ? -INFINITY : t2;
             }
         /* online softmax and O update, row by row */
         for (int a = 0; a < nr; ++a) {
@@ -335,7 +339,7 @@ void sage_oracle_attn_l2_slab_g(const int8_t* qq, const float* q_scale, const in
 #pragma omp parallel for schedule(dynamic)
     for (int u = 0; u < n; ++u) {
         int i = nblocks < 0 ? u : blocks[u];
-        l2_q_block(qq, q_scale, kq, k_scale, v, N, D, causal, block_q, block_k, gran_q, gran_k, flags, i, o);
+        l2_q_block(qq, q_scale, kq, k_scale, v, N, N, D, causal, block_q, block_k, gran_q, gran_k, flags, i, o);
     }
 }
 /* Algorithm 1 proper: one scale per block of the loop. */
@@ -358,7 +362,7 @@ void sage_oracle_attn_l2_g(const int8_t* qq, const float* q_scale, const int8_t*
     for (int64_t u = 0; u < units; ++u) {
         int64_t s = u / Tm; int i = (int)(u % Tm);
         l2_q_block(qq + s * N * D, q_scale + s * nsq, kq + s * N * D, k_scale + s * nsk,
-                   v + s * N * D, N, D, causal, block_q, block_k, gran_q, gran_k, flags, i,
+                   v + s * N * D, N, N, D, causal, block_q, block_k, gran_q, gran_k, flags, i,
                    o + s * N * D);
     }
 }
@@ -367,6 +371,23 @@ void sage_oracle_attn_l2(const int8_t* qq, const float* q_scale, const int8_t* k
                          int block_q, int block_k, unsigned flags, uint16_t* o) {
     sage_oracle_attn_l2_g(qq, q_scale, kq, k_scale, v, B, H, N, D, causal, block_q, block_k,
                           block_q, block_k, flags, o);
+}
+
+/* Algorithm 1 with Nq queries against Nk keys on whole tensors: Q^ [B,H,Nq,D], K^ and V [B,H,Nk,D],
+ * scales [B,H,ceil(Nq/gran_q)] and [B,H,ceil(Nk/gran_k)], output [B,H,Nq,D].  Causal needs Nq <= Nk. */
+void sage_oracle_attn_l2_cross_g(const int8_t* qq, const float* q_scale, const int8_t* kq, const float* k_scale,
+                                 const uint16_t* v, int B, int H, int Nq, int Nk, int D, int causal,
+                                 int block_q, int block_k, int gran_q, int gran_k, unsigned flags, uint16_t* o) {
+    int Tm = (Nq + block_q - 1) / block_q;
+    int nsq = (Nq + gran_q - 1) / gran_q, nsk = (Nk + gran_k - 1) / gran_k;
+    int64_t units = (int64_t)B * H * Tm;
+#pragma omp parallel for schedule(dynamic)
+    for (int64_t u = 0; u < units; ++u) {
+        int64_t s = u / Tm; int i = (int)(u % Tm);
+        l2_q_block(qq + s * Nq * D, q_scale + s * nsq, kq + s * Nk * D, k_scale + s * nsk,
+                   v + s * Nk * D, Nq, Nk, D, causal, block_q, block_k, gran_q, gran_k, flags, i,
+                   o + s * Nq * D);
+    }
 }
 
 /* ------------------------------------------------------------------ Section 4.3: INT8 P~ and V (SAGEAttn-vB / -vT) */

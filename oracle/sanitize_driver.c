@@ -29,6 +29,8 @@ void sage_oracle_attn_l2_slab_g(const int8_t*, const float*, const int8_t*, cons
 void sage_oracle_attn_l1_slab(const int8_t*, const float*, const int8_t*, const float*, const uint16_t*, int, int, int,
                               int, int, int, int, double*);
 void sage_oracle_attn_l0_slab(const float*, const float*, const float*, int, int, int, double, int, int, double*);
+void sage_oracle_attn_l2_cross_g(const int8_t*, const float*, const int8_t*, const float*, const uint16_t*, int, int, int,
+                                 int, int, int, int, int, int, int, unsigned, uint16_t*);
 void sage_oracle_quant_v(const uint16_t*, int, int, int, int, int8_t*, float*);
 void sage_oracle_attn_pv8_g(const int8_t*, const float*, const int8_t*, const float*, const int8_t*, const float*, int, int,
                             int, int, int, int, int, int, int, uint16_t*, float*);
@@ -61,6 +63,20 @@ static void one_case(int B, int H, int N, int D, int bq, int bk, int gq, int gk,
     if (gq == bq && gk == bk) sage_oracle_attn_l2(qq, qs, kq, ks, v, B, H, N, D, causal, bq, bk, 2u, o);
     int Tm = (N + bq - 1) / bq, blocks[2] = {Tm - 1, 0};
     sage_oracle_attn_l2_slab_g(qq, qs, kq, ks, v, N, D, causal, bq, bk, gq, gk, 0, blocks, 2, o);
+    /* fewer queries than keys: the first Nq rows of Q^ of every slab are repacked as a [B,H,Nq,D] tensor */
+    {
+        int Nq = N > 3 ? N - 3 : N, nqc = (Nq + gq - 1) / gq;
+        int8_t* qc = malloc((size_t)B * H * Nq * D);
+        float* qsc = malloc(sizeof(float) * B * H * nqc);
+        uint16_t* oc = malloc(2 * (size_t)B * H * Nq * D);
+        for (int s = 0; s < B * H; ++s) {
+            memcpy(qc + (size_t)s * Nq * D, qq + (size_t)s * N * D, (size_t)Nq * D);
+            for (int g = 0; g < nqc; ++g) qsc[s * nqc + g] = qs[s * nq + g];
+        }
+        sage_oracle_attn_l2_cross_g(qc, qsc, kq, ks, v, B, H, Nq, N, D, causal, bq, bk, gq, gk, 0, oc);
+        *sum += oc[0];
+        free(qc); free(qsc); free(oc);
+    }
     int8_t* vq = malloc(E);
     float *vs = malloc(sizeof(float) * B * H * D), *ls = malloc(sizeof(float) * B * H * N);
     sage_oracle_quant_v(v, B, H, N, D, vq, vs);
