@@ -176,6 +176,23 @@ int sage_attn_pv_int8_fwd(const int8_t* q_i8, const float* q_scale,
                           int block_q, int block_k, void* stream);
 
 /*
+ * sage_attn_fwd with Nq queries against Nkv keys and values (cross-attention, or the last Nq tokens
+ * of a sequence attending to all of it).  The paper states Algorithm 1 for Nq = Nkv; nothing but
+ * the ranges changes.
+ *   q_i8 [B,H,Nq,D], q_scale [B,H,ceil(Nq/block_q)]     from sage_quant_q with N = Nq
+ *   k_i8 [B,H,Nkv,D], k_scale [B,H,ceil(Nkv/block_k)]   from sage_smooth_quant_k with N = Nkv
+ *   v_f16 [B,H,Nkv,D], o_f16 out [B,H,Nq,D]
+ *   causal   non-zero: query t is the token at position t + Nkv - Nq and sees keys j <= t + Nkv - Nq
+ *            (mask aligned at the end); needs Nq <= Nkv, else SAGE_ERR_UNSUPPORTED
+ * Everything else as sage_attn_fwd, which is this call with Nq = Nkv.
+ */
+int sage_attn_cross_fwd(const int8_t* q_i8, const float* q_scale,
+                        const int8_t* k_i8, const float* k_scale,
+                        const void* v_f16, void* o_f16,
+                        int B, int H, int Nq, int Nkv, int D, int causal, float sm_scale,
+                        int block_q, int block_k, void* stream);
+
+/*
  * Test hook: the raw int32 scores S^ = Q^ K^^T (Algorithm 1, the Matmul inside the S update)
  * produced by the same matrix-instruction code path as sage_attn_fwd, without mask.
  *   s_i32   out [B,H,N,N] int32 -- O(N^2) memory: meant for small N or for sub-problems.

@@ -8,6 +8,7 @@ from .binding import (  # noqa: F401
     SageError,
     lib_path,
     load,
+    sage_attn_cross_fwd,
     sage_attn_fwd,
     sage_attn_pv_int8_fwd,
     sage_attn_qk_i32_debug,

@@ -13,7 +13,8 @@ _lib = None
 EXPORTS = ("sage_status_string", "sage_quant_q", "sage_smooth_quant_k_workspace",
            "sage_smooth_quant_k", "sage_rope_quant_q", "sage_rope_smooth_quant_k",
            "sage_attn_fwd", "sage_attn_qk_i32_debug",
-           "sage_quant_v_workspace", "sage_quant_v_pitch", "sage_quant_v", "sage_attn_pv_int8_fwd")
+           "sage_quant_v_workspace", "sage_quant_v_pitch", "sage_quant_v", "sage_attn_pv_int8_fwd",
+           "sage_attn_cross_fwd")
 
 
 class SageError(RuntimeError):
@@ -56,6 +57,9 @@ def load() -> ctypes.CDLL:
                                   c_int, c_int, c_int, c_int, c_int, c_float, c_int, c_int, c_void_p]
     lib.sage_attn_qk_i32_debug.restype = c_int
     lib.sage_attn_qk_i32_debug.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_void_p]
+    lib.sage_attn_cross_fwd.restype = c_int
+    lib.sage_attn_cross_fwd.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                        c_int, c_int, c_int, c_int, c_int, c_int, c_float, c_int, c_int, c_void_p]
     lib.sage_quant_v_workspace.restype = c_size_t
     lib.sage_quant_v_workspace.argtypes = [c_int, c_int, c_int, c_int]
     lib.sage_quant_v_pitch.restype = c_int
@@ -193,6 +197,26 @@ def sage_attn_fwd(q_i8, q_scale, k_i8, k_scale, v, causal: bool, sm_scale: float
                               _stream(stream))
     if st != 0:
         raise SageError(st, "sage_attn_fwd")
+    return out
+
+
+def sage_attn_cross_fwd(q_i8, q_scale, k_i8, k_scale, v, causal: bool, sm_scale: float,
+                        block_q: int = 128, block_k: int = 64, out=None, stream=None):
+    """sage_attn_fwd with Nq queries (q_i8 [B,H,Nq,D]) against Nkv keys and values ([B,H,Nkv,D]) -> O [B,H,Nq,D];
+    the causal mask is aligned at the end (needs Nq <= Nkv)."""
+    B, H, Nkv, D = v.shape
+    Nq = q_i8.shape[2]
+    if tuple(q_i8.shape) != (B, H, Nq, D) or tuple(k_i8.shape) != (B, H, Nkv, D):
+        raise TypeError("q_i8 / k_i8: shapes do not match v")
+    if out is None:
+        out = torch.empty((B, H, Nq, D), dtype=torch.float16, device=v.device)
+    st = load().sage_attn_cross_fwd(_dev(q_i8, torch.int8, "q_i8"), _dev(q_scale, torch.float32, "q_scale"),
+                                    _dev(k_i8, torch.int8, "k_i8"), _dev(k_scale, torch.float32, "k_scale"),
+                                    _dev(v, torch.float16, "v"), _dev(out, torch.float16, "out"),
+                                    B, H, Nq, Nkv, D, int(bool(causal)), float(sm_scale), int(block_q), int(block_k),
+                                    _stream(stream))
+    if st != 0:
+        raise SageError(st, "sage_attn_cross_fwd")
     return out
 
 

@@ -113,7 +113,25 @@ int sage_attn_fwd(const int8_t* q_i8, const float* q_scale, const int8_t* k_i8, 
     if (!aligned(q_i8, 16) || !aligned(k_i8, 16) || !aligned(v_f16, 16) || !aligned(o_f16, 16) ||
         !aligned(q_scale, 4) || !aligned(k_scale, 4))
         return SAGE_ERR_ALIGN;
-    hipError_t e = sage::launch_attn(q_i8, q_scale, k_i8, k_scale, v_f16, o_f16, nullptr, B * H, N, D,
+    hipError_t e = sage::launch_attn(q_i8, q_scale, k_i8, k_scale, v_f16, o_f16, nullptr, B * H, N, N, D,
+                                     causal ? 1 : 0, block_q, block_k, (hipStream_t)stream);
+    return e == hipSuccess ? SAGE_OK : SAGE_ERR_LAUNCH;
+}
+
+int sage_attn_cross_fwd(const int8_t* q_i8, const float* q_scale, const int8_t* k_i8, const float* k_scale,
+                        const void* v_f16, void* o_f16, int B, int H, int Nq, int Nkv, int D, int causal,
+                        float sm_scale, int block_q, int block_k, void* stream) {
+    if (!q_i8 || !q_scale || !k_i8 || !k_scale || !v_f16 || !o_f16) return SAGE_ERR_NULL;
+    if (int e = check_shape(B, H, Nq, D)) return e;
+    if (int e = check_shape(B, H, Nkv, D)) return e;
+    if (causal && Nq > Nkv) return SAGE_ERR_UNSUPPORTED;        // a query before the first key would see nothing
+    if (!quant_block_ok(block_q)) return SAGE_ERR_UNSUPPORTED;
+    if (block_k != 1 && block_k != 64 && block_k != 128) return SAGE_ERR_UNSUPPORTED;
+    if (!std::isfinite(sm_scale) || !(sm_scale > 0.0f)) return SAGE_ERR_VALUE;
+    if (!aligned(q_i8, 16) || !aligned(k_i8, 16) || !aligned(v_f16, 16) || !aligned(o_f16, 16) ||
+        !aligned(q_scale, 4) || !aligned(k_scale, 4))
+        return SAGE_ERR_ALIGN;
+    hipError_t e = sage::launch_attn(q_i8, q_scale, k_i8, k_scale, v_f16, o_f16, nullptr, B * H, Nq, Nkv, D,
                                      causal ? 1 : 0, block_q, block_k, (hipStream_t)stream);
     return e == hipSuccess ? SAGE_OK : SAGE_ERR_LAUNCH;
 }
@@ -161,7 +179,7 @@ int sage_attn_qk_i32_debug(const int8_t* q_i8, const int8_t* k_i8, int32_t* s_i3
     if (!aligned(q_i8, 16) || !aligned(k_i8, 16) || !aligned(s_i32, 4)) return SAGE_ERR_ALIGN;
     // scales are not read by the dump path; pass the tensor pointers as placeholders of valid memory
     hipError_t e = sage::launch_attn(q_i8, (const float*)q_i8, k_i8, (const float*)k_i8, nullptr, nullptr, s_i32,
-                                     B * H, N, D, 0, 128, 64, (hipStream_t)stream);
+                                     B * H, N, N, D, 0, 128, 64, (hipStream_t)stream);
     return e == hipSuccess ? SAGE_OK : SAGE_ERR_LAUNCH;
 }
 

@@ -225,7 +225,7 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
                  const int8_t* __restrict__ ki, const float* __restrict__ ksc,
                  const _Float16* __restrict__ vg, _Float16* __restrict__ og,
                  int32_t* __restrict__ sdump,
-                 int N, int shift_q, int shift_k, int tiles_q, int per_xcd, long total_tiles) {
+                 int Nq, int N, int shift_q, int shift_k, int tiles_q, int per_xcd, long total_tiles) {
     constexpr int NWAVES = NW, NTHREADS = NW * 64;
     constexpr int QTILE = NW * WROWS;   // query rows per workgroup
     constexpr int KROW = D;             // bytes per K^ row in LDS
@@ -256,8 +256,11 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);     // wave-uniform: keeps control flow scalar
     const int ql = lane & 31, g = lane >> 5;
     const int qrow0 = qt * QTILE + wave * WROWS;     // first row of the wavefront; sub-tile qs starts 32*qs later
-    const size_t slab = (size_t)bh * N;
-    const int nbq = (N + (1 << shift_q) - 1) >> shift_q, nbk = (N + (1 << shift_k) - 1) >> shift_k;
+    // Nq query rows against N keys per slab (the paper's setting is Nq = N).  With a causal mask the
+    // queries are the LAST Nq tokens: query row t sits at position t + coff among the keys.
+    const size_t slab = (size_t)bh * N, slab_q = (size_t)bh * Nq;
+    const int coff = N - Nq;
+    const int nbq = (Nq + (1 << shift_q) - 1) >> shift_q, nbk = (N + (1 << shift_k) - 1) >> shift_k;
 
     // Q^ operands (B matrix of S^T = K^ Q^^T) stay in accumulator registers for the whole kernel.
     v4i qreg[QS][KS];
@@ -268,12 +271,12 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             qreg[qs][ks] = (v4i){0, 0, 0, 0};
-            if (q_row < N) qreg[qs][ks] = *(const v4i*)(qi + (slab + q_row) * D + ks * 32 + g * 16);
+            if (q_row < Nq) qreg[qs][ks] = *(const v4i*)(qi + (slab_q + q_row) * D + ks * 32 + g * 16);
             pin_a(qreg[qs][ks]);
         }
         dq[qs] = 0.0f;
         if (!DUMP) {
-            const int rc = q_row < N ? q_row : N - 1;             // the lane's own query: any block_q down to 1
+            const int rc = q_row < Nq ? q_row : Nq - 1;           // the lane's own query: any block_q down to 1
             dq[qs] = qsc[(size_t)bh * nbq + (rc >> shift_q)] * LOG2E;
         }
     }
@@ -305,9 +308,9 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
     const int kv_tiles_all = (N + KTILE - 1) / KTILE;
     int T = kv_tiles_all, Tw = kv_tiles_all;
     if (CAUSAL && !DUMP) {
-        int last = (qt * QTILE + QTILE - 1) / KTILE + 1;
+        int last = (qt * QTILE + QTILE - 1 + coff) / KTILE + 1;
         T = last < kv_tiles_all ? last : kv_tiles_all;
-        last = (qrow0 + WROWS - 1) / KTILE + 1;
+        last = (qrow0 + WROWS - 1 + coff) / KTILE + 1;
         Tw = last < T ? last : T;
     }
 
@@ -484,7 +487,7 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
             const int jn = j + 1 < kv_tiles_all ? j + 1 : j;
             dk_next = ksc_bh[(jn * KTILE) >> shift_k];
         }
-        const bool need_mask = (kv0 + KTILE > N) || (CAUSAL && kv0 + KTILE - 1 > qrow0);
+        const bool need_mask = (kv0 + KTILE > N) || (CAUSAL && kv0 + KTILE - 1 > qrow0 + coff);
 #pragma unroll
         for (int qs = 0; qs < QS; ++qs) {
             // a zero scale (all-zero quantization block) would turn -inf * scale into NaN
@@ -522,7 +525,7 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
                         int key = kv0 + 32 * s + 8 * (r >> 2) + 4 * g + (r & 3);
-                        bool hide = (key >= N) || (CAUSAL && key > q_row);
+                        bool hide = (key >= N) || (CAUSAL && key > q_row + coff);
                         acc_s[qs][s][r] = hide ? (int)0xFF800000 : acc_s[qs][s][r];
                     }
             }
@@ -804,7 +807,7 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     int key = kv0 + 32 * s + 8 * (r >> 2) + 4 * g + (r & 3);
-                    if (q_row < N && key < N) sdump[(slab + q_row) * (size_t)N + key] = acc_s[qs][s][r] - MAGIC_I;
+                    if (q_row < Nq && key < N) sdump[(slab_q + q_row) * (size_t)N + key] = acc_s[qs][s][r] - MAGIC_I;
                 }
         }
     };
@@ -907,8 +910,8 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
         for (int dt = 0; dt < DT; ++dt) refresh(acc_o[qs][dt]);
         const float l_half = acc_l[qs][0][0] + acc_l[qs][1][0];            // this lane's keys
         const float inv = 1.0f / (l_half + as_f32(swap32i(as_i32(l_half))));   // + those of the lane 32 away
-        if (q_row < N) {
-            _Float16* orow = og + (slab + q_row) * D;
+        if (q_row < Nq) {
+            _Float16* orow = og + (slab_q + q_row) * D;
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
@@ -924,10 +927,10 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
 
 template <int D, int NW>
 static hipError_t launch_dn(const int8_t* qq, const float* qscale, const int8_t* kq, const float* kscale,
-                            const void* v, void* o, int32_t* sdump, int BH, int N, int causal,
+                            const void* v, void* o, int32_t* sdump, int BH, int Nq, int N, int causal,
                             int block_q, int block_k, hipStream_t st) {
     constexpr int QTILE = NW * WROWS, NTHREADS = NW * 64;
-    const int tiles_q = (N + QTILE - 1) / QTILE;
+    const int tiles_q = (Nq + QTILE - 1) / QTILE;
     const long total = (long)BH * tiles_q;
     const int per_xcd = (int)((total + 7) / 8);
     dim3 grid((unsigned)(per_xcd * 8));
@@ -935,7 +938,7 @@ static hipError_t launch_dn(const int8_t* qq, const float* qscale, const int8_t*
     const _Float16* vp = (const _Float16*)v;
     _Float16* op = (_Float16*)o;
     const bool ktok = block_k == 1;
-#define SAGE_LAUNCH(C, DMP, KT) sage_attn_kernel<D, NW, C, DMP, KT><<<grid, NTHREADS, 0, st>>>(qq, qscale, kq, kscale, vp, op, sdump, N, shift_q, shift_k, tiles_q, per_xcd, total)
+#define SAGE_LAUNCH(C, DMP, KT) sage_attn_kernel<D, NW, C, DMP, KT><<<grid, NTHREADS, 0, st>>>(qq, qscale, kq, kscale, vp, op, sdump, Nq, N, shift_q, shift_k, tiles_q, per_xcd, total)
     // per-token key scales need a few more registers than 4-wavefront workgroups at D = 128 have
     // (two workgroups per CU: 128 + 128 registers); launch_d() never asks for that combination
     constexpr bool KTOK_OK = !(D == 128 && NW == 4);
@@ -956,7 +959,7 @@ static hipError_t launch_dn(const int8_t* qq, const float* qscale, const int8_t*
 
 template <int D>
 static hipError_t launch_d(const int8_t* qq, const float* qscale, const int8_t* kq, const float* kscale,
-                           const void* v, void* o, int32_t* sdump, int BH, int N, int causal,
+                           const void* v, void* o, int32_t* sdump, int BH, int Nq, int N, int causal,
                            int block_q, int block_k, hipStream_t st) {
     // 256-row workgroups (8 wavefronts sharing one set of LDS tiles) for long sequences at D = 128;
     // 128-row workgroups, two or three per CU, for D = 64, whenever the larger tile would leave CUs
@@ -964,18 +967,18 @@ static hipError_t launch_d(const int8_t* qq, const float* qscale, const int8_t* 
     // visits few tiles and the finer causal staircase and the independent progress of the small
     // workgroups matter more than the sharing (measured at D = 128: +30 % at N = 1K causal, +11 %
     // non-causal; +19 % / +2 % at 2K; +4 % / -3 % at 4K).
-    const long big_tiles = (long)BH * ((N + 8 * WROWS - 1) / (8 * WROWS));
+    const long big_tiles = (long)BH * ((Nq + 8 * WROWS - 1) / (8 * WROWS));
     const bool short_seq = N <= 2048 || (causal && N <= 4096);
     const bool small = QS == 1 && (D == 64 || ((big_tiles < 2 * 256 || short_seq) && block_k != 1 && !sdump));
-    if (small) return launch_dn<D, 4>(qq, qscale, kq, kscale, v, o, sdump, BH, N, causal, block_q, block_k, st);
-    return launch_dn<D, 8>(qq, qscale, kq, kscale, v, o, sdump, BH, N, causal, block_q, block_k, st);
+    if (small) return launch_dn<D, 4>(qq, qscale, kq, kscale, v, o, sdump, BH, Nq, N, causal, block_q, block_k, st);
+    return launch_dn<D, 8>(qq, qscale, kq, kscale, v, o, sdump, BH, Nq, N, causal, block_q, block_k, st);
 }
 
 hipError_t launch_attn(const int8_t* qq, const float* qscale, const int8_t* kq, const float* kscale,
-                       const void* v, void* o, int32_t* sdump, int BH, int N, int D, int causal,
+                       const void* v, void* o, int32_t* sdump, int BH, int Nq, int N, int D, int causal,
                        int block_q, int block_k, hipStream_t st) {
-    if (D == 64) return launch_d<64>(qq, qscale, kq, kscale, v, o, sdump, BH, N, causal, block_q, block_k, st);
-    return launch_d<128>(qq, qscale, kq, kscale, v, o, sdump, BH, N, causal, block_q, block_k, st);
+    if (D == 64) return launch_d<64>(qq, qscale, kq, kscale, v, o, sdump, BH, Nq, N, causal, block_q, block_k, st);
+    return launch_d<128>(qq, qscale, kq, kscale, v, o, sdump, BH, Nq, N, causal, block_q, block_k, st);
 }
 
 }  // namespace sage

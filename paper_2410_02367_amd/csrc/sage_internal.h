@@ -13,9 +13,10 @@ hipError_t launch_smooth_quant_k(const void* k, int8_t* kq, float* kscale, float
                                  long long* sums, int BH, int N, int D, int block,
                                  const float* cs, const float* sn, hipStream_t st);
 
-// Fused attention (MFMA-bound).  sdump != nullptr selects the int32 score dump.
+// Fused attention (MFMA-bound): Nq query rows against N keys per slab.  sdump != nullptr selects the
+// int32 score dump.
 hipError_t launch_attn(const int8_t* qq, const float* qscale, const int8_t* kq, const float* kscale,
-                       const void* v, void* o, int32_t* sdump, int BH, int N, int D, int causal,
+                       const void* v, void* o, int32_t* sdump, int BH, int Nq, int N, int D, int causal,
                        int block_q, int block_k, hipStream_t st);
 
 // INT8 second product (Section 4.3): per-channel quantizer of V (transposed output, pitch

@@ -97,3 +97,16 @@ def test_int8_second_product_calls_validate_like_the_others(lib):
     assert lib.sage_attn_pv_int8_fwd(good, good, good, good, good, good, good, *args, f(0.125), 128, 32, None) == 3
     assert lib.sage_attn_pv_int8_fwd(good, good, good, good, good, good, good, *args, f(float("nan")), 128, 64, None) == 7
     assert lib.sage_attn_pv_int8_fwd(good, good, good, good, good, odd, good, *args, f(0.125), 128, 64, None) == 5
+
+
+def test_cross_attention_call_validates_both_lengths(lib):
+    f = ctypes.c_float
+    good = ctypes.c_void_p(0x1000)
+    odd = ctypes.c_void_p(0x1004)
+    assert lib.sage_attn_cross_fwd(good, good, good, good, good, None, 1, 1, 64, 64, 64, 0, f(0.125), 128, 64, None) == 1
+    assert lib.sage_attn_cross_fwd(good, good, good, good, good, good, 1, 1, 0, 64, 64, 0, f(0.125), 128, 64, None) == 2
+    assert lib.sage_attn_cross_fwd(good, good, good, good, good, good, 1, 1, 64, (1 << 23) + 1, 64, 0, f(0.125), 128, 64, None) == 2
+    assert lib.sage_attn_cross_fwd(good, good, good, good, good, good, 1, 1, 65, 64, 64, 1, f(0.125), 128, 64, None) == 3
+    assert lib.sage_attn_cross_fwd(good, good, good, good, good, good, 1, 1, 64, 64, 64, 0, f(0.125), 128, 32, None) == 3
+    assert lib.sage_attn_cross_fwd(good, good, good, good, good, good, 1, 1, 64, 64, 64, 0, f(0.0), 128, 64, None) == 7
+    assert lib.sage_attn_cross_fwd(good, good, odd, good, good, good, 1, 1, 64, 64, 64, 0, f(0.125), 128, 64, None) == 5
