@@ -245,6 +245,27 @@ def attn_pv8(qq, q_scale, kq, k_scale, vq, v_scale, causal: bool, block_q: int, 
     return (o, lsum) if return_l else o
 
 
+def attn_pv8_cross(qq, q_scale, kq, k_scale, vq, v_scale, causal: bool, block_q: int, block_k: int,
+                   gran_q: int | None = None, gran_k: int | None = None, return_l: bool = False):
+    """attn_pv8 with Nq queries (Q^ [B, H, Nq, D]) against Nk keys (K^, V^ [B, H, Nk, D]); end-aligned causal mask."""
+    gran_q = block_q if gran_q is None else gran_q
+    gran_k = block_k if gran_k is None else gran_k
+    vq = np.ascontiguousarray(vq, np.int8); B, H, Nk, D = vq.shape
+    qq = np.ascontiguousarray(qq, np.int8); kq = np.ascontiguousarray(kq, np.int8)
+    Nq = qq.shape[2]
+    q_scale = np.ascontiguousarray(q_scale, np.float32); k_scale = np.ascontiguousarray(k_scale, np.float32)
+    v_scale = np.ascontiguousarray(v_scale, np.float32)
+    assert qq.shape == (B, H, Nq, D) and kq.shape == (B, H, Nk, D) and v_scale.shape == (B, H, D)
+    assert q_scale.shape == (B, H, nblocks(Nq, gran_q)) and k_scale.shape == (B, H, nblocks(Nk, gran_k))
+    assert not causal or Nq <= Nk
+    o = np.zeros((B, H, Nq, D), np.float16)
+    lsum = np.zeros((B, H, Nq), np.float32)
+    _L().sage_oracle_attn_pv8_cross_g(_p(qq), _p(q_scale), _p(kq), _p(k_scale), _p(vq), _p(v_scale),
+                                      *map(ctypes.c_int, (B, H, Nq, Nk, D, int(causal), block_q, block_k, gran_q, gran_k)),
+                                      _p(o), _p(lsum))
+    return (o, lsum) if return_l else o
+
+
 def attn_pv8_slab(qq, q_scale, kq, k_scale, vq, v_scale, causal: bool, block_q: int, block_k: int,
                   q_blocks=None, gran_q: int | None = None, gran_k: int | None = None, return_l: bool = False):
     """attn_pv8 on one slab [N, D] for the listed Q blocks (all if None); other rows stay zero."""

@@ -432,10 +432,11 @@ void sage_oracle_quant_v(const uint16_t* v, int B, int H, int N, int D, int8_t* 
  * lsum (may be NULL) receives the final l of every row of the block (rows i*bq ...), which bounds
  * what one code of P^ is worth in the output: delta_V[c] * |V^| / (127 l) * 127 <= delta_V[c] / l. */
 static void l2_pv8_q_block(const int8_t* qq, const float* q_scale, const int8_t* kq, const float* k_scale,
-                           const int8_t* vq, const float* v_scale, int N, int D, int causal,
+                           const int8_t* vq, const float* v_scale, int Nq, int N, int D, int causal,
                            int bq, int bkv, int gq, int gk, int i, uint16_t* o, float* lsum) {
-    int r0 = i * bq, r1 = r0 + bq < N ? r0 + bq : N, nr = r1 - r0;
+    int r0 = i * bq, r1 = r0 + bq < Nq ? r0 + bq : Nq, nr = r1 - r0;
     int Tn = (N + bkv - 1) / bkv;
+    int shift = N - Nq;          /* Nq queries against N keys: end-aligned causal mask, as in l2_q_block */
     float* m = (float*)malloc(sizeof(float) * nr);
     float* l = (float*)malloc(sizeof(float) * nr);
     float* O = (float*)calloc((size_t)nr * D, sizeof(float));
@@ -446,7 +447,7 @@ static void l2_pv8_q_block(const int8_t* qq, const float* q_scale, const int8_t*
 
     for (int j = 0; j < Tn; ++j) {
         int c0 = j * bkv, c1 = c0 + bkv < N ? c0 + bkv : N, nc = c1 - c0;
-        if (causal && c0 > r1 - 1) break;
+        if (causal && c0 > r1 - 1 + shift) break;
         for (int a = 0; a < nr; ++a)
             for (int b = 0; b < nc; ++b) {
                 int32_t acc = 0;
@@ -454,7 +455,7 @@ static void l2_pv8_q_block(const int8_t* qq, const float* q_scale, const int8_t*
                     acc += (int32_t)qq[(int64_t)(r0 + a) * D + c] * (int32_t)kq[(int64_t)(c0 + b) * D + c];
                 volatile float t1 = (float)acc * q_scale[(r0 + a) / gq];
                 volatile float t2 = t1 * k_scale[(c0 + b) / gk];
-                S[a * bkv + b] = (causal && (c0 + b) > (r0 + a)) ? -INFINITY : t2;
+                S[a * bkv + b] = (causal && (c0 + b) > (r0 + a + shift)) ? -INFINITY : t2;
             }
         for (int a = 0; a < nr; ++a) {
             float m_old = m[a], m_new = m_old;
@@ -504,7 +505,7 @@ void sage_oracle_attn_pv8_slab_g(const int8_t* qq, const float* q_scale, const i
 #pragma omp parallel for schedule(dynamic)
     for (int u = 0; u < n; ++u) {
         int i = nblocks < 0 ? u : blocks[u];
-        l2_pv8_q_block(qq, q_scale, kq, k_scale, vq, v_scale, N, D, causal, block_q, block_k,
+        l2_pv8_q_block(qq, q_scale, kq, k_scale, vq, v_scale, N, N, D, causal, block_q, block_k,
                        gran_q, gran_k, i, o, lsum);
     }
 }
@@ -520,8 +521,25 @@ void sage_oracle_attn_pv8_g(const int8_t* qq, const float* q_scale, const int8_t
     for (int64_t u = 0; u < units; ++u) {
         int64_t s = u / Tm; int i = (int)(u % Tm);
         l2_pv8_q_block(qq + s * N * D, q_scale + s * nsq, kq + s * N * D, k_scale + s * nsk,
-                       vq + s * N * D, v_scale + s * D, N, D, causal, block_q, block_k, gran_q, gran_k,
+                       vq + s * N * D, v_scale + s * D, N, N, D, causal, block_q, block_k, gran_q, gran_k,
                        i, o + s * N * D, lsum ? lsum + s * N : NULL);
+    }
+}
+
+/* The same with Nq queries against Nk keys: Q^ [B,H,Nq,D], K^ and V^ [B,H,Nk,D], output and lsum over Nq rows. */
+void sage_oracle_attn_pv8_cross_g(const int8_t* qq, const float* q_scale, const int8_t* kq, const float* k_scale,
+                                  const int8_t* vq, const float* v_scale, int B, int H, int Nq, int Nk, int D,
+                                  int causal, int block_q, int block_k, int gran_q, int gran_k,
+                                  uint16_t* o, float* lsum) {
+    int Tm = (Nq + block_q - 1) / block_q;
+    int nsq = (Nq + gran_q - 1) / gran_q, nsk = (Nk + gran_k - 1) / gran_k;
+    int64_t units = (int64_t)B * H * Tm;
+#pragma omp parallel for schedule(dynamic)
+    for (int64_t u = 0; u < units; ++u) {
+        int64_t s = u / Tm; int i = (int)(u % Tm);
+        l2_pv8_q_block(qq + s * Nq * D, q_scale + s * nsq, kq + s * Nk * D, k_scale + s * nsk,
+                       vq + s * Nk * D, v_scale + s * D, Nq, Nk, D, causal, block_q, block_k, gran_q, gran_k,
+                       i, o + s * Nq * D, lsum ? lsum + s * Nq : NULL);
     }
 }
 

@@ -74,3 +74,37 @@ def test_constant_k_gives_the_mean_of_the_visible_values():
     vf = v[0, 0].astype(np.float64)
     want = np.stack([vf[:Nk - Nq + t + 1].mean(0) for t in range(Nq)])
     assert np.abs(o - want).max() <= 1e-3
+
+
+# ------------------------------------------------------------------ the same for the INT8 second product
+
+def test_pv8_cross_reduces_to_the_self_attention_entry_and_to_its_last_rows():
+    q, k, v = rand_qkv(16, 320, 64, k_bias=2.0)
+    kq, ks, _ = oracle.smooth_quant_k(k[None, None], 64)
+    qq, qs = oracle.quant_q(q[None, None], 0.125, 1)
+    vq, vs = oracle.quant_v(v[None, None])
+    for causal in (False, True):
+        a, la = oracle.attn_pv8(qq, qs, kq, ks, vq, vs, causal, 64, 64, gran_q=1, return_l=True)
+        b, lb = oracle.attn_pv8_cross(qq, qs, kq, ks, vq, vs, causal, 64, 64, gran_q=1, return_l=True)
+        assert np.array_equal(a.view(np.uint16), b.view(np.uint16)) and np.array_equal(la, lb)
+    tail, lt = oracle.attn_pv8_cross(np.ascontiguousarray(qq[:, :, 256:]), np.ascontiguousarray(qs[:, :, 256:]), kq, ks,
+                                     vq, vs, True, 64, 64, gran_q=1, return_l=True)
+    assert np.array_equal(a[:, :, 256:].view(np.uint16), tail.view(np.uint16)) and np.array_equal(la[:, :, 256:], lt)
+
+
+def test_pv8_cross_matches_the_numpy_recursion():
+    from test_oracle_pv8 import brute_pv8
+    g = np.random.default_rng(31)
+    Nq, Nk, D = 90, 210, 32
+    qq = g.integers(-127, 128, (Nk, D), dtype=np.int8); kq = g.integers(-127, 128, (Nk, D), dtype=np.int8)
+    vq = g.integers(-127, 128, (Nk, D), dtype=np.int8)
+    dq = (g.uniform(0.2, 3.0, Nk) * 2e-3).astype(np.float32); dk = (g.uniform(0.2, 3.0, Nk) * 2e-3).astype(np.float32)
+    dv = g.uniform(0.01, 0.1, D).astype(np.float32)
+    # the numpy recursion on the full square problem; its last Nq rows are the causal cross problem when
+    # the Q block boundaries coincide (Nk - Nq = 120 is not a multiple of 64: use Q blocks of 30 rows)
+    ref, l_ref = brute_pv8(qq, dq, kq, dk, vq, dv, True, 30, 32)
+    o, l = oracle.attn_pv8_cross(np.ascontiguousarray(qq[None, None, Nk - Nq:]), dq[None, None, Nk - Nq:], kq[None, None],
+                                 dk[None, None], vq[None, None], dv[None, None], True, 30, 32, gran_q=1, gran_k=1, return_l=True)
+    assert np.allclose(l[0, 0], l_ref[Nk - Nq:], rtol=1e-5)
+    diff = np.abs(o[0, 0].astype(np.float64) - ref[Nk - Nq:])
+    assert np.all(diff <= 1e-3 + 2.0 * dv[None, :] / l_ref[Nk - Nq:, None])
