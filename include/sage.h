@@ -193,6 +193,17 @@ int sage_attn_cross_fwd(const int8_t* q_i8, const float* q_scale,
                         int block_q, int block_k, void* stream);
 
 /*
+ * sage_attn_pv_int8_fwd with Nq queries against Nkv keys and values: the lengths, the layouts of
+ * q_i8 / q_scale / o_f16 (Nq) and of k_i8 / k_scale / v_i8t / v_scale (Nkv; v_i8t from sage_quant_v
+ * with N = Nkv) and the end-aligned causal mask are those of sage_attn_cross_fwd.
+ */
+int sage_attn_pv_int8_cross_fwd(const int8_t* q_i8, const float* q_scale,
+                                const int8_t* k_i8, const float* k_scale,
+                                const int8_t* v_i8t, const float* v_scale, void* o_f16,
+                                int B, int H, int Nq, int Nkv, int D, int causal, float sm_scale,
+                                int block_q, int block_k, void* stream);
+
+/*
  * Test hook: the raw int32 scores S^ = Q^ K^^T (Algorithm 1, the Matmul inside the S update)
  * produced by the same matrix-instruction code path as sage_attn_fwd, without mask.
  *   s_i32   out [B,H,N,N] int32 -- O(N^2) memory: meant for small N or for sub-problems.

@@ -10,6 +10,7 @@ from .binding import (  # noqa: F401
     load,
     sage_attn_cross_fwd,
     sage_attn_fwd,
+    sage_attn_pv_int8_cross_fwd,
     sage_attn_pv_int8_fwd,
     sage_attn_qk_i32_debug,
     sage_quant_q,

@@ -14,7 +14,7 @@ EXPORTS = ("sage_status_string", "sage_quant_q", "sage_smooth_quant_k_workspace"
            "sage_smooth_quant_k", "sage_rope_quant_q", "sage_rope_smooth_quant_k",
            "sage_attn_fwd", "sage_attn_qk_i32_debug",
            "sage_quant_v_workspace", "sage_quant_v_pitch", "sage_quant_v", "sage_attn_pv_int8_fwd",
-           "sage_attn_cross_fwd")
+           "sage_attn_cross_fwd", "sage_attn_pv_int8_cross_fwd")
 
 
 class SageError(RuntimeError):
@@ -60,6 +60,8 @@ def load() -> ctypes.CDLL:
     lib.sage_attn_cross_fwd.restype = c_int
     lib.sage_attn_cross_fwd.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                         c_int, c_int, c_int, c_int, c_int, c_int, c_float, c_int, c_int, c_void_p]
+    lib.sage_attn_pv_int8_cross_fwd.restype = c_int
+    lib.sage_attn_pv_int8_cross_fwd.argtypes = [c_void_p] * 7 + [c_int] * 6 + [c_float, c_int, c_int, c_void_p]
     lib.sage_quant_v_workspace.restype = c_size_t
     lib.sage_quant_v_workspace.argtypes = [c_int, c_int, c_int, c_int]
     lib.sage_quant_v_pitch.restype = c_int
@@ -267,6 +269,27 @@ def sage_attn_pv_int8_fwd(q_i8, q_scale, k_i8, k_scale, v_i8t, v_scale, causal: 
                                       _stream(stream))
     if st != 0:
         raise SageError(st, "sage_attn_pv_int8_fwd")
+    return out
+
+
+def sage_attn_pv_int8_cross_fwd(q_i8, q_scale, k_i8, k_scale, v_i8t, v_scale, causal: bool, sm_scale: float,
+                                block_q: int = 128, block_k: int = 64, out=None, stream=None):
+    """sage_attn_pv_int8_fwd with Nq queries (q_i8 [B,H,Nq,D]) against Nkv keys (k_i8 [B,H,Nkv,D], v_i8t from
+    sage_quant_v of the Nkv values) -> O [B,H,Nq,D]; end-aligned causal mask (needs Nq <= Nkv)."""
+    B, H, Nq, D = q_i8.shape
+    Nkv = k_i8.shape[2]
+    if tuple(k_i8.shape) != (B, H, Nkv, D) or tuple(v_i8t.shape) != (B, H, D, sage_quant_v_pitch(Nkv)):
+        raise TypeError("k_i8 / v_i8t: shapes do not match q_i8")
+    if out is None:
+        out = torch.empty((B, H, Nq, D), dtype=torch.float16, device=q_i8.device)
+    st = load().sage_attn_pv_int8_cross_fwd(_dev(q_i8, torch.int8, "q_i8"), _dev(q_scale, torch.float32, "q_scale"),
+                                            _dev(k_i8, torch.int8, "k_i8"), _dev(k_scale, torch.float32, "k_scale"),
+                                            _dev(v_i8t, torch.int8, "v_i8t"), _dev(v_scale, torch.float32, "v_scale"),
+                                            _dev(out, torch.float16, "out"),
+                                            B, H, Nq, Nkv, D, int(bool(causal)), float(sm_scale), int(block_q), int(block_k),
+                                            _stream(stream))
+    if st != 0:
+        raise SageError(st, "sage_attn_pv_int8_cross_fwd")
     return out
 
 

@@ -77,7 +77,7 @@ sage_attn_pv8_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qs
                      const int8_t* __restrict__ ki, const float* __restrict__ ksc,
                      const int8_t* __restrict__ vt, const float* __restrict__ vsc,
                      _Float16* __restrict__ og,
-                     int N, int Np, int shift_q, int shift_k, int tiles_q, int per_xcd, long total_tiles) {
+                     int Nq, int N, int Np, int shift_q, int shift_k, int tiles_q, int per_xcd, long total_tiles) {
     constexpr int NT = 256, QTILE = 128, KT = 64;
     constexpr int KS = D / 32, DT = D / 32;
     constexpr int KB = KT * D, VB = D * KT;            // bytes per K^ tile / V^^T tile
@@ -99,24 +99,26 @@ sage_attn_pv8_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qs
     const int ql = lane & 31, h = lane >> 5;
     const int qrow0 = qt * QTILE + wave * 32;
     const int q_row = qrow0 + ql;
-    const size_t slab = (size_t)bh * N;
-    const int nbq = (N + (1 << shift_q) - 1) >> shift_q, nbk = (N + (1 << shift_k) - 1) >> shift_k;
+    // Nq query rows against N keys per slab; with a causal mask the queries are the last Nq tokens
+    const size_t slab = (size_t)bh * N, slab_q = (size_t)bh * Nq;
+    const int coff = N - Nq;
+    const int nbq = (Nq + (1 << shift_q) - 1) >> shift_q, nbk = (N + (1 << shift_k) - 1) >> shift_k;
 
     p4i qreg[KS];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
         qreg[ks] = (p4i){0, 0, 0, 0};
-        if (q_row < N) qreg[ks] = *(const p4i*)(qi + (slab + q_row) * D + ks * 32 + h * 16);
+        if (q_row < Nq) qreg[ks] = *(const p4i*)(qi + (slab_q + q_row) * D + ks * 32 + h * 16);
     }
-    const float dq = qsc[(size_t)bh * nbq + ((q_row < N ? q_row : N - 1) >> shift_q)] * PV8_LOG2E;
+    const float dq = qsc[(size_t)bh * nbq + ((q_row < Nq ? q_row : Nq - 1) >> shift_q)] * PV8_LOG2E;
     const float* __restrict__ ksc_bh = ksc + (size_t)bh * nbk;
 
     const int kv_tiles_all = (N + KT - 1) / KT;
     int T = kv_tiles_all, Tw = kv_tiles_all;
     if (CAUSAL) {
-        int last = (qt * QTILE + QTILE - 1) / KT + 1;
+        int last = (qt * QTILE + QTILE - 1 + coff) / KT + 1;
         T = last < kv_tiles_all ? last : kv_tiles_all;
-        last = (qrow0 + 31) / KT + 1;
+        last = (qrow0 + 31 + coff) / KT + 1;
         Tw = last < T ? last : T;
     }
 
@@ -216,7 +218,7 @@ sage_attn_pv8_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qs
                 }
             }
             // mask: keys past N, and keys after the lane's query when causal (edge tiles only)
-            const bool edge = (j * KT + KT > N) || (CAUSAL && j * KT + KT - 1 > qrow0);
+            const bool edge = (j * KT + KT > N) || (CAUSAL && j * KT + KT - 1 > qrow0 + coff);
             // Per-block key scale: y = (float)S^ and sc = delta_Q log2(e) delta_K[tile]; per-token key
             // scales: y = (float)S^ * delta_K[key] and sc = delta_Q log2(e).  Either way the maximum is
             // taken on y and scaled once (sc > 0), and the softmax argument is one FMA, y * sc - m'.
@@ -246,7 +248,7 @@ sage_attn_pv8_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qs
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
                         const int kidx = j * KT + 32 * kb + 16 * h + r;
-                        if (kidx >= N || (CAUSAL && kidx > q_row)) y[kb][r] = PV8_HIDDEN;
+                        if (kidx >= N || (CAUSAL && kidx > q_row + coff)) y[kb][r] = PV8_HIDDEN;
                     }
             }
             float tmax = PV8_HIDDEN;
@@ -321,8 +323,8 @@ sage_attn_pv8_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qs
     // ---- epilogue: O = (O_fp32 + A) * delta_V[c] / sum(127 P~)
     const float lt = l127 + lane32_partner(l127);
     const float inv = 1.0f / lt, g_run = 1.0f / ginv;
-    if (q_row < N) {
-        _Float16* orow = og + (slab + q_row) * D;
+    if (q_row < Nq) {
+        _Float16* orow = og + (slab_q + q_row) * D;
         const float* dv = vsc + (size_t)bh * D;
 #pragma unroll
         for (int cb = 0; cb < DT; ++cb)
@@ -344,14 +346,14 @@ sage_attn_pv8_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qs
 
 template <int D>
 static hipError_t launch_pv8_d(const int8_t* qq, const float* qscale, const int8_t* kq, const float* kscale,
-                               const int8_t* vt, const float* vscale, void* o, int BH, int N, int causal,
+                               const int8_t* vt, const float* vscale, void* o, int BH, int Nq, int N, int causal,
                                int shift_q, int shift_k, bool ktok, hipStream_t st) {
-    const int tiles_q = (N + 127) / 128, Np = 64 * ((N + 63) / 64);
+    const int tiles_q = (Nq + 127) / 128, Np = 64 * ((N + 63) / 64);
     const long total = (long)BH * tiles_q;
     const int per_xcd = (int)((total + 7) / 8);
     const dim3 grid((unsigned)(per_xcd * 8)), block(256);
 #define SAGE_PV8(C, K) sage_attn_pv8_kernel<D, C, K><<<grid, block, 0, st>>>( \
-        qq, qscale, kq, kscale, vt, vscale, (_Float16*)o, N, Np, shift_q, shift_k, tiles_q, per_xcd, total)
+        qq, qscale, kq, kscale, vt, vscale, (_Float16*)o, Nq, N, Np, shift_q, shift_k, tiles_q, per_xcd, total)
     if (causal) { if (ktok) SAGE_PV8(true, true); else SAGE_PV8(true, false); }
     else        { if (ktok) SAGE_PV8(false, true); else SAGE_PV8(false, false); }
 #undef SAGE_PV8
@@ -359,14 +361,14 @@ static hipError_t launch_pv8_d(const int8_t* qq, const float* qscale, const int8
 }
 
 hipError_t launch_attn_pv8(const int8_t* qq, const float* qscale, const int8_t* kq, const float* kscale,
-                           const int8_t* vt, const float* vscale, void* o, int BH, int N, int D, int causal,
+                           const int8_t* vt, const float* vscale, void* o, int BH, int Nq, int N, int D, int causal,
                            int block_q, int block_k, hipStream_t st) {
     int shift_q = 0, shift_k = 0;
     while ((1 << shift_q) < block_q) ++shift_q;
     while ((1 << shift_k) < block_k) ++shift_k;
     const bool ktok = block_k == 1;
-    if (D == 64) return launch_pv8_d<64>(qq, qscale, kq, kscale, vt, vscale, o, BH, N, causal, shift_q, shift_k, ktok, st);
-    return launch_pv8_d<128>(qq, qscale, kq, kscale, vt, vscale, o, BH, N, causal, shift_q, shift_k, ktok, st);
+    if (D == 64) return launch_pv8_d<64>(qq, qscale, kq, kscale, vt, vscale, o, BH, Nq, N, causal, shift_q, shift_k, ktok, st);
+    return launch_pv8_d<128>(qq, qscale, kq, kscale, vt, vscale, o, BH, Nq, N, causal, shift_q, shift_k, ktok, st);
 }
 
 }  // namespace sage

@@ -24,7 +24,7 @@ hipError_t launch_attn(const int8_t* qq, const float* qscale, const int8_t* kq, 
 hipError_t launch_quant_v(const void* v, int8_t* vt, float* vscale, unsigned* amax_bits,
                           int BH, int N, int D, hipStream_t st);
 hipError_t launch_attn_pv8(const int8_t* qq, const float* qscale, const int8_t* kq, const float* kscale,
-                           const int8_t* vt, const float* vscale, void* o, int BH, int N, int D, int causal,
+                           const int8_t* vt, const float* vscale, void* o, int BH, int Nq, int N, int D, int causal,
                            int block_q, int block_k, hipStream_t st);
 
 }  // namespace sage

@@ -75,3 +75,42 @@ def test_causal_with_more_queries_than_keys_is_refused():
     with pytest.raises(sage.SageError) as e:
         sage.sage_attn_cross_fwd(q_i8, sc, k_i8, sc, v, True, 0.125, 128, 64)
     assert e.value.status == 3
+
+
+# ------------------------------------------------------------------ the INT8 second product with two lengths
+
+from test_gpu_pv_int8 import assert_pv8_close  # noqa: E402
+
+PV8_CASES = [c for c in CASES if c[0] in ("text_to_image_cross", "image_to_text_cross", "decode_one_query",
+                                          "chunked_prefill_tail", "chunked_prefill_d64", "chunk_crossing_tiles",
+                                          "per_token_cross")]
+
+
+@pytest.mark.parametrize("name,B,H,Nq,Nkv,D,causal,bq,bk", PV8_CASES, ids=[c[0] for c in PV8_CASES])
+def test_cross_parity_int8_second_product(name, B, H, Nq, Nkv, D, causal, bq, bk):
+    print(f"[case] INT8 PV cross {name} B{B} H{H} Nq{Nq} Nkv{Nkv} D{D} causal={causal} scales {bq}x{bk}", flush=True)
+    q, k, v, sm = make(name, B, H, Nq, Nkv, D, len(name))
+    k_i8, k_scale, _ = sage.sage_smooth_quant_k(to_dev(k), bk)
+    q_i8, q_scale = sage.sage_quant_q(to_dev(q), sm, bq)
+    v_i8t, v_scale = sage.sage_quant_v(to_dev(v))
+    o = sage.sage_attn_pv_int8_cross_fwd(q_i8, q_scale, k_i8, k_scale, v_i8t, v_scale, causal, sm, bq, bk)
+    torch.cuda.synchronize()
+    kq, ks, _ = oracle.smooth_quant_k(k, bk)
+    qq, qs = oracle.quant_q(q, sm, bq)
+    vq, vs = oracle.quant_v(v)
+    assert np.array_equal(v_i8t.cpu().numpy()[..., :Nkv], vq.transpose(0, 1, 3, 2))
+    o_ref, l_ref = oracle.attn_pv8_cross(qq, qs, kq, ks, vq, vs, causal, 128, 64, gran_q=bq, gran_k=bk, return_l=True)
+    err, cos, frac = assert_pv8_close(o.cpu().numpy(), o_ref, l_ref, vs, name)
+    print(f"  max_abs {err:.2e} cos {cos:.7f} within 2e-3: {frac:.5f}", flush=True)
+
+
+def test_int8_second_product_equal_lengths_give_the_self_attention_result_bit_for_bit():
+    w = si.custom("same8", 2, 2, 457, 128, True, seed=si.BASE_SEED + 760)
+    q, k, v = si.full(w)
+    k_i8, k_scale, _ = sage.sage_smooth_quant_k(to_dev(k), 64)
+    q_i8, q_scale = sage.sage_quant_q(to_dev(q), w.sm_scale, 128)
+    v_i8t, v_scale = sage.sage_quant_v(to_dev(v))
+    a = sage.sage_attn_pv_int8_fwd(q_i8, q_scale, k_i8, k_scale, v_i8t, v_scale, True, w.sm_scale, 128, 64)
+    b = sage.sage_attn_pv_int8_cross_fwd(q_i8, q_scale, k_i8, k_scale, v_i8t, v_scale, True, w.sm_scale, 128, 64)
+    torch.cuda.synchronize()
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16))

@@ -110,3 +110,7 @@ def test_cross_attention_call_validates_both_lengths(lib):
     assert lib.sage_attn_cross_fwd(good, good, good, good, good, good, 1, 1, 64, 64, 64, 0, f(0.125), 128, 32, None) == 3
     assert lib.sage_attn_cross_fwd(good, good, good, good, good, good, 1, 1, 64, 64, 64, 0, f(0.0), 128, 64, None) == 7
     assert lib.sage_attn_cross_fwd(good, good, odd, good, good, good, 1, 1, 64, 64, 64, 0, f(0.125), 128, 64, None) == 5
+    args = (good,) * 7
+    assert lib.sage_attn_pv_int8_cross_fwd(*args, 1, 1, 65, 64, 64, 1, f(0.125), 128, 64, None) == 3
+    assert lib.sage_attn_pv_int8_cross_fwd(*args, 1, 1, 64, 0, 64, 0, f(0.125), 128, 64, None) == 2
+    assert lib.sage_attn_pv_int8_cross_fwd(good, good, good, good, None, good, good, 1, 1, 64, 64, 64, 0, f(0.125), 128, 64, None) == 1
