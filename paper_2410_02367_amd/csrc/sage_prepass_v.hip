@@ -54,14 +54,17 @@ __global__ void __launch_bounds__(256) v_absmax_kernel(const _Float16* __restric
     }
 }
 
-// grid (Np / 64, BH): one workgroup quantizes 64 tokens x D channels and writes them transposed.
+// grid (ceil(Np / ROWS), BH), ROWS = 64 (D = 128) or 128 (D = 64): one workgroup quantizes ROWS tokens
+// x D channels and writes them transposed.  A thread owns 8 channels of 4 CONSECUTIVE tokens, so that
+// the four codes of a channel leave as one 32-bit LDS store; the LDS rows are padded by one word,
+// which spreads those stores over the banks.
 template <int D>
 __global__ void __launch_bounds__(256) v_quant_transpose_kernel(const _Float16* __restrict__ v,
                                                                 const unsigned* __restrict__ amax_bits,
                                                                 int8_t* __restrict__ vt, float* __restrict__ vscale,
                                                                 int N, int Np) {
-    constexpr int VPR = D / 8, RG = 256 / VPR, ROWS = 64, PITCH = 80;      // LDS bytes per channel row (16-byte aligned)
-    const int t = threadIdx.x, c8 = t % VPR, rg = t / VPR;
+    constexpr int VPR = D / 8, G = 256 / VPR, ROWS = 4 * G, PITCH = ROWS + 4;      // LDS bytes per channel row
+    const int t = threadIdx.x, c8 = t % VPR, g = t / VPR;
     const int bh = blockIdx.y, tile = blockIdx.x;
     const _Float16* base = v + ((size_t)bh * N) * D;
     __shared__ __attribute__((aligned(16))) int8_t tr[D * PITCH];
@@ -71,30 +74,39 @@ __global__ void __launch_bounds__(256) v_quant_transpose_kernel(const _Float16* 
     for (int e = 0; e < 8; ++e) {
         const float amax = __uint_as_float(amax_bits[(size_t)bh * D + c8 * 8 + e]);
         r[e] = amax > 0.0f ? 127.0f / amax : 0.0f;
-        if (tile == 0 && rg == 0) vscale[(size_t)bh * D + c8 * 8 + e] = amax / 127.0f;
+        if (tile == 0 && g == 0) vscale[(size_t)bh * D + c8 * 8 + e] = amax / 127.0f;
+    }
+    vh8 x[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int row = tile * ROWS + 4 * g + i;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[i][e] = (_Float16)0.0f;
+        if (row < N) x[i] = *(const vh8*)(base + (size_t)row * D + c8 * 8);
     }
 #pragma unroll
-    for (int i = 0; i < ROWS / RG; ++i) {
-        const int lr = rg + i * RG, row = tile * ROWS + lr;
-        vh8 x;
+    for (int e = 0; e < 8; ++e) {
+        unsigned word = 0u;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) x[e] = (_Float16)0.0f;
-        if (row < N) x = *(const vh8*)(base + (size_t)row * D + c8 * 8);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            float q = __builtin_rintf((float)x[e] * r[e]);            // ties to even
+        for (int i = 0; i < 4; ++i) {
+            float q = __builtin_rintf((float)x[i][e] * r[e]);            // ties to even
             q = __builtin_fminf(__builtin_fmaxf(q, -127.0f), 127.0f);
-            tr[(c8 * 8 + e) * PITCH + lr] = (int8_t)(int)q;
+            word |= ((unsigned)(int)q & 0xffu) << (8 * i);
         }
+        *(unsigned*)(tr + (c8 * 8 + e) * PITCH + 4 * g) = word;
     }
     __syncthreads();
-    // D rows of 64 bytes = 4 * D chunks of 16 bytes
+    // D rows of ROWS bytes = D * ROWS / 16 chunks of 16 bytes, two per thread
+    constexpr int CPR = ROWS / 16;          // chunks per channel row
     int8_t* out = vt + ((size_t)bh * D) * Np + (size_t)tile * ROWS;
 #pragma unroll
-    for (int i = 0; i < (4 * D) / 256; ++i) {
-        const int idx = t + 256 * i, c = idx >> 2, part = idx & 3;
-        const int4 chunk = *(const int4*)(tr + c * PITCH + part * 16);
-        *(int4*)(out + (size_t)c * Np + part * 16) = chunk;
+    for (int i = 0; i < (D * CPR) / 256; ++i) {
+        const int idx = t + 256 * i, c = idx / CPR, part = idx % CPR;
+        if (tile * ROWS + part * 16 < Np) {          // D = 64: the last 128-token tile may be half outside
+            const unsigned* src = (const unsigned*)(tr + c * PITCH + part * 16);
+            const int4 chunk = {(int)src[0], (int)src[1], (int)src[2], (int)src[3]};
+            *(int4*)(out + (size_t)c * Np + part * 16) = chunk;
+        }
     }
 }
 
@@ -109,7 +121,7 @@ hipError_t launch_quant_v(const void* v, int8_t* vt, float* vscale, unsigned* am
         constexpr int CHUNK = (256 / 8) * 32;
         v_absmax_kernel<64><<<dim3((N + CHUNK - 1) / CHUNK, BH), 256, 0, st>>>(vp, amax_bits, N);
         if ((e = hipGetLastError()) != hipSuccess) return e;
-        v_quant_transpose_kernel<64><<<dim3(Np / 64, BH), 256, 0, st>>>(vp, amax_bits, vt, vscale, N, Np);
+        v_quant_transpose_kernel<64><<<dim3((Np + 127) / 128, BH), 256, 0, st>>>(vp, amax_bits, vt, vscale, N, Np);
     } else {
         constexpr int CHUNK = (256 / 16) * 32;
         v_absmax_kernel<128><<<dim3((N + CHUNK - 1) / CHUNK, BH), 256, 0, st>>>(vp, amax_bits, N);
