@@ -101,18 +101,22 @@ __global__ void __launch_bounds__(256) k_colsum_kernel(const _Float16* __restric
     }
 }
 
+template <int NT = 256>
 __device__ __forceinline__ float wg_max(float v, float* red) {
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) v = __builtin_fmaxf(v, __shfl_xor(v, off, 64));
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
     __syncthreads();
-    return __builtin_fmaxf(__builtin_fmaxf(red[0], red[1]), __builtin_fmaxf(red[2], red[3]));
+    float m = red[0];
+#pragma unroll
+    for (int w = 1; w < NT / 64; ++w) m = __builtin_fmaxf(m, red[w]);
+    return m;
 }
 
-// One workgroup per quantization block of `block` tokens x D channels; block * D = 2048 * LPT.
-// IS_K: x - mean (mean derived from the exact sums); else x * sm_scale.
-template <int D, int LPT, bool IS_K, bool ROPE>
-__global__ void __launch_bounds__(256) quant_block_kernel(const _Float16* __restrict__ x,
+// One workgroup of NT threads per quantization block of `block` tokens x D channels;
+// block * D = 8 * NT * LPT.  IS_K: x - mean (mean derived from the exact sums); else x * sm_scale.
+template <int D, int LPT, bool IS_K, bool ROPE, int NT = 256>
+__global__ void __launch_bounds__(NT) quant_block_kernel(const _Float16* __restrict__ x,
                                                           int8_t* __restrict__ xq,
                                                           float* __restrict__ scale,
                                                           float* __restrict__ k_mean,
@@ -120,14 +124,14 @@ __global__ void __launch_bounds__(256) quant_block_kernel(const _Float16* __rest
                                                           int N, int block, float sm_scale,
                                                           const float* __restrict__ cs, const float* __restrict__ sn) {
     constexpr int VPR = D / 8;
-    constexpr int RSTEP = 256 / VPR;
+    constexpr int RSTEP = NT / VPR;
     const int t = threadIdx.x, c8 = t % VPR, rbase = t / VPR;
     const int g = blockIdx.x, bh = blockIdx.y, nblk = gridDim.x;
     const int row0 = g * block;
     const int rows = (N - row0 < block) ? (N - row0) : block;
 
     __shared__ float s_mean[D];
-    __shared__ float s_red[4];
+    __shared__ float s_red[NT / 64];
     float mean[8];
     if (IS_K) {
         if (t < D) {
@@ -159,7 +163,7 @@ __global__ void __launch_bounds__(256) quant_block_kernel(const _Float16* __rest
             }
         }
     }
-    amax = wg_max(amax, s_red);
+    amax = wg_max<NT>(amax, s_red);
     const float delta = amax / 127.0f;
     const float rcp = amax > 0.0f ? 127.0f / amax : 0.0f;
     if (t == 0) scale[(size_t)bh * nblk + g] = delta;
@@ -390,7 +394,9 @@ static hipError_t launch_quant(const void* x, int8_t* xq, float* scale, float* m
         case 1: SAGE_QUANT(1); break;
         case 2: SAGE_QUANT(2); break;
         case 4: SAGE_QUANT(4); break;
-        case 8: SAGE_QUANT(8); break;
+        // the largest block (128 tokens x 128 channels) runs with 512 threads of 4 rows each: twice the
+        // loads in flight per block and half the work per thread behind the block-wide maximum
+        case 8: quant_block_kernel<D, 4, IS_K, ROPE, 512><<<grid, 512, 0, st>>>(xp, xq, scale, mean, sums, N, block, sm_scale, cs, sn); break;
         default: return hipErrorInvalidValue;
     }
 #undef SAGE_QUANT
