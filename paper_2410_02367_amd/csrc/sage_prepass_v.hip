@@ -21,11 +21,12 @@ __global__ void __launch_bounds__(256) zero_words_kernel(unsigned* w, int n) {
     if (i < n) w[i] = 0u;
 }
 
-// grid (ceil(N / CHUNK), BH); CHUNK = 32 rows per thread * (256 / (D/8)) row groups.
+// grid (ceil(N / CHUNK), BH); CHUNK = V_RPT rows per thread * (256 / (D/8)) row groups.
+constexpr int V_RPT = 16;
 template <int D>
 __global__ void __launch_bounds__(256) v_absmax_kernel(const _Float16* __restrict__ v,
                                                        unsigned* __restrict__ amax_bits, int N) {
-    constexpr int VPR = D / 8, RG = 256 / VPR, RPT = 32, CHUNK = RG * RPT;
+    constexpr int VPR = D / 8, RG = 256 / VPR, RPT = V_RPT, CHUNK = RG * RPT;
     const int t = threadIdx.x, c8 = t % VPR, rg = t / VPR;
     const int bh = blockIdx.y;
     const int row_base = blockIdx.x * CHUNK + rg;
@@ -33,7 +34,7 @@ __global__ void __launch_bounds__(256) v_absmax_kernel(const _Float16* __restric
     float m[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) m[e] = 0.0f;
-#pragma unroll 8
+#pragma unroll
     for (int i = 0; i < RPT; ++i) {
         const int r = row_base + i * RG;
         if (r < N) {
@@ -118,12 +119,12 @@ hipError_t launch_quant_v(const void* v, int8_t* vt, float* vscale, unsigned* am
     if (e != hipSuccess) return e;
     const _Float16* vp = (const _Float16*)v;
     if (D == 64) {
-        constexpr int CHUNK = (256 / 8) * 32;
+        constexpr int CHUNK = (256 / 8) * V_RPT;
         v_absmax_kernel<64><<<dim3((N + CHUNK - 1) / CHUNK, BH), 256, 0, st>>>(vp, amax_bits, N);
         if ((e = hipGetLastError()) != hipSuccess) return e;
         v_quant_transpose_kernel<64><<<dim3((Np + 127) / 128, BH), 256, 0, st>>>(vp, amax_bits, vt, vscale, N, Np);
     } else {
-        constexpr int CHUNK = (256 / 16) * 32;
+        constexpr int CHUNK = (256 / 16) * V_RPT;
         v_absmax_kernel<128><<<dim3((N + CHUNK - 1) / CHUNK, BH), 256, 0, st>>>(vp, amax_bits, N);
         if ((e = hipGetLastError()) != hipSuccess) return e;
         v_quant_transpose_kernel<128><<<dim3(Np / 64, BH), 256, 0, st>>>(vp, amax_bits, vt, vscale, N, Np);
