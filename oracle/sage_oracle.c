@@ -11,7 +11,7 @@
  * It shares no code with the HIP path.  OpenMP (if enabled) only spreads independent
  * (batch, head, Q-block) units over host cores; the arithmetic of each unit is unchanged.
  *
- * Arithmetic contract (the paper leaves these open; each reading is listed in the design notes):
+ * Arithmetic contract (the paper leaves these open; the readings taken are):
  *   - fp32 means IEEE binary32, round-to-nearest-even, one rounding per written operation,
  *     no FMA contraction (compile with -ffp-contract=off), denormals kept.
  *   - mean(K) is the exactly-summed column total (integer arithmetic in units of 2^-24),
