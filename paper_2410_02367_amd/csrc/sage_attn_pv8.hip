@@ -274,7 +274,9 @@ sage_attn_pv8_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qs
                     for (int r = 0; r < 16; ++r) of[cb][r] = __builtin_fmaf((float)acc[cb][r], ginv, of[cb][r]);
                 const bool first = m_run == -__builtin_inff();
                 l127 *= __builtin_amdgcn_exp2f(m_run - m_new);          // 0 on the first tile; l127 is 0 there
-                ginv = first ? 1.0f : ginv * __builtin_amdgcn_exp2f(m_new - m_run);
+                // (a rise of more than 60 is taken as 60: what was accumulated before is then below 2^-60
+                // of the new terms either way, and 1 / g stays finite: <= 2^60 * 2^60)
+                ginv = first ? 1.0f : ginv * __builtin_amdgcn_exp2f(__builtin_fminf(m_new - m_run, 60.0f));
                 if (__builtin_amdgcn_ballot_w64(ginv > 0x1p60f) != 0ull) {      // rare: fold g into of before 1 / g overflows
                     const float g = ginv > 0x1p60f ? 1.0f / ginv : 1.0f;
 #pragma unroll

@@ -203,3 +203,32 @@ def test_full_size_vb_parity(name, n_blocks):
                                           f"{name} head ({b},{h}) blocks {blocks}")
         print(f"  head ({b},{h}) blocks {blocks}: max_abs {err:.2e} cos {cos:.7f} within 2e-3: {frac:.5f}"
               f"  {time.time() - t0:.1f}s", flush=True)
+
+
+@pytest.mark.parametrize("pv8", [True, False], ids=["int8_pv", "fp16_pv"])
+def test_a_cliff_in_the_scores_leaves_finite_exact_results(pv8):
+    # the first 64 keys score about -400 (natural units) for every query, all later keys about 0: the
+    # running maximum rises by about 577 in log2 units between the first and the second tile, far
+    # beyond what exp2 can represent; the earlier accumulation must vanish, not overflow
+    w = si.custom("cliff", 1, 2, 400, 64, False, 128, 64, seed=si.BASE_SEED + 95)
+    print(f"[case] score cliff, int8_pv={pv8}", flush=True)
+    q, k, v = si.full(w)
+    g = np.random.default_rng(95)
+    k = (g.standard_normal(k.shape) * 0.5).astype(np.float16)
+    q[..., 0] = 40.0
+    k[..., 0] = 40.0
+    k[..., :64, 0] = -40.0
+    (q_i8, q_scale, k_i8, k_scale, _), (qq, qs, kq, ks, _) = assert_prepass_bit_exact(q, k, w.sm_scale, 128, 64)
+    s = oracle.qk_i32(qq[0, 0], kq[0, 0], 0, 4).astype(np.float64) * qs[0, 0, 0]
+    assert (s[:, 64:] * ks[0, 0, 1]).max() - (s[:, :64] * ks[0, 0, 0]).max() > 300.0      # the premise
+    if pv8:
+        (v_i8t, v_scale), (vq, vs) = assert_v_quant_bit_exact(v)
+        o = sage.sage_attn_pv_int8_fwd(q_i8, q_scale, k_i8, k_scale, v_i8t, v_scale, False, w.sm_scale, 128, 64)
+        torch.cuda.synchronize()
+        o_ref, l_ref = oracle.attn_pv8(qq, qs, kq, ks, vq, vs, False, 128, 64, return_l=True)
+        assert_pv8_close(o.cpu().numpy(), o_ref, l_ref, vs, "cliff")
+    else:
+        from gpu_util import assert_output_close
+        o = sage.sage_attn_fwd(q_i8, q_scale, k_i8, k_scale, to_dev(v), False, w.sm_scale, 128, 64)
+        torch.cuda.synchronize()
+        assert_output_close(o.cpu().numpy(), oracle.attn_l2(qq, qs, kq, ks, v, False, 128, 64), "cliff")
