@@ -232,3 +232,24 @@ def test_a_cliff_in_the_scores_leaves_finite_exact_results(pv8):
         o = sage.sage_attn_fwd(q_i8, q_scale, k_i8, k_scale, to_dev(v), False, w.sm_scale, 128, 64)
         torch.cuda.synchronize()
         assert_output_close(o.cpu().numpy(), oracle.attn_l2(qq, qs, kq, ks, v, False, 128, 64), "cliff")
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_all_zero_blocks_give_uniform_attention_over_the_dequantized_v(causal):
+    # K constant over tokens (smoothed K = 0: zero codes, zero scales) and one all-zero block of Q:
+    # every visible key gets code 127, O = (prefix) mean of delta_V V^
+    w = si.custom("zeros", 1, 2, 300, 128, causal, 128, 64, seed=si.BASE_SEED + 96)
+    print(f"[case] INT8 PV zero blocks causal={causal}", flush=True)
+    q, k, v = si.full(w)
+    k[...] = k[:, :, :1, :]
+    q[:, :, 128:256, :] = 0
+    (q_i8, q_scale, k_i8, k_scale, _), (qq, qs, kq, ks, _) = assert_prepass_bit_exact(q, k, w.sm_scale, 128, 64)
+    assert not kq.any() and not ks.any() and qs[0, 0, 1] == 0.0
+    (v_i8t, v_scale), (vq, vs) = assert_v_quant_bit_exact(v)
+    o = sage.sage_attn_pv_int8_fwd(q_i8, q_scale, k_i8, k_scale, v_i8t, v_scale, causal, w.sm_scale, 128, 64)
+    torch.cuda.synchronize()
+    deq = vq.astype(np.float64) * vs[:, :, None, :].astype(np.float64)
+    want = np.cumsum(deq, 2) / np.arange(1, 301)[None, None, :, None] if causal else np.broadcast_to(deq.mean(2, keepdims=True), deq.shape)
+    assert np.abs(o.cpu().numpy().astype(np.float64) - want).max() <= 2e-3
+    o_ref, l_ref = oracle.attn_pv8(qq, qs, kq, ks, vq, vs, causal, 128, 64, return_l=True)
+    assert_pv8_close(o.cpu().numpy(), o_ref, l_ref, vs, "zeros")
