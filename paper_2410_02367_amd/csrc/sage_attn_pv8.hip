@@ -34,6 +34,7 @@
 // 8-12 % at 128K (flushes are rare there), 5-12 % slower below 8K; it is bound by VALU issue
 // (about 264 VALU instructions against 16 matrix instructions per 32 x 64 step).
 #include "sage_internal.h"
+#include <type_traits>
 
 namespace sage {
 
@@ -87,7 +88,15 @@ sage_attn_pv8_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qs
     constexpr int KL = KB / 16 / NT, VL = VB / 16 / NT;
     static_assert(KL >= 1 && VL >= 1, "tile loads cover whole workgroups");
     constexpr int KSL = KTOK ? KT * 4 : 0;             // per-key scales of a tile (per-token variant)
-    __shared__ __attribute__((aligned(16))) unsigned char lds[3 * (KB + VB) + 3 * KSL];
+    // Q^ operands (B matrix of S^T = K^ Q^^T): QREG of the KS contraction steps stay in registers for
+    // the whole kernel, the others are read from an LDS copy of the workgroup's Q^ rows tile after
+    // tile (16 bytes per lane and step).  Registers are faster (no second LDS operand per matrix
+    // instruction); the LDS copy is what keeps the pipeline below inside the register budget: 168
+    // registers at D = 64 (three wavefronts per SIMD), 256 without spills at D = 128 with a causal mask.
+    constexpr int QREG = D == 64 ? 0 : (CAUSAL ? 2 : KS);
+    constexpr int QB = QREG < KS ? QTILE * D : 0;
+    constexpr int QOFF = 3 * (KB + VB) + 3 * KSL;
+    __shared__ __attribute__((aligned(16))) unsigned char lds[QOFF + QB];
 
     // workgroup -> (slab, query tile): contiguous ranges per XCD, heaviest query tiles first
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
@@ -106,9 +115,9 @@ sage_attn_pv8_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qs
     const int coff = N - Nq;
     const int nbq = (Nq + (1 << shift_q) - 1) >> shift_q, nbk = (N + (1 << shift_k) - 1) >> shift_k;
 
-    p4i qreg[KS];
+    p4i qreg[QREG > 0 ? QREG : 1];
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
+    for (int ks = 0; ks < QREG; ++ks) {
         qreg[ks] = (p4i){0, 0, 0, 0};
         if (q_row < Nq) qreg[ks] = *(const p4i*)(qi + (slab_q + q_row) * D + ks * 32 + h * 16);
     }
@@ -128,31 +137,35 @@ sage_attn_pv8_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qs
     // vectors NT*i + t of the (linear) LDS tile, one per lane; the global chunk a lane fetches is the
     // one that belongs there (row permutation and chunk swizzle inverted).  K^ rows past N lie beyond
     // the slab's descriptor and read as zero; V^^T rows are padded to whole tiles.
-    unsigned k_goff[KL], v_goff[VL];
-#pragma unroll
-    for (int i = 0; i < KL; ++i) {
-        const int vidx = t + NT * i, p = vidx / KCH, slot = vidx % KCH;
-        k_goff[i] = (unsigned)(k_unperm(p) * D + ((slot ^ k_swz8<D>(p)) * 16));
-    }
-#pragma unroll
-    for (int i = 0; i < VL; ++i) {
-        const int vidx = t + NT * i, ch = vidx >> 2, slot = vidx & 3;
-        v_goff[i] = (unsigned)(ch * Np + ((slot ^ vt_swz(ch)) * 16));
-    }
+    // (instruction i of a tensor is instruction 0 plus a constant: NT / KCH further K^ rows -- a
+    // multiple of 32, which neither the permutation nor the swizzle sees -- or 64 further channels)
+    static_assert((NT / KCH) % 32 == 0, "K^ rows of consecutive load instructions differ by whole 32-key blocks");
+    const unsigned k_goff0 = (unsigned)(k_unperm(t / KCH) * D + (((t % KCH) ^ k_swz8<D>(t / KCH)) * 16));
+    const unsigned v_goff0 = (unsigned)((t >> 2) * Np + (((t & 3) ^ vt_swz(t >> 2)) * 16));
     const p4i k_desc = pv8_descriptor(ki + slab * D, (unsigned)N * D);
     const p4i v_desc = pv8_descriptor(vt + (size_t)bh * D * Np, (unsigned)D * Np);
     const p4i ks_desc = pv8_descriptor(ksc_bh, (unsigned)N * 4u);      // per-token variant: N scales; past the end reads 0
     const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)lds;
+    if (QREG < KS) {
+        // same row pitch and chunk swizzle as a K^ tile (no key permutation); rows past Nq read as zero
+        const p4i q_desc = pv8_descriptor(qi + slab_q * D, (unsigned)Nq * D);
+#pragma unroll
+        for (int i = 0; i < QB / 16 / NT; ++i) {
+            const int vidx = t + NT * i, p = vidx / KCH, slot = vidx % KCH;
+            pv8_load_to_lds16(q_desc, (unsigned)((qt * QTILE + p) * D + ((slot ^ k_swz8<D>(p)) * 16)),
+                              lds_base + QOFF + wave * 1024 + i * (NT * 16));
+        }
+    }
     auto fetch = [&](int j, int buf) {
         if (KTOK && wave == 0 && lane < KT / 4)          // the tile's 64 key scales, 16 bytes per lane
             pv8_load_to_lds16(ks_desc, (unsigned)lane * 16u + (unsigned)j * (KT * 4), lds_base + 3 * (KB + VB) + buf * KSL);
         const unsigned kb_addr = lds_base + buf * (KB + VB) + wave * 1024;
 #pragma unroll
         for (int i = 0; i < KL; ++i)
-            pv8_load_to_lds16(k_desc, k_goff[i] + (unsigned)j * (KT * D), kb_addr + i * (NT * 16));
+            pv8_load_to_lds16(k_desc, k_goff0 + (unsigned)(i * (NT / KCH) * D) + (unsigned)j * (KT * D), kb_addr + i * (NT * 16));
 #pragma unroll
         for (int i = 0; i < VL; ++i)
-            pv8_load_to_lds16(v_desc, v_goff[i] + (unsigned)j * KT, kb_addr + KB + i * (NT * 16));
+            pv8_load_to_lds16(v_desc, v_goff0 + (unsigned)(i * (NT / 4)) * (unsigned)Np + (unsigned)j * KT, kb_addr + KB + i * (NT * 16));
     };
 
     // ---- operand read offsets (per lane, inside a buffer).  The swizzle of a row depends on the
@@ -176,9 +189,23 @@ sage_attn_pv8_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qs
     int since = 0;
     bool fresh = false;
 
-    p4i pk[2];             // codes of the tile in flight: B operands of the second product
-    bool pending = false;  // the second half (keys 32..63) of the previous tile's product is still to be issued
+    // Software pipeline over the key tiles.  The second 32-key half of a tile is finished one
+    // iteration late, so that every group of matrix instructions but one has independent VALU work
+    // next to it in the instruction stream:
+    //     K^Q^^T of tile j (8 matrix instructions)            | codes of tile j-1, second half
+    //     V^^T P^^T of tile j-1, second half (4)              | int -> float conversion of tile j's scores
+    //     maximum, flush if a row's maximum rose (rare), codes of tile j, first half
+    //     V^^T P^^T of tile j, first half (4)
+    // State carried to the next iteration: the second half's 16 dequantizable scores per lane, the
+    // tile's scale and softmax offset, and the LDS address of its V^^T tile (three tile buffers: that
+    // tile is still read while tile j+1 is being loaded).
+    p4i pk[2];             // codes: B operands of the second product
+    float yp[16];          // second-half scores of the previous tile (per-token variant: already times delta_K)
+    float sc_p = 1.0f, mb_p = 0.0f;
+    bool pending = false;  // a second half is waiting
     const unsigned char* pend_tb = lds;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) yp[r] = 0.0f;
 
     // second product, one 32-key half: O^T blocks += V^^T operand (LDS) x codes
     auto pv_half = [&](const unsigned char* tb, int kb, const p4i& codes, bool from_zero) {
@@ -197,132 +224,150 @@ sage_attn_pv8_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qs
             }
         }
     };
+    // codes of 16 scores: 127 P~ (0 for hidden keys) out of the exponential; the packed conversion
+    // rounds to the nearest integer, ties to even (checked on hardware), and inserts byte b
+    auto codes16 = [&](const float* y16, float sc, float mb, p4i& out) {
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            unsigned word = 0u;
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const float v = __builtin_amdgcn_exp2f(__builtin_fmaf(y16[4 * w + b], sc, -mb));
+                l127 += v;
+                word = __builtin_amdgcn_cvt_pk_u8_f32(v, (unsigned)b, word);
+            }
+            out[w] = (int)word;
+        }
+    };
+    auto finish_previous = [&]() {          // a wavefront's last tile, or the drain after the loop
+        codes16(yp, sc_p, mb_p, pk[1]);
+        pv_half(pend_tb, 1, pk[1], false);
+        pending = false;
+    };
+
+    // one tile; HAS_PREV (a compile-time constant) says whether a second half is waiting, so that the
+    // deferred work sits in the same basic block as the matrix instructions it is to run beside
+    auto tile = [&](int j, auto has_prev) {
+        constexpr bool HAS_PREV = decltype(has_prev)::value;
+        const int buf = j % 3;
+        const unsigned char* tb = lds + buf * (KB + VB);
+        // S^T block kb: keys 64j + 32kb + 16h + r in register r
+        p16i s[2];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s[kb][r] = 0;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                const p4i a = *(const p4i*)(tb + k_rd(kb, ks));
+                p4i b;
+                if (ks < QREG) b = qreg[ks];
+                else b = *(const p4i*)(lds + QOFF + wave * (32 * D) + k_rd0[ks]);      // this wavefront's Q^ rows
+                s[kb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, s[kb], 0, 0, 0);
+            }
+        }
+        if (HAS_PREV) {
+            codes16(yp, sc_p, mb_p, pk[1]);
+            pv_half(pend_tb, 1, pk[1], false);
+        }
+        // mask: keys past N, and keys after the lane's query when causal (edge tiles only)
+        const bool edge = (j * KT + KT > N) || (CAUSAL && j * KT + KT - 1 > qrow0 + coff);
+        // Per-block key scale: y = (float)S^ and sc = delta_Q log2(e) delta_K[tile]; per-token key
+        // scales: y = (float)S^ * delta_K[key] and sc = delta_Q log2(e).  Either way the maximum is
+        // taken on y and scaled once (sc > 0), and the softmax argument is one FMA, y * sc - m'.
+        // Hidden scores become a huge negative number whose exponential is 0 (sc >= 1e-30 keeps the
+        // product far below any maximum).
+        const float sc = __builtin_fmaxf(KTOK ? dq : dq * ksc_bh[(j * KT) >> shift_k], 1e-30f);
+        float y[2][16];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                y[kb][r] = (float)s[kb][r];
+                if (KTOK) {
+                    const float* kl = (const float*)(lds + 3 * (KB + VB) + buf * KSL);
+                    y[kb][r] *= kl[32 * kb + 16 * h + r];
+                }
+            }
+            // per-token variant: one half's 16 key scales in registers at a time
+            if (KTOK && kb == 0) __builtin_amdgcn_sched_barrier(0);
+        }
+        if (edge) {          // wave-uniform: interior tiles skip the mask arithmetic
+            asm volatile("" ::: "memory");      // keeps this a branch (not 64 compare-and-select pairs on every tile)
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int kidx = j * KT + 32 * kb + 16 * h + r;
+                    if (kidx >= N || (CAUSAL && kidx > q_row + coff)) y[kb][r] = PV8_HIDDEN;
+                }
+        }
+        float tmax = PV8_HIDDEN;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) tmax = __builtin_fmaxf(tmax, y[kb][r]);
+        tmax *= sc;
+        tmax = __builtin_fmaxf(tmax, lane32_partner(tmax));
+        const float m_new = __builtin_fmaxf(m_run, tmax);
+        ++since;
+        if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0ull || since >= PV8_FLUSH_TILES) {
+            // O relative to the running maximum is g * of + A with a per-lane factor g that takes
+            // the rescaling: (g of + A) alpha = (g alpha) (of + A / g), so a flush is one conversion and
+            // one FMA per element, of += A * (1 / g), and then g *= alpha.  1 / g = 2^(rise of the
+            // maximum since the row began) is carried instead of g; the first tile (m_run = -inf,
+            // of = A = 0) leaves it at 1.
+#pragma unroll
+            for (int cb = 0; cb < DT; ++cb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) of[cb][r] = __builtin_fmaf((float)acc[cb][r], ginv, of[cb][r]);
+            const bool first = m_run == -__builtin_inff();
+            l127 *= __builtin_amdgcn_exp2f(m_run - m_new);          // 0 on the first tile; l127 is 0 there
+            // (a rise of more than 60 is taken as 60: what was accumulated before is then below 2^-60
+            // of the new terms either way, and 1 / g stays finite: <= 2^60 * 2^60)
+            ginv = first ? 1.0f : ginv * __builtin_amdgcn_exp2f(__builtin_fminf(m_new - m_run, 60.0f));
+            if (__builtin_amdgcn_ballot_w64(ginv > 0x1p60f) != 0ull) {      // rare: fold g into of before 1 / g overflows
+                const float g = ginv > 0x1p60f ? 1.0f / ginv : 1.0f;
+#pragma unroll
+                for (int cb = 0; cb < DT; ++cb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) of[cb][r] *= g;
+                ginv = ginv > 0x1p60f ? 1.0f : ginv;
+            }
+            m_run = m_new;
+            since = 0;
+            fresh = true;          // the next product starts from zero inside the matrix instruction
+        }
+        const float mb = m_run - PV8_LOG2_127;
+        codes16(y[0], sc, mb, pk[0]);
+        // first half of the product; the first product after a flush starts from zero inside the
+        // matrix instruction
+        pv_half(tb, 0, pk[0], fresh);
+        fresh = false;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) yp[r] = y[1][r];
+        sc_p = sc; mb_p = mb;
+        pend_tb = tb;
+        pending = true;
+    };
 
     fetch(0, 0);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
-    for (int j = 0; j < T; ++j) {
-        const int buf = j % 3;                     // three buffers: the deferred half reads tile j-1 while tile j+1 is staged
+    // tile 0 has no predecessor (every wavefront computes it: Tw >= 1)
+    if (1 < T) fetch(1, 1);
+    tile(0, std::false_type{});
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // this wavefront's part of tile 1 has landed
+    __syncthreads();
+    for (int j = 1; j < T; ++j) {
         if (j + 1 < T) fetch(j + 1, (j + 1) % 3);
-        if (j < Tw) {
-            const unsigned char* tb = lds + buf * (KB + VB);
-            // S^T block kb: keys 64j + 32kb + 16h + r in register r
-            p16i s[2];
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) s[kb][r] = 0;
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    const p4i a = *(const p4i*)(tb + k_rd(kb, ks));
-                    s[kb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, qreg[ks], s[kb], 0, 0, 0);
-                }
-            }
-            // mask: keys past N, and keys after the lane's query when causal (edge tiles only)
-            const bool edge = (j * KT + KT > N) || (CAUSAL && j * KT + KT - 1 > qrow0 + coff);
-            // Per-block key scale: y = (float)S^ and sc = delta_Q log2(e) delta_K[tile]; per-token key
-            // scales: y = (float)S^ * delta_K[key] and sc = delta_Q log2(e).  Either way the maximum is
-            // taken on y and scaled once (sc > 0), and the softmax argument is one FMA, y * sc - m'.
-            // Hidden scores become a huge negative number whose exponential is 0 (sc >= 1e-30 keeps the
-            // product far below any maximum).
-            const float sc = __builtin_fmaxf(KTOK ? dq : dq * ksc_bh[(j * KT) >> shift_k], 1e-30f);
-            float y[2][16];
-            // the previous tile's second half goes to the matrix pipe while this tile's scores are converted
-            if (pending) pv_half(pend_tb, 1, pk[1], false);
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    y[kb][r] = (float)s[kb][r];
-                    if (KTOK) {
-                        const float* kl = (const float*)(lds + 3 * (KB + VB) + buf * KSL);
-                        y[kb][r] *= kl[32 * kb + 16 * h + r];
-                    }
-                }
-                // per-token variant: one half's 16 key scales in registers at a time
-                if (KTOK && kb == 0) __builtin_amdgcn_sched_barrier(0);
-            }
-            if (edge) {          // wave-uniform: interior tiles skip the mask arithmetic
-                asm volatile("" ::: "memory");      // keeps this a branch (not 64 compare-and-select pairs on every tile)
-#pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int kidx = j * KT + 32 * kb + 16 * h + r;
-                        if (kidx >= N || (CAUSAL && kidx > q_row + coff)) y[kb][r] = PV8_HIDDEN;
-                    }
-            }
-            float tmax = PV8_HIDDEN;
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) tmax = __builtin_fmaxf(tmax, y[kb][r]);
-            tmax *= sc;
-            tmax = __builtin_fmaxf(tmax, lane32_partner(tmax));
-            const float m_new = __builtin_fmaxf(m_run, tmax);
-            ++since;
-            if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0ull || since >= PV8_FLUSH_TILES) {
-                // O relative to the running maximum is g * of + A with a per-lane factor g that takes
-                // the rescaling: (g of + A) alpha = (g alpha) (of + A / g), so a flush is one conversion and
-                // one FMA per element, of += A * (1 / g), and then g *= alpha.  1 / g = 2^(rise of the
-                // maximum since the row began) is carried instead of g; the first tile (m_run = -inf,
-                // of = A = 0) leaves it at 1.
-#pragma unroll
-                for (int cb = 0; cb < DT; ++cb)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) of[cb][r] = __builtin_fmaf((float)acc[cb][r], ginv, of[cb][r]);
-                const bool first = m_run == -__builtin_inff();
-                l127 *= __builtin_amdgcn_exp2f(m_run - m_new);          // 0 on the first tile; l127 is 0 there
-                // (a rise of more than 60 is taken as 60: what was accumulated before is then below 2^-60
-                // of the new terms either way, and 1 / g stays finite: <= 2^60 * 2^60)
-                ginv = first ? 1.0f : ginv * __builtin_amdgcn_exp2f(__builtin_fminf(m_new - m_run, 60.0f));
-                if (__builtin_amdgcn_ballot_w64(ginv > 0x1p60f) != 0ull) {      // rare: fold g into of before 1 / g overflows
-                    const float g = ginv > 0x1p60f ? 1.0f / ginv : 1.0f;
-#pragma unroll
-                    for (int cb = 0; cb < DT; ++cb)
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) of[cb][r] *= g;
-                    ginv = ginv > 0x1p60f ? 1.0f : ginv;
-                }
-                m_run = m_new;
-                since = 0;
-                fresh = true;          // the next product starts from zero inside the matrix instruction
-            }
-            const float mb = m_run - PV8_LOG2_127;
-            // codes of one 32-key half: 127 P~ (0 for hidden keys) out of the exponential; the packed
-            // conversion rounds to the nearest integer, ties to even (checked on hardware), and
-            // inserts byte b
-            auto softmax_half = [&](int kb) {
-#pragma unroll
-                for (int w = 0; w < 4; ++w) {
-                    unsigned word = 0u;
-#pragma unroll
-                    for (int b = 0; b < 4; ++b) {
-                        const int r = 4 * w + b;
-                        const float v = __builtin_amdgcn_exp2f(__builtin_fmaf(y[kb][r], sc, -mb));
-                        l127 += v;
-                        word = __builtin_amdgcn_cvt_pk_u8_f32(v, (unsigned)b, word);
-                    }
-                    pk[kb][w] = (int)word;
-                }
-            };
-            softmax_half(0);
-            // first half of the product on the matrix pipe, then the second half's codes; the first
-            // product after a flush starts from zero inside the matrix instruction
-            pv_half(tb, 0, pk[0], fresh);
-            fresh = false;
-            softmax_half(1);
-            pending = true;
-            pend_tb = tb;
-        } else if (pending) {
-            pv_half(pend_tb, 1, pk[1], false);
-            pending = false;
-        }
+        if (j < Tw) tile(j, std::true_type{});
+        else if (pending) finish_previous();
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // this wavefront's part of tile j + 1 has landed
         __syncthreads();
     }
-    if (pending) pv_half(pend_tb, 1, pk[1], false);
+    if (pending) finish_previous();
 
     // ---- epilogue: O = (O_fp32 + A) * delta_V[c] / sum(127 P~)
     const float lt = l127 + lane32_partner(l127);
