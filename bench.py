@@ -30,8 +30,8 @@ HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 # HBM bytes per attention launch from the hardware counters (FETCH_SIZE and WRITE_SIZE, one profiler
 # run each, scaled by what the same counter reads for a 1 GiB copy kernel); the profiler cannot run
 # inside this script, so the figure of the committed summary under profiles/ is carried here.
-ATTN_TRAFFIC_BYTES = {"cfg3_prefill16k": 511.2e6}
-ATTN_TRAFFIC_BYTES_INT8_PV = {"cfg3_prefill16k": 423.0e6}
+ATTN_TRAFFIC_BYTES = {"cfg3_prefill16k": 511.0e6}
+ATTN_TRAFFIC_BYTES_INT8_PV = {"cfg3_prefill16k": 444.4e6}
 
 
 def cpu_baseline(w, seconds_budget=20.0, per_token=False, gpu_out_head0=None, pv_int8=False):

@@ -30,8 +30,8 @@
 //
 // This variant is written with compiler builtins and compiler scheduling; it trades the second
 // product's instruction count (half) for more VALU work per score (conversion, rounding, packing,
-// flushes).  Measured on MI355X against the FP16-second-product kernel: 3-8 % faster at 16K keys,
-// 8-12 % at 128K (flushes are rare there), 5-12 % slower below 8K; it is bound by VALU issue
+// flushes).  Measured on MI355X against the FP16-second-product kernel: 0-5 % faster at 16K keys,
+// 8-15 % from 32K up (flushes are rare there), 3-6 % slower below 8K; it is bound by VALU issue
 // (about 264 VALU instructions against 16 matrix instructions per 32 x 64 step).
 #include "sage_internal.h"
 #include <type_traits>
