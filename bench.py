@@ -157,9 +157,10 @@ def sweep(per_token: bool, pv_int8: bool = False):
 
 
 def cross(workload: str, nqs):
-    """Speed of sage_attn_cross_fwd: the last Nq tokens of the workload's sequence as queries against
-    all of its keys and values (chunked prefill / decode shapes; the mask, if causal, is aligned at
-    the end).  Prints one table row per Nq; not part of the one-line benchmark contract."""
+    """Speed of sage_attn_cross_fwd and sage_attn_cross_split_fwd: the last Nq tokens of the workload's
+    sequence as queries against all of its keys and values (chunked prefill / decode shapes; the mask,
+    if causal, is aligned at the end).  Prints one table row per Nq; not part of the one-line
+    benchmark contract."""
     import torch
 
     import paper_2410_02367_amd as sage
@@ -173,23 +174,35 @@ def cross(workload: str, nqs):
     k_i8, k_scale, _ = sage.sage_smooth_quant_k(kd, w.block_k)
     print(f"{w.name}: B={B} H={H} Nkv={N} D={D} causal={w.causal}, block_q={w.block_q} block_k={w.block_k}; "
           "ops = 4 B H D x visible (query, key) pairs")
-    print("%8s  %10s %9s" % ("Nq", "attn ms", "TOPS"))
+    print("%8s  %10s %9s   %7s %10s %9s" % ("Nq", "attn ms", "TOPS", "chunks", "split ms", "TOPS"))
+
+    def timed(call):
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        for _ in range(10):
+            call()
+        reps = 20
+        ev[0].record()
+        for _ in range(reps):
+            call()
+        ev[1].record()
+        torch.cuda.synchronize()
+        return ev[0].elapsed_time(ev[1]) / reps
+
     for nq in nqs:
         qd = torch.from_numpy(np.ascontiguousarray(q[:, :, N - nq:])).cuda()
         q_i8, q_scale = sage.sage_quant_q(qd, w.sm_scale, w.block_q)
         out = torch.empty((B, H, nq, D), dtype=torch.float16, device="cuda")
-        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-        for _ in range(3):
-            sage.sage_attn_cross_fwd(q_i8, q_scale, k_i8, k_scale, vd, w.causal, w.sm_scale, w.block_q, w.block_k, out)
-        reps = 10
-        ev[0].record()
-        for _ in range(reps):
-            sage.sage_attn_cross_fwd(q_i8, q_scale, k_i8, k_scale, vd, w.causal, w.sm_scale, w.block_q, w.block_k, out)
-        ev[1].record()
-        torch.cuda.synchronize()
-        ms = ev[0].elapsed_time(ev[1]) / reps
+        ms = timed(lambda: sage.sage_attn_cross_fwd(q_i8, q_scale, k_i8, k_scale, vd, w.causal, w.sm_scale,
+                                                    w.block_q, w.block_k, out))
         pairs = float(nq) * N - (float(nq) * (nq - 1) / 2 if w.causal else 0.0)
-        print("%8d  %10.4f %9.0f" % (nq, ms, 4.0 * B * H * D * pairs / (ms * 1e-3) / 1e12), flush=True)
+        ops = 4.0 * B * H * D * pairs
+        # the same with the keys cut into the number of chunks the library chooses (sage_attn_cross_split_fwd)
+        n = sage.sage_attn_split_count(B, H, nq, N, w.causal, 0)
+        ws = torch.empty(max(sage.sage_attn_split_workspace(B, H, nq, N, D, w.causal, 0), 16), dtype=torch.uint8, device="cuda")
+        ms_s = timed(lambda: sage.sage_attn_cross_split_fwd(q_i8, q_scale, k_i8, k_scale, vd, w.causal, w.sm_scale,
+                                                            w.block_q, w.block_k, 0, out, ws))
+        print("%8d  %10.4f %9.0f   %7d %10.4f %9.0f" % (nq, ms, ops / (ms * 1e-3) / 1e12, n, ms_s, ops / (ms_s * 1e-3) / 1e12),
+              flush=True)
 
 
 def main():
@@ -215,8 +228,8 @@ def main():
                     help="instead of the benchmark line, print the attention kernel's speed over N = 1K..32K, "
                          "D = 64/128, with and without the causal mask")
     ap.add_argument("--cross", default=None,
-                    help="instead of the benchmark line, time sage_attn_cross_fwd with the last Nq tokens of the "
-                         "workload as queries against all of its keys; comma-separated list of Nq")
+                    help="instead of the benchmark line, time sage_attn_cross_fwd and sage_attn_cross_split_fwd with the "
+                         "last Nq tokens of the workload as queries against all of its keys; comma-separated list of Nq")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one plain elementwise copy kernel of 1 GiB before the warm-up, so that a "
                          "hardware-counter run holds a kernel of known HBM traffic beside the library's kernels")

@@ -53,7 +53,7 @@ enum {
     SAGE_ERR_NULL = 1,        /* a required pointer is NULL                                    */
     SAGE_ERR_SHAPE = 2,       /* B, H, N or D <= 0, N > 2^23, or B*H*N*D overflows             */
     SAGE_ERR_UNSUPPORTED = 3, /* D not in {64,128} or a block size the kernels do not cover    */
-    SAGE_ERR_WORKSPACE = 4,   /* workspace_bytes smaller than sage_smooth_quant_k_workspace()  */
+    SAGE_ERR_WORKSPACE = 4,   /* workspace_bytes smaller than the call's *_workspace() size   */
     SAGE_ERR_ALIGN = 5,       /* a pointer is not aligned as required                          */
     SAGE_ERR_LAUNCH = 6,      /* the HIP runtime reported an error at launch                   */
     SAGE_ERR_VALUE = 7        /* sm_scale not finite or not positive                           */
@@ -191,6 +191,28 @@ int sage_attn_cross_fwd(const int8_t* q_i8, const float* q_scale,
                         const void* v_f16, void* o_f16,
                         int B, int H, int Nq, int Nkv, int D, int causal, float sm_scale,
                         int block_q, int block_k, void* stream);
+
+/*
+ * sage_attn_cross_fwd for few queries against many keys (decoding, the tail of a chunked prefill):
+ * the keys of a slab are cut into n_splits chunks that run as separate workgroups, each leaving the
+ * attention of its rows over its chunk and the chunk's share of the softmax denominator, and a
+ * merge kernel combines them.  The result is that of Algorithm 1 over all keys up to the order
+ * of the floating-point sums (the partial outputs pass through fp16); the paper has no such split.
+ *   n_splits   requested number of chunks, 0 = chosen from the shape; the number actually used is
+ *              sage_attn_split_count() (chunks are multiples of 128 keys, and with a causal mask the
+ *              last chunk starts at or before key Nkv - Nq); 1 chunk is sage_attn_cross_fwd itself
+ *   workspace  device, >= sage_attn_split_workspace() bytes (same arguments), 16-byte aligned;
+ *              scratch, contents undefined on entry and exit; may be NULL when that size is 0
+ * sage_attn_split_count returns 0 for arguments the call would reject.
+ * Everything else as sage_attn_cross_fwd; SAGE_ERR_VALUE for n_splits < 0.
+ */
+int sage_attn_split_count(int B, int H, int Nq, int Nkv, int causal, int n_splits);
+size_t sage_attn_split_workspace(int B, int H, int Nq, int Nkv, int D, int causal, int n_splits);
+int sage_attn_cross_split_fwd(const int8_t* q_i8, const float* q_scale,
+                              const int8_t* k_i8, const float* k_scale,
+                              const void* v_f16, void* o_f16, void* workspace, size_t workspace_bytes,
+                              int B, int H, int Nq, int Nkv, int D, int causal, float sm_scale,
+                              int block_q, int block_k, int n_splits, void* stream);
 
 /*
  * sage_attn_pv_int8_fwd with Nq queries against Nkv keys and values: the lengths, the layouts of

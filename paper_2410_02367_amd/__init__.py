@@ -9,10 +9,13 @@ from .binding import (  # noqa: F401
     lib_path,
     load,
     sage_attn_cross_fwd,
+    sage_attn_cross_split_fwd,
     sage_attn_fwd,
     sage_attn_pv_int8_cross_fwd,
     sage_attn_pv_int8_fwd,
     sage_attn_qk_i32_debug,
+    sage_attn_split_count,
+    sage_attn_split_workspace,
     sage_quant_q,
     sage_quant_v,
     sage_quant_v_pitch,

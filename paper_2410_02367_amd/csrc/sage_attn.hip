@@ -224,8 +224,9 @@ __global__ void __launch_bounds__(NW * 64, NW == 4 && SAGE_QS == 1 ? 2 : 1)
 sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
                  const int8_t* __restrict__ ki, const float* __restrict__ ksc,
                  const _Float16* __restrict__ vg, _Float16* __restrict__ og,
-                 int32_t* __restrict__ sdump,
-                 int Nq, int N, int shift_q, int shift_k, int tiles_q, int per_xcd, long total_tiles) {
+                 int32_t* __restrict__ sdump, float* __restrict__ lse,
+                 int Nq, int Nkv, int shift_q, int shift_k, int tiles_q, int per_xcd, long total_tiles,
+                 int BH, int n_splits, int chunk) {
     constexpr int NWAVES = NW, NTHREADS = NW * 64;
     constexpr int QTILE = NW * WROWS;   // query rows per workgroup
     constexpr int KROW = D;             // bytes per K^ row in LDS
@@ -249,8 +250,9 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
     const long gidx = (long)xcd * per_xcd + slot;
     if (slot >= per_xcd || gidx >= total_tiles) return;
-    const int bh = (int)(gidx / tiles_q);
+    const int unit = (int)(gidx / tiles_q);          // (slab, key chunk), chunk fastest
     const int qt = tiles_q - 1 - (int)(gidx % tiles_q);
+    const int bh = unit / n_splits, split = unit - bh * n_splits;
 
     const int t = threadIdx.x, lane = t & 63;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);     // wave-uniform: keeps control flow scalar
@@ -258,9 +260,17 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
     const int qrow0 = qt * QTILE + wave * WROWS;     // first row of the wavefront; sub-tile qs starts 32*qs later
     // Nq query rows against N keys per slab (the paper's setting is Nq = N).  With a causal mask the
     // queries are the LAST Nq tokens: query row t sits at position t + coff among the keys.
-    const size_t slab = (size_t)bh * N, slab_q = (size_t)bh * Nq;
-    const int coff = N - Nq;
-    const int nbq = (Nq + (1 << shift_q) - 1) >> shift_q, nbk = (N + (1 << shift_k) - 1) >> shift_k;
+    // With n_splits > 1 the workgroup sees only the keys k0 .. k0 + N - 1 of its slab (chunk is a
+    // multiple of the key tile and of the K block; the last chunk takes the remainder) and leaves a
+    // partial result: its own normalized O and, per row, log2 of its softmax denominator in absolute
+    // terms (lse), from which the partial results of a row are merged.  N is the chunk's key count
+    // from here on; one chunk is the whole slab.
+    const int k0 = split * chunk;
+    const int N = split == n_splits - 1 ? Nkv - k0 : chunk;
+    const size_t slab = (size_t)bh * Nkv + k0, slab_q = (size_t)bh * Nq;
+    const size_t slab_o = ((size_t)split * BH + bh) * Nq;
+    const int coff = Nkv - Nq - k0;
+    const int nbq = (Nq + (1 << shift_q) - 1) >> shift_q, nbk = (Nkv + (1 << shift_k) - 1) >> shift_k;
 
     // Q^ operands (B matrix of S^T = K^ Q^^T) stay in accumulator registers for the whole kernel.
     v4i qreg[QS][KS];
@@ -301,7 +311,7 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
     }
     v2i ones2 = {0x3C003C00, 0x3C003C00};     // FP16 (1, 1) pairs
     pin_a(ones2);
-    const float* __restrict__ ksc_bh = ksc + (size_t)bh * nbk;
+    const float* __restrict__ ksc_bh = ksc + (size_t)bh * nbk + (k0 >> shift_k);
 
     // kv tiles visited by the workgroup (T) and by this wavefront (Tw <= T: tiles above the
     // wavefront's last row are skipped when causal)
@@ -909,9 +919,11 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) refresh(acc_o[qs][dt]);
         const float l_half = acc_l[qs][0][0] + acc_l[qs][1][0];            // this lane's keys
-        const float inv = 1.0f / (l_half + as_f32(swap32i(as_i32(l_half))));   // + those of the lane 32 away
+        const float l_row = l_half + as_f32(swap32i(as_i32(l_half)));       // + those of the lane 32 away
+        const float inv = 1.0f / l_row;
         if (q_row < Nq) {
-            _Float16* orow = og + (slab_q + q_row) * D;
+            if (lse != nullptr && g == 0) lse[slab_o + q_row] = m_run[qs] + __builtin_amdgcn_logf(l_row);
+            _Float16* orow = og + (slab_o + q_row) * D;
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
@@ -928,17 +940,17 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
 template <int D, int NW>
 static hipError_t launch_dn(const int8_t* qq, const float* qscale, const int8_t* kq, const float* kscale,
                             const void* v, void* o, int32_t* sdump, int BH, int Nq, int N, int causal,
-                            int block_q, int block_k, hipStream_t st) {
+                            int block_q, int block_k, const SplitPlan& sp, hipStream_t st) {
     constexpr int QTILE = NW * WROWS, NTHREADS = NW * 64;
     const int tiles_q = (Nq + QTILE - 1) / QTILE;
-    const long total = (long)BH * tiles_q;
+    const long total = (long)BH * sp.n_splits * tiles_q;
     const int per_xcd = (int)((total + 7) / 8);
     dim3 grid((unsigned)(per_xcd * 8));
     const int shift_q = __builtin_ctz((unsigned)block_q), shift_k = __builtin_ctz((unsigned)block_k);
     const _Float16* vp = (const _Float16*)v;
     _Float16* op = (_Float16*)o;
     const bool ktok = block_k == 1;
-#define SAGE_LAUNCH(C, DMP, KT) sage_attn_kernel<D, NW, C, DMP, KT><<<grid, NTHREADS, 0, st>>>(qq, qscale, kq, kscale, vp, op, sdump, Nq, N, shift_q, shift_k, tiles_q, per_xcd, total)
+#define SAGE_LAUNCH(C, DMP, KT) sage_attn_kernel<D, NW, C, DMP, KT><<<grid, NTHREADS, 0, st>>>(qq, qscale, kq, kscale, vp, op, sdump, sp.lse, Nq, N, shift_q, shift_k, tiles_q, per_xcd, total, BH, sp.n_splits, sp.chunk)
     // per-token key scales need a few more registers than 4-wavefront workgroups at D = 128 have
     // (two workgroups per CU: 128 + 128 registers); launch_d() never asks for that combination
     constexpr bool KTOK_OK = !(D == 128 && NW == 4);
@@ -960,25 +972,101 @@ static hipError_t launch_dn(const int8_t* qq, const float* qscale, const int8_t*
 template <int D>
 static hipError_t launch_d(const int8_t* qq, const float* qscale, const int8_t* kq, const float* kscale,
                            const void* v, void* o, int32_t* sdump, int BH, int Nq, int N, int causal,
-                           int block_q, int block_k, hipStream_t st) {
+                           int block_q, int block_k, const SplitPlan& sp, hipStream_t st) {
     // 256-row workgroups (8 wavefronts sharing one set of LDS tiles) for long sequences at D = 128;
     // 128-row workgroups, two or three per CU, for D = 64, whenever the larger tile would leave CUs
     // without work (fewer than two workgroups per CU), and for short sequences, where a workgroup
     // visits few tiles and the finer causal staircase and the independent progress of the small
     // workgroups matter more than the sharing (measured at D = 128: +30 % at N = 1K causal, +11 %
     // non-causal; +19 % / +2 % at 2K; +4 % / -3 % at 4K).
-    const long big_tiles = (long)BH * ((Nq + 8 * WROWS - 1) / (8 * WROWS));
-    const bool short_seq = N <= 2048 || (causal && N <= 4096);
+    const long big_tiles = (long)BH * sp.n_splits * ((Nq + 8 * WROWS - 1) / (8 * WROWS));
+    const int n_seen = sp.n_splits > 1 ? sp.chunk : N;           // keys a workgroup walks
+    const bool short_seq = n_seen <= 2048 || (causal && n_seen <= 4096);
     const bool small = QS == 1 && (D == 64 || ((big_tiles < 2 * 256 || short_seq) && block_k != 1 && !sdump));
-    if (small) return launch_dn<D, 4>(qq, qscale, kq, kscale, v, o, sdump, BH, Nq, N, causal, block_q, block_k, st);
-    return launch_dn<D, 8>(qq, qscale, kq, kscale, v, o, sdump, BH, Nq, N, causal, block_q, block_k, st);
+    if (small) return launch_dn<D, 4>(qq, qscale, kq, kscale, v, o, sdump, BH, Nq, N, causal, block_q, block_k, sp, st);
+    return launch_dn<D, 8>(qq, qscale, kq, kscale, v, o, sdump, BH, Nq, N, causal, block_q, block_k, sp, st);
 }
 
 hipError_t launch_attn(const int8_t* qq, const float* qscale, const int8_t* kq, const float* kscale,
                        const void* v, void* o, int32_t* sdump, int BH, int Nq, int N, int D, int causal,
                        int block_q, int block_k, hipStream_t st) {
-    if (D == 64) return launch_d<64>(qq, qscale, kq, kscale, v, o, sdump, BH, Nq, N, causal, block_q, block_k, st);
-    return launch_d<128>(qq, qscale, kq, kscale, v, o, sdump, BH, Nq, N, causal, block_q, block_k, st);
+    const SplitPlan whole = {1, 0, nullptr};
+    if (D == 64) return launch_d<64>(qq, qscale, kq, kscale, v, o, sdump, BH, Nq, N, causal, block_q, block_k, whole, st);
+    return launch_d<128>(qq, qscale, kq, kscale, v, o, sdump, BH, Nq, N, causal, block_q, block_k, whole, st);
+}
+
+// ---- split over the keys ------------------------------------------------------------------------
+// With few query rows per slab a launch has too few workgroups for the chip and each walks every
+// key tile.  The keys are cut into n_splits chunks, a workgroup per (slab, chunk, query tile) leaves
+// the attention of its rows over its chunk -- O_s normalized by the chunk's own denominator, fp16,
+// and lse_s = m_s + log2 l_s -- and the merge below forms
+//     O = sum_s w_s O_s / sum_s w_s,   w_s = 2^(lse_s - max_s lse_s),
+// which is the attention over all keys: w_s is the chunk's share of the softmax denominator.
+SplitPlan plan_split(int BH, int Nq, int N, int causal, int requested) {
+    if (requested <= 0) {
+        // One 128-row workgroup per CU (measured: 256 to 512 workgroups are the fastest at every
+        // shape tried, more lose to the fixed cost per workgroup and to the longer merge); chunks of
+        // at least 8 key tiles.
+        const long wg = (long)BH * ((Nq + 127) / 128);
+        long want = (256 + wg - 1) / wg;
+        const long most = N / 512 < 64 ? N / 512 : 64;
+        requested = (int)(want < most ? want : most);
+    }
+    if (requested <= 1) return {1, 0, nullptr};
+    // Every chunk but the last has `chunk` keys, a multiple of the 64-key tile and of the largest K
+    // block (128); the last takes the rest.  It starts at or before key N - Nq when causal (N - 1 otherwise), so
+    // that every row sees at least one key of every chunk and no partial result is empty.
+    const int chunk = 128 * ((N + 128 * requested - 1) / (128 * requested));
+    const int limit = causal ? N - Nq : N - 1;
+    const int fit = limit / chunk + 1;
+    const int n = requested < fit ? requested : fit;
+    if (n <= 1) return {1, 0, nullptr};
+    return {n, chunk, nullptr};
+}
+
+template <int D>
+__global__ void __launch_bounds__(256) merge_splits_kernel(const _Float16* __restrict__ part, const float* __restrict__ lse,
+                                                           _Float16* __restrict__ og, long rows, int n_splits) {
+    constexpr int TPR = D / 8;                         // threads per row, 8 channels each
+    const long row = (long)blockIdx.x * (256 / TPR) + threadIdx.x / TPR;
+    const int c8 = threadIdx.x % TPR;
+    if (row >= rows) return;
+    float top = -__builtin_inff();
+    for (int s = 0; s < n_splits; ++s) top = __builtin_fmaxf(top, lse[(size_t)s * rows + row]);
+    float acc[8], wsum = 0.0f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = 0.0f;
+    for (int s = 0; s < n_splits; ++s) {
+        const float w = __builtin_amdgcn_exp2f(lse[(size_t)s * rows + row] - top);
+        const v8h x = *(const v8h*)(part + ((size_t)s * rows + row) * D + c8 * 8);
+        wsum += w;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] = __builtin_fmaf(w, (float)x[e], acc[e]);
+    }
+    const float inv = 1.0f / wsum;
+    v8h y;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) y[e] = (_Float16)(acc[e] * inv);
+    *(v8h*)(og + (size_t)row * D + c8 * 8) = y;
+}
+
+hipError_t launch_attn_split(const int8_t* qq, const float* qscale, const int8_t* kq, const float* kscale,
+                             const void* v, void* o, void* workspace, int BH, int Nq, int N, int D, int causal,
+                             int block_q, int block_k, int requested, hipStream_t st) {
+    SplitPlan sp = plan_split(BH, Nq, N, causal, requested);
+    if (sp.n_splits == 1) return launch_attn(qq, qscale, kq, kscale, v, o, nullptr, BH, Nq, N, D, causal, block_q, block_k, st);
+    const long rows = (long)BH * Nq;
+    // workspace: partial O [n_splits, BH, Nq, D] fp16, then lse [n_splits, BH, Nq] fp32
+    _Float16* part = (_Float16*)workspace;
+    sp.lse = (float*)((char*)workspace + (size_t)sp.n_splits * rows * D * sizeof(_Float16));
+    hipError_t e = D == 64
+        ? launch_d<64>(qq, qscale, kq, kscale, v, part, nullptr, BH, Nq, N, causal, block_q, block_k, sp, st)
+        : launch_d<128>(qq, qscale, kq, kscale, v, part, nullptr, BH, Nq, N, causal, block_q, block_k, sp, st);
+    if (e != hipSuccess) return e;
+    _Float16* op = (_Float16*)o;
+    if (D == 64) merge_splits_kernel<64><<<(unsigned)((rows + 31) / 32), 256, 0, st>>>(part, sp.lse, op, rows, sp.n_splits);
+    else merge_splits_kernel<128><<<(unsigned)((rows + 15) / 16), 256, 0, st>>>(part, sp.lse, op, rows, sp.n_splits);
+    return hipGetLastError();
 }
 
 }  // namespace sage

@@ -19,6 +19,20 @@ hipError_t launch_attn(const int8_t* qq, const float* qscale, const int8_t* kq, 
                        const void* v, void* o, int32_t* sdump, int BH, int Nq, int N, int D, int causal,
                        int block_q, int block_k, hipStream_t st);
 
+// The same with the keys of a slab cut into chunks (for few query rows): partial results per chunk in
+// `workspace` (n_splits * BH * Nq * (2 D + 4) bytes), then a merge into o.  plan_split() resolves the
+// requested number of chunks (0 = choose) into the one used and the chunk length; lse is filled in
+// by the launcher.
+struct SplitPlan {
+    int n_splits;
+    int chunk;
+    float* lse;
+};
+SplitPlan plan_split(int BH, int Nq, int N, int causal, int requested);
+hipError_t launch_attn_split(const int8_t* qq, const float* qscale, const int8_t* kq, const float* kscale,
+                             const void* v, void* o, void* workspace, int BH, int Nq, int N, int D, int causal,
+                             int block_q, int block_k, int requested, hipStream_t st);
+
 // INT8 second product (Section 4.3): per-channel quantizer of V (transposed output, pitch
 // 64 * ceil(N / 64)) and the attention kernel that consumes it.
 hipError_t launch_quant_v(const void* v, int8_t* vt, float* vscale, unsigned* amax_bits,

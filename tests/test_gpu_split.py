@@ -1,0 +1,115 @@
+"""GPU parity of sage_attn_cross_split_fwd (the keys of a slab cut into chunks that run as separate
+workgroups, then a merge) against the CPU oracle, through the C ABI.  What it computes is the
+attention of Algorithm 1 over all keys, so the oracle is the one of sage_attn_cross_fwd and the bar
+is the same: max-abs <= 2e-3, cosine >= 0.9999.  Also: one chunk is the unsplit call bit for bit, the
+split and unsplit GPU results agree far inside the tolerance."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2410_02367_amd as sage
+import sage_inputs as si
+from gpu_util import assert_output_close, to_dev
+
+pytestmark = pytest.mark.gpu
+
+# (name, B, H, Nq, Nkv, D, causal, block_q, block_k, requested chunks, chunks used)
+CASES = [
+    ("decode_one_query", 2, 4, 1, 3000, 128, True, 128, 64, 4, 4),
+    ("decode_one_query_nc_d64", 2, 4, 1, 3000, 64, False, 128, 64, 6, 6),
+    ("decode_auto", 1, 3, 5, 9000, 128, True, 128, 64, 0, 15),
+    ("chunked_prefill_tail", 1, 2, 300, 1333, 128, True, 128, 64, 3, 3),
+    ("request_cut_by_the_mask", 2, 2, 257, 900, 64, True, 64, 64, 8, 6),
+    ("k_blocks_of_128", 1, 2, 40, 2100, 128, True, 128, 128, 5, 5),
+    ("per_token_scales", 1, 2, 70, 1500, 128, True, 1, 1, 4, 4),
+    ("per_token_scales_d64", 1, 3, 33, 1100, 64, False, 1, 1, 3, 3),
+    ("cross_attention_nc", 1, 2, 200, 1000, 128, False, 128, 64, 8, 8),
+    ("last_chunk_one_key", 1, 2, 3, 1025, 64, False, 128, 64, 8, 5),
+]
+
+
+def make(name, B, H, Nq, Nkv, D, seed):
+    wq = si.custom(name + "_q", B, H, Nq, D, False, seed=si.BASE_SEED + 900 + seed)
+    wk = si.custom(name + "_k", B, H, Nkv, D, False, k_noise=1.0, k_bias=3.0, seed=si.BASE_SEED + 950 + seed)
+    q, _, _ = si.full(wq)
+    _, k, v = si.full(wk)
+    return q, k, v, wq.sm_scale
+
+
+@pytest.mark.parametrize("name,B,H,Nq,Nkv,D,causal,bq,bk,req,used", CASES, ids=[c[0] for c in CASES])
+def test_split_parity(name, B, H, Nq, Nkv, D, causal, bq, bk, req, used):
+    print(f"[case] split {name} B{B} H{H} Nq{Nq} Nkv{Nkv} D{D} causal={causal} scales {bq}x{bk} chunks {req}", flush=True)
+    n = sage.sage_attn_split_count(B, H, Nq, Nkv, causal, req)
+    assert n == used, f"{name}: {n} chunks"
+    assert sage.sage_attn_split_workspace(B, H, Nq, Nkv, D, causal, req) == n * B * H * Nq * (2 * D + 4)
+    q, k, v, sm = make(name, B, H, Nq, Nkv, D, len(name))
+    k_i8, k_scale, _ = sage.sage_smooth_quant_k(to_dev(k), bk)
+    q_i8, q_scale = sage.sage_quant_q(to_dev(q), sm, bq)
+    vd = to_dev(v)
+    o = sage.sage_attn_cross_split_fwd(q_i8, q_scale, k_i8, k_scale, vd, causal, sm, bq, bk, n_splits=req)
+    o_whole = sage.sage_attn_cross_fwd(q_i8, q_scale, k_i8, k_scale, vd, causal, sm, bq, bk)
+    torch.cuda.synchronize()
+    kq, ks, _ = oracle.smooth_quant_k(k, bk)
+    qq, qs = oracle.quant_q(q, sm, bq)
+    assert np.array_equal(k_i8.cpu().numpy(), kq) and np.array_equal(q_i8.cpu().numpy(), qq)
+    lq, lk = (128, 64) if bq == 1 else (max(bq, 64), max(bk, 64))
+    o_ref = oracle.attn_l2_cross(qq, qs, kq, ks, v, causal, lq, lk, gran_q=bq, gran_k=bk)
+    err, cos = assert_output_close(o.cpu().numpy(), o_ref, name)
+    # against the unsplit kernel: two roundings to fp16 of values of the size of V, and the order of the sums
+    gap = (o.float() - o_whole.float()).abs().max().item()
+    assert gap <= 5e-4 * max(1.0, float(np.abs(v.astype(np.float32)).max())), f"{name}: split vs whole {gap:.2e}"
+    print(f"  max_abs {err:.2e} cos {cos:.7f} split-vs-whole {gap:.2e}", flush=True)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_one_chunk_is_the_unsplit_call_bit_for_bit(causal):
+    q, k, v, sm = make("one", 2, 2, 100, 777, 128, 1)
+    k_i8, k_scale, _ = sage.sage_smooth_quant_k(to_dev(k), 64)
+    q_i8, q_scale = sage.sage_quant_q(to_dev(q), sm, 128)
+    vd = to_dev(v)
+    assert sage.sage_attn_split_workspace(2, 2, 100, 777, 128, causal, 1) == 0
+    a = sage.sage_attn_cross_fwd(q_i8, q_scale, k_i8, k_scale, vd, causal, sm, 128, 64)
+    b = sage.sage_attn_cross_split_fwd(q_i8, q_scale, k_i8, k_scale, vd, causal, sm, 128, 64, n_splits=1)
+    torch.cuda.synchronize()
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+
+
+def test_bad_arguments_are_refused():
+    q_i8 = torch.zeros((1, 1, 4, 64), dtype=torch.int8, device="cuda")
+    k_i8 = torch.zeros((1, 1, 2048, 64), dtype=torch.int8, device="cuda")
+    sq = torch.ones((1, 1, 1), dtype=torch.float32, device="cuda")
+    sk = torch.ones((1, 1, 32), dtype=torch.float32, device="cuda")
+    v = torch.zeros((1, 1, 2048, 64), dtype=torch.float16, device="cuda")
+    small = torch.empty(16, dtype=torch.uint8, device="cuda")
+    with pytest.raises(sage.SageError) as e:
+        sage.sage_attn_cross_split_fwd(q_i8, sq, k_i8, sk, v, True, 0.125, 128, 64, n_splits=4, workspace=small)
+    assert e.value.status == 4
+    with pytest.raises(sage.SageError) as e:
+        sage.sage_attn_cross_split_fwd(q_i8, sq, k_i8, sk, v, True, 0.125, 128, 64, n_splits=-1)
+    assert e.value.status == 7
+    assert sage.sage_attn_split_count(1, 1, 4096, 2048, True, 4) == 0        # causal with Nq > Nkv
+
+
+def test_decode_at_the_headline_shape_sampled_slabs():
+    """B1 H32 Nkv16384 D128 causal (the headline shape's keys) with 1 and 128 queries, in the chunk
+    count the call chooses; the oracle runs on three of the 32 slabs."""
+    B, H, Nkv, D = 1, 32, 16384, 128
+    for Nq in (1, 128):
+        q, k, v, sm = make(f"full{Nq}", B, H, Nq, Nkv, D, Nq)
+        k_i8, k_scale, _ = sage.sage_smooth_quant_k(to_dev(k), 64)
+        q_i8, q_scale = sage.sage_quant_q(to_dev(q), sm, 128)
+        n = sage.sage_attn_split_count(B, H, Nq, Nkv, True, 0)
+        print(f"[case] split headline keys, Nq {Nq}: {n} chunks", flush=True)
+        assert n == 8
+        o = sage.sage_attn_cross_split_fwd(q_i8, q_scale, k_i8, k_scale, to_dev(v), True, sm, 128, 64)
+        torch.cuda.synchronize()
+        o = o.cpu().numpy()
+        assert np.all(np.isfinite(o.astype(np.float32)))
+        for h in (0, 13, 31):
+            kq, ks, _ = oracle.smooth_quant_k(k[:, h:h + 1], 64)
+            qq, qs = oracle.quant_q(q[:, h:h + 1], sm, 128)
+            assert np.array_equal(k_i8[:, h:h + 1].cpu().numpy(), kq)
+            o_ref = oracle.attn_l2_cross(qq, qs, kq, ks, v[:, h:h + 1], True, 128, 64)
+            err, cos = assert_output_close(o[:, h:h + 1], o_ref, f"Nq{Nq} head {h}")
+            print(f"  head {h}: max_abs {err:.2e} cos {cos:.7f}", flush=True)

@@ -114,3 +114,34 @@ def test_cross_attention_call_validates_both_lengths(lib):
     assert lib.sage_attn_pv_int8_cross_fwd(*args, 1, 1, 65, 64, 64, 1, f(0.125), 128, 64, None) == 3
     assert lib.sage_attn_pv_int8_cross_fwd(*args, 1, 1, 64, 0, 64, 0, f(0.125), 128, 64, None) == 2
     assert lib.sage_attn_pv_int8_cross_fwd(good, good, good, good, None, good, good, 1, 1, 64, 64, 64, 0, f(0.125), 128, 64, None) == 1
+
+
+def test_split_call_validates_and_its_chunk_plan_keeps_its_promises(lib):
+    """Host logic of sage_attn_cross_split_fwd: argument checks, and the chunk plan -- never more chunks
+    than requested (64 when it chooses), never an empty chunk and, with a causal mask, never a chunk
+    that some query row cannot see (the last chunk starts at or before key Nkv - Nq)."""
+    import numpy as np
+    f = ctypes.c_float
+    good = ctypes.c_void_p(0x1000)
+    sz = ctypes.c_size_t
+    head = (good,) * 6
+    assert lib.sage_attn_cross_split_fwd(*head, None, sz(0), 1, 1, 4, 4096, 64, 1, f(0.125), 128, 64, 4, None) == 1
+    assert lib.sage_attn_cross_split_fwd(*head, good, sz(64), 1, 1, 4, 4096, 64, 1, f(0.125), 128, 64, 4, None) == 4
+    assert lib.sage_attn_cross_split_fwd(*head, good, sz(1 << 30), 1, 1, 4, 4096, 64, 1, f(0.125), 128, 64, -1, None) == 7
+    assert lib.sage_attn_cross_split_fwd(*head, good, sz(1 << 30), 1, 1, 4097, 4096, 64, 1, f(0.125), 128, 64, 4, None) == 3
+    assert lib.sage_attn_cross_split_fwd(*head, ctypes.c_void_p(0x1004), sz(1 << 30), 1, 1, 4, 4096, 64, 1, f(0.125), 128, 64, 4, None) == 5
+    assert lib.sage_attn_split_count(1, 1, 4097, 4096, 1, 4) == 0
+    assert lib.sage_attn_split_count(1, 1, 4, 4096, 1, 1) == 1 and lib.sage_attn_split_workspace(1, 1, 4, 4096, 64, 1, 1) == 0
+    assert lib.sage_attn_split_workspace(2, 3, 4, 4096, 64, 1, 4) == 4 * 2 * 3 * 4 * (2 * 64 + 4)
+    g = np.random.default_rng(20241002)
+    for _ in range(3000):
+        Nkv = int(g.integers(1, 40000))
+        causal = int(g.integers(0, 2))
+        Nq = int(g.integers(1, Nkv + 1)) if causal else int(g.integers(1, 3000))
+        req = int(g.integers(0, 70))
+        B, H = int(g.integers(1, 4)), int(g.integers(1, 40))
+        n = lib.sage_attn_split_count(B, H, Nq, Nkv, causal, req)
+        assert 1 <= n <= (req if req > 0 else 64), (Nq, Nkv, causal, req, n)
+        if n > 1 and req > 0:        # the chunk length follows from the requested count
+            chunk = 128 * -(-Nkv // (128 * req))
+            assert (n - 1) * chunk <= (Nkv - Nq if causal else Nkv - 1), (Nq, Nkv, causal, req, n)
