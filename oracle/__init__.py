@@ -246,8 +246,10 @@ def attn_pv8(qq, q_scale, kq, k_scale, vq, v_scale, causal: bool, block_q: int, 
 
 
 def attn_pv8_cross(qq, q_scale, kq, k_scale, vq, v_scale, causal: bool, block_q: int, block_k: int,
-                   gran_q: int | None = None, gran_k: int | None = None, return_l: bool = False):
-    """attn_pv8 with Nq queries (Q^ [B, H, Nq, D]) against Nk keys (K^, V^ [B, H, Nk, D]); end-aligned causal mask."""
+                   gran_q: int | None = None, gran_k: int | None = None, return_l: bool = False,
+                   return_m: bool = False):
+    """attn_pv8 with Nq queries (Q^ [B, H, Nq, D]) against Nk keys (K^, V^ [B, H, Nk, D]); end-aligned causal mask.
+    return_m: also the final row maxima m of Algorithm 1 [B, H, Nq] (implies return_l)."""
     gran_q = block_q if gran_q is None else gran_q
     gran_k = block_k if gran_k is None else gran_k
     vq = np.ascontiguousarray(vq, np.int8); B, H, Nk, D = vq.shape
@@ -260,10 +262,47 @@ def attn_pv8_cross(qq, q_scale, kq, k_scale, vq, v_scale, causal: bool, block_q:
     assert not causal or Nq <= Nk
     o = np.zeros((B, H, Nq, D), np.float16)
     lsum = np.zeros((B, H, Nq), np.float32)
+    mrow = np.zeros((B, H, Nq), np.float32)
     _L().sage_oracle_attn_pv8_cross_g(_p(qq), _p(q_scale), _p(kq), _p(k_scale), _p(vq), _p(v_scale),
                                       *map(ctypes.c_int, (B, H, Nq, Nk, D, int(causal), block_q, block_k, gran_q, gran_k)),
-                                      _p(o), _p(lsum))
+                                      _p(o), _p(lsum), _p(mrow))
+    if return_m:
+        return o, lsum, mrow
     return (o, lsum) if return_l else o
+
+
+def attn_pv8_cross_split(qq, q_scale, kq, k_scale, vq, v_scale, causal: bool, block_q: int, block_k: int,
+                         starts, gran_q: int | None = None, gran_k: int | None = None, return_l: bool = False):
+    """The INT8-second-product kernels with the keys of a slab cut into chunks (not in the paper: the
+    decode-shape variant of the library).  Chunk s holds keys starts[s] .. starts[s+1]-1 (the last one
+    up to Nk); Algorithm 1 with the second product of Section 4.3 runs on each chunk as if it were the
+    whole key set -- own running maximum, hence own codes of P~ -- and leaves O_s (fp16), m_s, l_s;
+    the partial results are merged by their shares of the softmax denominator,
+        O = sum_s w_s O_s / sum_s w_s,   w_s = l_s exp(m_s - max_s m_s)      (fp64, rounded to fp16).
+    starts must be multiples of gran_k (and of block_k), increasing from 0, and with a causal mask the
+    last start must not exceed Nk - Nq: then all chunks but the last are fully visible to every query
+    and the last carries the end-aligned mask.  return_l: also L = sum_s w_s, the denominator relative
+    to the global maximum [B, H, Nq]."""
+    gran_q = block_q if gran_q is None else gran_q
+    gran_k = block_k if gran_k is None else gran_k
+    Nk, Nq = kq.shape[2], qq.shape[2]
+    starts = [int(x) for x in starts]
+    assert starts[0] == 0 and all(a < b for a, b in zip(starts, starts[1:])) and starts[-1] < Nk
+    assert all(x % gran_k == 0 and x % block_k == 0 for x in starts)
+    assert not causal or starts[-1] <= Nk - Nq
+    ends = starts[1:] + [Nk]
+    parts, ms, ls = [], [], []
+    for s, (a, b) in enumerate(zip(starts, ends)):
+        o_s, l_s, m_s = attn_pv8_cross(qq, q_scale, kq[:, :, a:b], k_scale[:, :, a // gran_k:nblocks(b, gran_k)],
+                                       vq[:, :, a:b], v_scale, causal and s == len(starts) - 1, block_q, block_k,
+                                       gran_q, gran_k, return_m=True)
+        parts.append(o_s.astype(np.float64)); ms.append(m_s.astype(np.float64)); ls.append(l_s.astype(np.float64))
+    top = np.max(np.stack(ms), axis=0)
+    w = [l_s * np.exp(m_s - top) for l_s, m_s in zip(ls, ms)]
+    total = np.sum(np.stack(w), axis=0)
+    o = sum(w_s[..., None] * o_s for w_s, o_s in zip(w, parts)) / total[..., None]
+    o = o.astype(np.float16)
+    return (o, total.astype(np.float32)) if return_l else o
 
 
 def attn_pv8_slab(qq, q_scale, kq, k_scale, vq, v_scale, causal: bool, block_q: int, block_k: int,

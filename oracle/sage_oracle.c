@@ -433,7 +433,7 @@ void sage_oracle_quant_v(const uint16_t* v, int B, int H, int N, int D, int8_t* 
  * what one code of P^ is worth in the output: delta_V[c] * |V^| / (127 l) * 127 <= delta_V[c] / l. */
 static void l2_pv8_q_block(const int8_t* qq, const float* q_scale, const int8_t* kq, const float* k_scale,
                            const int8_t* vq, const float* v_scale, int Nq, int N, int D, int causal,
-                           int bq, int bkv, int gq, int gk, int i, uint16_t* o, float* lsum) {
+                           int bq, int bkv, int gq, int gk, int i, uint16_t* o, float* lsum, float* mrow) {
     int r0 = i * bq, r1 = r0 + bq < Nq ? r0 + bq : Nq, nr = r1 - r0;
     int Tn = (N + bkv - 1) / bkv;
     int shift = N - Nq;          /* Nq queries against N keys: end-aligned causal mask, as in l2_q_block */
@@ -490,6 +490,7 @@ static void l2_pv8_q_block(const int8_t* qq, const float* q_scale, const int8_t*
             o[(int64_t)(r0 + a) * D + c] = f32_to_f16(q, 0);
         }
         if (lsum) lsum[r0 + a] = l[a];
+        if (mrow) mrow[r0 + a] = m[a];
     }
     free(m); free(l); free(O); free(S); free(Pq);
 }
@@ -506,7 +507,7 @@ void sage_oracle_attn_pv8_slab_g(const int8_t* qq, const float* q_scale, const i
     for (int u = 0; u < n; ++u) {
         int i = nblocks < 0 ? u : blocks[u];
         l2_pv8_q_block(qq, q_scale, kq, k_scale, vq, v_scale, N, N, D, causal, block_q, block_k,
-                       gran_q, gran_k, i, o, lsum);
+                       gran_q, gran_k, i, o, lsum, NULL);
     }
 }
 
@@ -522,15 +523,16 @@ void sage_oracle_attn_pv8_g(const int8_t* qq, const float* q_scale, const int8_t
         int64_t s = u / Tm; int i = (int)(u % Tm);
         l2_pv8_q_block(qq + s * N * D, q_scale + s * nsq, kq + s * N * D, k_scale + s * nsk,
                        vq + s * N * D, v_scale + s * D, N, N, D, causal, block_q, block_k, gran_q, gran_k,
-                       i, o + s * N * D, lsum ? lsum + s * N : NULL);
+                       i, o + s * N * D, lsum ? lsum + s * N : NULL, NULL);
     }
 }
 
-/* The same with Nq queries against Nk keys: Q^ [B,H,Nq,D], K^ and V^ [B,H,Nk,D], output and lsum over Nq rows. */
+/* The same with Nq queries against Nk keys: Q^ [B,H,Nq,D], K^ and V^ [B,H,Nk,D], output, lsum and
+ * mrow (the final row maxima m of Algorithm 1, in the units of S; may be NULL) over Nq rows. */
 void sage_oracle_attn_pv8_cross_g(const int8_t* qq, const float* q_scale, const int8_t* kq, const float* k_scale,
                                   const int8_t* vq, const float* v_scale, int B, int H, int Nq, int Nk, int D,
                                   int causal, int block_q, int block_k, int gran_q, int gran_k,
-                                  uint16_t* o, float* lsum) {
+                                  uint16_t* o, float* lsum, float* mrow) {
     int Tm = (Nq + block_q - 1) / block_q;
     int nsq = (Nq + gran_q - 1) / gran_q, nsk = (Nk + gran_k - 1) / gran_k;
     int64_t units = (int64_t)B * H * Tm;
@@ -539,7 +541,7 @@ void sage_oracle_attn_pv8_cross_g(const int8_t* qq, const float* q_scale, const 
         int64_t s = u / Tm; int i = (int)(u % Tm);
         l2_pv8_q_block(qq + s * Nq * D, q_scale + s * nsq, kq + s * Nk * D, k_scale + s * nsk,
                        vq + s * Nk * D, v_scale + s * D, Nq, Nk, D, causal, block_q, block_k, gran_q, gran_k,
-                       i, o + s * Nq * D, lsum ? lsum + s * Nq : NULL);
+                       i, o + s * Nq * D, lsum ? lsum + s * Nq : NULL, mrow ? mrow + s * Nq : NULL);
     }
 }
 

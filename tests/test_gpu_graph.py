@@ -79,3 +79,52 @@ def test_graph_replays_equal_eager_runs(block_q, block_k, rope, pv8):
         outs = (k_i8, k_scale, k_mean, q_i8, q_scale, out) + ((v_i8t, v_scale) if pv8 else ())
         for got, want in zip(outs, eager[i]):
             assert torch.equal(got.view(torch.uint8), want.view(torch.uint8)), f"replay with inputs {i} differs from the eager run"
+
+
+def test_graph_replays_of_a_decode_step_with_the_keys_split():
+    """A decode step -- quantize a few new queries, attend to all keys with the keys split over
+    workgroups -- captured once and replayed with other queries; the workspace is dirtied between replays."""
+    print("[case] graph capture of sage_quant_q + sage_attn_cross_split_fwd", flush=True)
+    B, H, Nq, Nkv, D, chunks = 2, 3, 4, 2000, 128, 3
+    wk = si.custom("graph_split_k", B, H, Nkv, D, False, seed=si.BASE_SEED + 90)
+    _, k, v = si.full(wk)
+    queries = [si.full(si.custom("graph_split_q", B, H, Nq, D, False, seed=si.BASE_SEED + 91 + i))[0] for i in range(3)]
+    k_i8, k_scale, _ = sage.sage_smooth_quant_k(to_dev(k), 64)
+    vd = to_dev(v)
+    qd = torch.empty((B, H, Nq, D), dtype=torch.float16, device="cuda")
+    q_i8 = torch.empty((B, H, Nq, D), dtype=torch.int8, device="cuda")
+    q_scale = torch.empty((B, H, 1), dtype=torch.float32, device="cuda")
+    out = torch.empty((B, H, Nq, D), dtype=torch.float16, device="cuda")
+    assert sage.sage_attn_split_count(B, H, Nq, Nkv, True, chunks) == chunks
+    ws = torch.empty(sage.sage_attn_split_workspace(B, H, Nq, Nkv, D, True, chunks), dtype=torch.uint8, device="cuda")
+
+    def step():
+        sage.sage_quant_q(qd, wk.sm_scale, 128, q_i8, q_scale)
+        sage.sage_attn_cross_split_fwd(q_i8, q_scale, k_i8, k_scale, vd, True, wk.sm_scale, 128, 64, chunks, out, ws)
+
+    eager = []
+    for q in queries:
+        qd.copy_(to_dev(q))
+        step()
+        torch.cuda.synchronize()
+        eager.append(out.clone())
+    assert not torch.equal(eager[0], eager[1])
+
+    qd.copy_(to_dev(queries[0]))
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step()
+    for i in (1, 2, 0, 1):
+        qd.copy_(to_dev(queries[i]))
+        for t in (q_i8, q_scale, out, ws):
+            t.fill_(1)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int16), eager[i].view(torch.int16)), f"replay with queries {i} differs from the eager run"
