@@ -156,11 +156,11 @@ def sweep(per_token: bool, pv_int8: bool = False):
                 del q, k, v, k_i8, q_i8, out
 
 
-def cross(workload: str, nqs):
+def cross(workload: str, nqs, pv_int8: bool = False):
     """Speed of sage_attn_cross_fwd and sage_attn_cross_split_fwd: the last Nq tokens of the workload's
     sequence as queries against all of its keys and values (chunked prefill / decode shapes; the mask,
-    if causal, is aligned at the end).  Prints one table row per Nq; not part of the one-line
-    benchmark contract."""
+    if causal, is aligned at the end); with pv_int8 the same for the calls with the INT8 second product.
+    Prints one table row per Nq; not part of the one-line benchmark contract."""
     import torch
 
     import paper_2410_02367_amd as sage
@@ -172,8 +172,10 @@ def cross(workload: str, nqs):
     kd, vd = torch.from_numpy(k).cuda(), torch.from_numpy(v).cuda()
     B, H, N, D = w.B, w.H, w.N, w.D
     k_i8, k_scale, _ = sage.sage_smooth_quant_k(kd, w.block_k)
-    print(f"{w.name}: B={B} H={H} Nkv={N} D={D} causal={w.causal}, block_q={w.block_q} block_k={w.block_k}; "
-          "ops = 4 B H D x visible (query, key) pairs")
+    if pv_int8:
+        v_i8t, v_scale = sage.sage_quant_v(vd)
+    print(f"{w.name}: B={B} H={H} Nkv={N} D={D} causal={w.causal}, block_q={w.block_q} block_k={w.block_k}, "
+          f"{'INT8' if pv_int8 else 'FP16'} second product; ops = 4 B H D x visible (query, key) pairs")
     print("%8s  %10s %9s   %7s %10s %9s" % ("Nq", "attn ms", "TOPS", "chunks", "split ms", "TOPS"))
 
     def timed(call):
@@ -192,15 +194,25 @@ def cross(workload: str, nqs):
         qd = torch.from_numpy(np.ascontiguousarray(q[:, :, N - nq:])).cuda()
         q_i8, q_scale = sage.sage_quant_q(qd, w.sm_scale, w.block_q)
         out = torch.empty((B, H, nq, D), dtype=torch.float16, device="cuda")
-        ms = timed(lambda: sage.sage_attn_cross_fwd(q_i8, q_scale, k_i8, k_scale, vd, w.causal, w.sm_scale,
-                                                    w.block_q, w.block_k, out))
+        if pv_int8:
+            whole = lambda: sage.sage_attn_pv_int8_cross_fwd(q_i8, q_scale, k_i8, k_scale, v_i8t, v_scale, w.causal,
+                                                             w.sm_scale, w.block_q, w.block_k, out)
+        else:
+            whole = lambda: sage.sage_attn_cross_fwd(q_i8, q_scale, k_i8, k_scale, vd, w.causal, w.sm_scale,
+                                                     w.block_q, w.block_k, out)
+        ms = timed(whole)
         pairs = float(nq) * N - (float(nq) * (nq - 1) / 2 if w.causal else 0.0)
         ops = 4.0 * B * H * D * pairs
-        # the same with the keys cut into the number of chunks the library chooses (sage_attn_cross_split_fwd)
+        # the same with the keys cut into the number of chunks the library chooses (the *_cross_split_fwd call)
         n = sage.sage_attn_split_count(B, H, nq, N, w.causal, 0)
         ws = torch.empty(max(sage.sage_attn_split_workspace(B, H, nq, N, D, w.causal, 0), 16), dtype=torch.uint8, device="cuda")
-        ms_s = timed(lambda: sage.sage_attn_cross_split_fwd(q_i8, q_scale, k_i8, k_scale, vd, w.causal, w.sm_scale,
-                                                            w.block_q, w.block_k, 0, out, ws))
+        if pv_int8:
+            split = lambda: sage.sage_attn_pv_int8_cross_split_fwd(q_i8, q_scale, k_i8, k_scale, v_i8t, v_scale, w.causal,
+                                                                   w.sm_scale, w.block_q, w.block_k, 0, out, ws)
+        else:
+            split = lambda: sage.sage_attn_cross_split_fwd(q_i8, q_scale, k_i8, k_scale, vd, w.causal, w.sm_scale,
+                                                           w.block_q, w.block_k, 0, out, ws)
+        ms_s = timed(split)
         print("%8d  %10.4f %9.0f   %7d %10.4f %9.0f" % (nq, ms, ops / (ms * 1e-3) / 1e12, n, ms_s, ops / (ms_s * 1e-3) / 1e12),
               flush=True)
 
@@ -251,7 +263,7 @@ def main():
         sweep(args.scales == "token", args.pv == "int8")
         return
     if args.cross:
-        cross(args.workload, [int(x) for x in args.cross.split(",")])
+        cross(args.workload, [int(x) for x in args.cross.split(",")], args.pv == "int8")
         return
     w = si.WORKLOADS[args.workload]
     torch.cuda.set_device(0)

@@ -226,6 +226,22 @@ int sage_attn_pv_int8_cross_fwd(const int8_t* q_i8, const float* q_scale,
                                 int block_q, int block_k, void* stream);
 
 /*
+ * sage_attn_pv_int8_cross_fwd for few queries against many keys, with the keys cut into chunks as in
+ * sage_attn_cross_split_fwd (same chunk plan: sage_attn_split_count; same workspace size:
+ * sage_attn_split_workspace).  Every chunk runs the loop of Algorithm 1 with the second product of
+ * Section 4.3 as if it were the whole key set, so a code of P~ is relative to the running maximum
+ * WITHIN ITS CHUNK, not over all keys before it: the same attention as the unsplit call, but not the
+ * same rounding of P~ (never coarser: a chunk's maximum is at most the running maximum over all keys).
+ * One chunk is sage_attn_pv_int8_cross_fwd itself.
+ */
+int sage_attn_pv_int8_cross_split_fwd(const int8_t* q_i8, const float* q_scale,
+                                      const int8_t* k_i8, const float* k_scale,
+                                      const int8_t* v_i8t, const float* v_scale, void* o_f16,
+                                      void* workspace, size_t workspace_bytes,
+                                      int B, int H, int Nq, int Nkv, int D, int causal, float sm_scale,
+                                      int block_q, int block_k, int n_splits, void* stream);
+
+/*
  * Test hook: the raw int32 scores S^ = Q^ K^^T (Algorithm 1, the Matmul inside the S update)
  * produced by the same matrix-instruction code path as sage_attn_fwd, without mask.
  *   s_i32   out [B,H,N,N] int32 -- O(N^2) memory: meant for small N or for sub-problems.

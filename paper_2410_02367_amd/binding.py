@@ -15,7 +15,8 @@ EXPORTS = ("sage_status_string", "sage_quant_q", "sage_smooth_quant_k_workspace"
            "sage_attn_fwd", "sage_attn_qk_i32_debug",
            "sage_quant_v_workspace", "sage_quant_v_pitch", "sage_quant_v", "sage_attn_pv_int8_fwd",
            "sage_attn_cross_fwd", "sage_attn_pv_int8_cross_fwd",
-           "sage_attn_split_count", "sage_attn_split_workspace", "sage_attn_cross_split_fwd")
+           "sage_attn_split_count", "sage_attn_split_workspace", "sage_attn_cross_split_fwd",
+           "sage_attn_pv_int8_cross_split_fwd")
 
 
 class SageError(RuntimeError):
@@ -67,6 +68,8 @@ def load() -> ctypes.CDLL:
     lib.sage_attn_split_workspace.argtypes = [c_int] * 7
     lib.sage_attn_cross_split_fwd.restype = c_int
     lib.sage_attn_cross_split_fwd.argtypes = [c_void_p] * 7 + [c_size_t] + [c_int] * 6 + [c_float, c_int, c_int, c_int, c_void_p]
+    lib.sage_attn_pv_int8_cross_split_fwd.restype = c_int
+    lib.sage_attn_pv_int8_cross_split_fwd.argtypes = [c_void_p] * 8 + [c_size_t] + [c_int] * 6 + [c_float, c_int, c_int, c_int, c_void_p]
     lib.sage_attn_pv_int8_cross_fwd.restype = c_int
     lib.sage_attn_pv_int8_cross_fwd.argtypes = [c_void_p] * 7 + [c_int] * 6 + [c_float, c_int, c_int, c_void_p]
     lib.sage_quant_v_workspace.restype = c_size_t
@@ -262,6 +265,33 @@ def sage_attn_cross_split_fwd(q_i8, q_scale, k_i8, k_scale, v, causal: bool, sm_
                                           int(block_q), int(block_k), int(n_splits), _stream(stream))
     if st != 0:
         raise SageError(st, "sage_attn_cross_split_fwd")
+    return out
+
+
+def sage_attn_pv_int8_cross_split_fwd(q_i8, q_scale, k_i8, k_scale, v_i8t, v_scale, causal: bool, sm_scale: float,
+                                      block_q: int = 128, block_k: int = 64, n_splits: int = 0,
+                                      out=None, workspace=None, stream=None):
+    """sage_attn_pv_int8_cross_fwd with the keys cut into n_splits chunks (0 = chosen from the shape) and a merge.
+    workspace: uint8 device tensor of at least sage_attn_split_workspace(...) bytes (allocated here if not given)."""
+    B, H, Nkv, D = k_i8.shape
+    Nq = q_i8.shape[2]
+    if tuple(q_i8.shape) != (B, H, Nq, D) or tuple(v_i8t.shape) != (B, H, D, sage_quant_v_pitch(Nkv)):
+        raise TypeError("q_i8 / v_i8t: shapes do not match k_i8")
+    if out is None:
+        out = torch.empty((B, H, Nq, D), dtype=torch.float16, device=k_i8.device)
+    need = sage_attn_split_workspace(B, H, Nq, Nkv, D, causal, n_splits)
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=k_i8.device)
+    ws_ptr = _dev(workspace, torch.uint8, "workspace") if workspace is not None else 0
+    ws_bytes = workspace.numel() if workspace is not None else 0
+    st = load().sage_attn_pv_int8_cross_split_fwd(
+        _dev(q_i8, torch.int8, "q_i8"), _dev(q_scale, torch.float32, "q_scale"),
+        _dev(k_i8, torch.int8, "k_i8"), _dev(k_scale, torch.float32, "k_scale"),
+        _dev(v_i8t, torch.int8, "v_i8t"), _dev(v_scale, torch.float32, "v_scale"), _dev(out, torch.float16, "out"),
+        ws_ptr, ws_bytes, B, H, Nq, Nkv, D, int(bool(causal)), float(sm_scale), int(block_q), int(block_k), int(n_splits),
+        _stream(stream))
+    if st != 0:
+        raise SageError(st, "sage_attn_pv_int8_cross_split_fwd")
     return out
 
 

@@ -184,8 +184,8 @@ def check_pv8_asm(text: str) -> list:
     import re
     bodies = re.findall(r"^(_ZN4sage20sage_attn_pv8_kernel\w+):(.*?)^\.Lfunc_end\d+:", text, re.S | re.M)
     problems = []
-    if len(bodies) != 8:      # head dimension {64, 128} x {causal, full} x {per-block, per-token key scales}
-        problems.append(f"expected 8 INT8-P~V attention kernels in the assembly, found {len(bodies)}")
+    if len(bodies) != 16:     # head dimension {64, 128} x {causal, full} x {per-block, per-token key scales} x {whole, key chunks}
+        problems.append(f"expected 16 INT8-P~V attention kernels in the assembly, found {len(bodies)}")
     for name, body in bodies:
         in_asm = False
         for line in body.split("\n"):

@@ -171,6 +171,30 @@ int sage_attn_cross_split_fwd(const int8_t* q_i8, const float* q_scale, const in
     return e == hipSuccess ? SAGE_OK : SAGE_ERR_LAUNCH;
 }
 
+int sage_attn_pv_int8_cross_split_fwd(const int8_t* q_i8, const float* q_scale, const int8_t* k_i8, const float* k_scale,
+                                      const int8_t* v_i8t, const float* v_scale, void* o_f16,
+                                      void* workspace, size_t workspace_bytes,
+                                      int B, int H, int Nq, int Nkv, int D, int causal, float sm_scale,
+                                      int block_q, int block_k, int n_splits, void* stream) {
+    if (!q_i8 || !q_scale || !k_i8 || !k_scale || !v_i8t || !v_scale || !o_f16) return SAGE_ERR_NULL;
+    if (int e = check_shape(B, H, Nq, D)) return e;
+    if (int e = check_shape(B, H, Nkv, D)) return e;
+    if (causal && Nq > Nkv) return SAGE_ERR_UNSUPPORTED;
+    if (!quant_block_ok(block_q)) return SAGE_ERR_UNSUPPORTED;
+    if (block_k != 1 && block_k != 64 && block_k != 128) return SAGE_ERR_UNSUPPORTED;
+    if (n_splits < 0) return SAGE_ERR_VALUE;
+    if (!std::isfinite(sm_scale) || !(sm_scale > 0.0f)) return SAGE_ERR_VALUE;
+    const size_t need = sage_attn_split_workspace(B, H, Nq, Nkv, D, causal, n_splits);
+    if (need > 0 && !workspace) return SAGE_ERR_NULL;
+    if (workspace_bytes < need) return SAGE_ERR_WORKSPACE;
+    if (!aligned(q_i8, 16) || !aligned(k_i8, 16) || !aligned(v_i8t, 16) || !aligned(o_f16, 16) ||
+        !aligned(q_scale, 4) || !aligned(k_scale, 4) || !aligned(v_scale, 16) || (need > 0 && !aligned(workspace, 16)))
+        return SAGE_ERR_ALIGN;
+    hipError_t e = sage::launch_attn_pv8_split(q_i8, q_scale, k_i8, k_scale, v_i8t, v_scale, o_f16, workspace, B * H, Nq, Nkv,
+                                               D, causal ? 1 : 0, block_q, block_k, n_splits, (hipStream_t)stream);
+    return e == hipSuccess ? SAGE_OK : SAGE_ERR_LAUNCH;
+}
+
 size_t sage_quant_v_workspace(int B, int H, int N, int D) {
     (void)N;
     if (B <= 0 || H <= 0 || D <= 0) return 0;

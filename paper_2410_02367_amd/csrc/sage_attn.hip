@@ -1050,6 +1050,14 @@ __global__ void __launch_bounds__(256) merge_splits_kernel(const _Float16* __res
     *(v8h*)(og + (size_t)row * D + c8 * 8) = y;
 }
 
+hipError_t launch_merge_splits(const void* part, const float* lse, void* o, long rows, int D, int n_splits, hipStream_t st) {
+    const _Float16* pp = (const _Float16*)part;
+    _Float16* op = (_Float16*)o;
+    if (D == 64) merge_splits_kernel<64><<<(unsigned)((rows + 31) / 32), 256, 0, st>>>(pp, lse, op, rows, n_splits);
+    else merge_splits_kernel<128><<<(unsigned)((rows + 15) / 16), 256, 0, st>>>(pp, lse, op, rows, n_splits);
+    return hipGetLastError();
+}
+
 hipError_t launch_attn_split(const int8_t* qq, const float* qscale, const int8_t* kq, const float* kscale,
                              const void* v, void* o, void* workspace, int BH, int Nq, int N, int D, int causal,
                              int block_q, int block_k, int requested, hipStream_t st) {
@@ -1063,10 +1071,7 @@ hipError_t launch_attn_split(const int8_t* qq, const float* qscale, const int8_t
         ? launch_d<64>(qq, qscale, kq, kscale, v, part, nullptr, BH, Nq, N, causal, block_q, block_k, sp, st)
         : launch_d<128>(qq, qscale, kq, kscale, v, part, nullptr, BH, Nq, N, causal, block_q, block_k, sp, st);
     if (e != hipSuccess) return e;
-    _Float16* op = (_Float16*)o;
-    if (D == 64) merge_splits_kernel<64><<<(unsigned)((rows + 31) / 32), 256, 0, st>>>(part, sp.lse, op, rows, sp.n_splits);
-    else merge_splits_kernel<128><<<(unsigned)((rows + 15) / 16), 256, 0, st>>>(part, sp.lse, op, rows, sp.n_splits);
-    return hipGetLastError();
+    return launch_merge_splits(part, sp.lse, o, rows, D, sp.n_splits, st);
 }
 
 }  // namespace sage

@@ -74,13 +74,14 @@ template <int D> __device__ __forceinline__ int k_swz8(int row) { return D == 12
 __device__ __forceinline__ int vt_swz(int ch) { return (ch >> 2) & 3; }
 }  // namespace
 
-template <int D, bool CAUSAL, bool KTOK>
+template <int D, bool CAUSAL, bool KTOK, bool SPLIT>
 __global__ void __launch_bounds__(256, 2)
 sage_attn_pv8_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
                      const int8_t* __restrict__ ki, const float* __restrict__ ksc,
                      const int8_t* __restrict__ vt, const float* __restrict__ vsc,
-                     _Float16* __restrict__ og,
-                     int Nq, int N, int Np, int shift_q, int shift_k, int tiles_q, int per_xcd, long total_tiles) {
+                     _Float16* __restrict__ og, float* __restrict__ lse,
+                     int Nq, int Nkv, int Np, int shift_q, int shift_k, int tiles_q, int per_xcd, long total_tiles,
+                     int BH, int n_splits, int chunk) {
     constexpr int NT = 256, QTILE = 128, KT = 64;
     constexpr int KS = D / 32, DT = D / 32;
     constexpr int KB = KT * D, VB = D * KT;            // bytes per K^ tile / V^^T tile
@@ -102,18 +103,28 @@ sage_attn_pv8_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qs
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
     const long gidx = (long)xcd * per_xcd + slot;
     if (slot >= per_xcd || gidx >= total_tiles) return;
-    const int bh = (int)(gidx / tiles_q);
+    const int unit = (int)(gidx / tiles_q);          // (slab, key chunk), chunk fastest
     const int qt = tiles_q - 1 - (int)(gidx % tiles_q);
+    const int bh = SPLIT ? unit / n_splits : unit, split = SPLIT ? unit - bh * n_splits : 0;
 
     const int t = threadIdx.x, lane = t & 63;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
     const int ql = lane & 31, h = lane >> 5;
     const int qrow0 = qt * QTILE + wave * 32;
     const int q_row = qrow0 + ql;
-    // Nq query rows against N keys per slab; with a causal mask the queries are the last Nq tokens
-    const size_t slab = (size_t)bh * N, slab_q = (size_t)bh * Nq;
-    const int coff = N - Nq;
-    const int nbq = (Nq + (1 << shift_q) - 1) >> shift_q, nbk = (N + (1 << shift_k) - 1) >> shift_k;
+    // Nq query rows against Nkv keys per slab; with a causal mask the queries are the last Nq tokens.
+    // With n_splits > 1 the workgroup sees only the keys k0 .. k0 + N - 1 of its slab (chunk is a
+    // multiple of 128 keys; the last chunk takes the remainder), runs the whole recursion on them --
+    // own running maximum, hence own codes of P~ -- and leaves a partial result: its normalized O and,
+    // per row, lse = m + log2(sum of 127 P~), from which the partial results of a row are merged.
+    // N is the chunk's key count from here on.  SPLIT is a template parameter so that the unsplit
+    // kernels keep their register allocation (as a run-time case it cost them 5-8 %).
+    const int k0 = SPLIT ? split * chunk : 0;
+    const int N = SPLIT ? (split == n_splits - 1 ? Nkv - k0 : chunk) : Nkv;
+    const size_t slab = (size_t)bh * Nkv + k0, slab_q = (size_t)bh * Nq;
+    const size_t slab_o = SPLIT ? ((size_t)split * BH + bh) * Nq : slab_q;
+    const int coff = Nkv - Nq - k0;
+    const int nbq = (Nq + (1 << shift_q) - 1) >> shift_q, nbk = (Nkv + (1 << shift_k) - 1) >> shift_k;
 
     p4i qreg[QREG > 0 ? QREG : 1];
 #pragma unroll
@@ -122,7 +133,7 @@ sage_attn_pv8_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qs
         if (q_row < Nq) qreg[ks] = *(const p4i*)(qi + (slab_q + q_row) * D + ks * 32 + h * 16);
     }
     const float dq = qsc[(size_t)bh * nbq + ((q_row < Nq ? q_row : Nq - 1) >> shift_q)] * PV8_LOG2E;
-    const float* __restrict__ ksc_bh = ksc + (size_t)bh * nbk;
+    const float* __restrict__ ksc_bh = ksc + (size_t)bh * nbk + (k0 >> shift_k);
 
     const int kv_tiles_all = (N + KT - 1) / KT;
     int T = kv_tiles_all, Tw = kv_tiles_all;
@@ -143,7 +154,7 @@ sage_attn_pv8_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qs
     const unsigned k_goff0 = (unsigned)(k_unperm(t / KCH) * D + (((t % KCH) ^ k_swz8<D>(t / KCH)) * 16));
     const unsigned v_goff0 = (unsigned)((t >> 2) * Np + (((t & 3) ^ vt_swz(t >> 2)) * 16));
     const p4i k_desc = pv8_descriptor(ki + slab * D, (unsigned)N * D);
-    const p4i v_desc = pv8_descriptor(vt + (size_t)bh * D * Np, (unsigned)D * Np);
+    const p4i v_desc = pv8_descriptor(vt + (size_t)bh * D * Np + k0, (unsigned)D * Np - (unsigned)k0);
     const p4i ks_desc = pv8_descriptor(ksc_bh, (unsigned)N * 4u);      // per-token variant: N scales; past the end reads 0
     const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)lds;
     if (QREG < KS) {
@@ -372,8 +383,11 @@ sage_attn_pv8_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qs
     // ---- epilogue: O = (O_fp32 + A) * delta_V[c] / sum(127 P~)
     const float lt = l127 + lane32_partner(l127);
     const float inv = 1.0f / lt, g_run = 1.0f / ginv;
-    if (q_row < Nq) {
-        _Float16* orow = og + (slab_q + q_row) * D;
+    int q_out = q_row;
+    if (SPLIT) asm volatile("" : "+v"(q_out));       // the output addresses are formed here, not carried through the loop
+    if (q_out < Nq) {
+        if (SPLIT && h == 0) lse[slab_o + q_out] = m_run + __builtin_amdgcn_logf(lt);
+        _Float16* orow = og + (slab_o + q_out) * D;
         const float* dv = vsc + (size_t)bh * D;
 #pragma unroll
         for (int cb = 0; cb < DT; ++cb)
@@ -396,28 +410,52 @@ sage_attn_pv8_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qs
 template <int D>
 static hipError_t launch_pv8_d(const int8_t* qq, const float* qscale, const int8_t* kq, const float* kscale,
                                const int8_t* vt, const float* vscale, void* o, int BH, int Nq, int N, int causal,
-                               int shift_q, int shift_k, bool ktok, hipStream_t st) {
+                               int shift_q, int shift_k, bool ktok, const SplitPlan& sp, hipStream_t st) {
     const int tiles_q = (Nq + 127) / 128, Np = 64 * ((N + 63) / 64);
-    const long total = (long)BH * tiles_q;
+    const long total = (long)BH * sp.n_splits * tiles_q;
     const int per_xcd = (int)((total + 7) / 8);
     const dim3 grid((unsigned)(per_xcd * 8)), block(256);
-#define SAGE_PV8(C, K) sage_attn_pv8_kernel<D, C, K><<<grid, block, 0, st>>>( \
-        qq, qscale, kq, kscale, vt, vscale, (_Float16*)o, Nq, N, Np, shift_q, shift_k, tiles_q, per_xcd, total)
+#define SAGE_PV8_S(C, K, S) sage_attn_pv8_kernel<D, C, K, S><<<grid, block, 0, st>>>( \
+        qq, qscale, kq, kscale, vt, vscale, (_Float16*)o, sp.lse, Nq, N, Np, shift_q, shift_k, tiles_q, per_xcd, total, \
+        BH, sp.n_splits, sp.chunk)
+#define SAGE_PV8(C, K) do { if (sp.n_splits > 1) SAGE_PV8_S(C, K, true); else SAGE_PV8_S(C, K, false); } while (0)
     if (causal) { if (ktok) SAGE_PV8(true, true); else SAGE_PV8(true, false); }
     else        { if (ktok) SAGE_PV8(false, true); else SAGE_PV8(false, false); }
 #undef SAGE_PV8
+#undef SAGE_PV8_S
     return hipGetLastError();
+}
+
+static hipError_t launch_pv8_plan(const int8_t* qq, const float* qscale, const int8_t* kq, const float* kscale,
+                                  const int8_t* vt, const float* vscale, void* o, int BH, int Nq, int N, int D, int causal,
+                                  int block_q, int block_k, const SplitPlan& sp, hipStream_t st) {
+    int shift_q = 0, shift_k = 0;
+    while ((1 << shift_q) < block_q) ++shift_q;
+    while ((1 << shift_k) < block_k) ++shift_k;
+    const bool ktok = block_k == 1;
+    if (D == 64) return launch_pv8_d<64>(qq, qscale, kq, kscale, vt, vscale, o, BH, Nq, N, causal, shift_q, shift_k, ktok, sp, st);
+    return launch_pv8_d<128>(qq, qscale, kq, kscale, vt, vscale, o, BH, Nq, N, causal, shift_q, shift_k, ktok, sp, st);
 }
 
 hipError_t launch_attn_pv8(const int8_t* qq, const float* qscale, const int8_t* kq, const float* kscale,
                            const int8_t* vt, const float* vscale, void* o, int BH, int Nq, int N, int D, int causal,
                            int block_q, int block_k, hipStream_t st) {
-    int shift_q = 0, shift_k = 0;
-    while ((1 << shift_q) < block_q) ++shift_q;
-    while ((1 << shift_k) < block_k) ++shift_k;
-    const bool ktok = block_k == 1;
-    if (D == 64) return launch_pv8_d<64>(qq, qscale, kq, kscale, vt, vscale, o, BH, Nq, N, causal, shift_q, shift_k, ktok, st);
-    return launch_pv8_d<128>(qq, qscale, kq, kscale, vt, vscale, o, BH, Nq, N, causal, shift_q, shift_k, ktok, st);
+    const SplitPlan whole = {1, 0, nullptr};
+    return launch_pv8_plan(qq, qscale, kq, kscale, vt, vscale, o, BH, Nq, N, D, causal, block_q, block_k, whole, st);
+}
+
+// The keys cut into chunks, as in launch_attn_split(): same plan, same workspace layout, same merge
+// (the common factor 127 of the chunks' denominators cancels in the weights).
+hipError_t launch_attn_pv8_split(const int8_t* qq, const float* qscale, const int8_t* kq, const float* kscale,
+                                 const int8_t* vt, const float* vscale, void* o, void* workspace, int BH, int Nq, int N,
+                                 int D, int causal, int block_q, int block_k, int requested, hipStream_t st) {
+    SplitPlan sp = plan_split(BH, Nq, N, causal, requested);
+    if (sp.n_splits == 1) return launch_attn_pv8(qq, qscale, kq, kscale, vt, vscale, o, BH, Nq, N, D, causal, block_q, block_k, st);
+    const long rows = (long)BH * Nq;
+    sp.lse = (float*)((char*)workspace + (size_t)sp.n_splits * rows * D * sizeof(_Float16));
+    hipError_t e = launch_pv8_plan(qq, qscale, kq, kscale, vt, vscale, workspace, BH, Nq, N, D, causal, block_q, block_k, sp, st);
+    if (e != hipSuccess) return e;
+    return launch_merge_splits(workspace, sp.lse, o, rows, D, sp.n_splits, st);
 }
 
 }  // namespace sage

@@ -33,6 +33,11 @@ hipError_t launch_attn_split(const int8_t* qq, const float* qscale, const int8_t
                              const void* v, void* o, void* workspace, int BH, int Nq, int N, int D, int causal,
                              int block_q, int block_k, int requested, hipStream_t st);
 
+hipError_t launch_merge_splits(const void* part, const float* lse, void* o, long rows, int D, int n_splits, hipStream_t st);
+hipError_t launch_attn_pv8_split(const int8_t* qq, const float* qscale, const int8_t* kq, const float* kscale,
+                                 const int8_t* vt, const float* vscale, void* o, void* workspace, int BH, int Nq, int N,
+                                 int D, int causal, int block_q, int block_k, int requested, hipStream_t st);
+
 // INT8 second product (Section 4.3): per-channel quantizer of V (transposed output, pitch
 // 64 * ceil(N / 64)) and the attention kernel that consumes it.
 hipError_t launch_quant_v(const void* v, int8_t* vt, float* vscale, unsigned* amax_bits,

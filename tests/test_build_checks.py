@@ -96,8 +96,8 @@ def test_matrix_instruction_reading_a_fresh_valu_result_is_reported():
 
 from paper_2410_02367_amd.build import check_pv8_asm  # noqa: E402
 
-PV8_KERNELS = ["_ZN4sage20sage_attn_pv8_kernelILi%dELb%dELb%dEEEvPKa" % (d, c, k)
-               for d in (64, 128) for c in (0, 1) for k in (0, 1)]
+PV8_KERNELS = ["_ZN4sage20sage_attn_pv8_kernelILi%dELb%dELb%dELb%dEEEvPKa" % (d, c, k, sp)
+               for d in (64, 128) for c in (0, 1) for k in (0, 1) for sp in (0, 1)]
 
 
 def fake_pv8(body_of_first: str, kernels=PV8_KERNELS) -> str:
@@ -117,7 +117,7 @@ PV8_CLEAN = """\t;;#ASMSTART
 
 def test_pv8_clean_text_passes_and_a_missing_kernel_is_reported():
     assert check_pv8_asm(fake_pv8(PV8_CLEAN)) == []
-    assert any("expected 8" in p for p in check_pv8_asm(fake_pv8(PV8_CLEAN, PV8_KERNELS[:-1])))
+    assert any("expected 16" in p for p in check_pv8_asm(fake_pv8(PV8_CLEAN, PV8_KERNELS[:-1])))
 
 
 def test_pv8_scratch_and_compiler_use_of_m0_are_reported():

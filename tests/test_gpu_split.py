@@ -113,3 +113,80 @@ def test_decode_at_the_headline_shape_sampled_slabs():
             o_ref = oracle.attn_l2_cross(qq, qs, kq, ks, v[:, h:h + 1], True, 128, 64)
             err, cos = assert_output_close(o[:, h:h + 1], o_ref, f"Nq{Nq} head {h}")
             print(f"  head {h}: max_abs {err:.2e} cos {cos:.7f}", flush=True)
+
+
+# ------------------------------------------------------------------ the INT8 second product with the keys split
+#
+# Here the split is NOT the unsplit kernel in another order: every chunk has its own running maximum
+# and hence its own codes of P~, so the oracle is the split algorithm itself
+# (oracle.attn_pv8_cross_split), with the chunk boundaries of the documented plan: chunks of
+# 128 * ceil(Nkv / (128 * requested)) keys, sage_attn_split_count() of them.  Tolerance as for the unsplit
+# INT8 kernels: 2e-3 plus two codes (delta_V[c] / L, L = the row's denominator relative to its global
+# maximum) for every element, 99.9 % of the elements within 2e-3, cosine >= 0.9999.
+
+from test_gpu_pv_int8 import assert_pv8_close  # noqa: E402
+
+PV8_CASES = [c for c in CASES if c[0] in ("decode_one_query", "decode_one_query_nc_d64", "chunked_prefill_tail",
+                                          "request_cut_by_the_mask", "k_blocks_of_128", "per_token_scales",
+                                          "per_token_scales_d64", "last_chunk_one_key")]
+
+
+def chunk_starts(B, H, Nq, Nkv, causal, req):
+    n = sage.sage_attn_split_count(B, H, Nq, Nkv, causal, req)
+    chunk = 128 * -(-Nkv // (128 * req))
+    return [i * chunk for i in range(n)]
+
+
+@pytest.mark.parametrize("name,B,H,Nq,Nkv,D,causal,bq,bk,req,used", PV8_CASES, ids=[c[0] for c in PV8_CASES])
+def test_split_parity_int8_second_product(name, B, H, Nq, Nkv, D, causal, bq, bk, req, used):
+    print(f"[case] INT8 PV split {name} B{B} H{H} Nq{Nq} Nkv{Nkv} D{D} causal={causal} scales {bq}x{bk} chunks {req}", flush=True)
+    starts = chunk_starts(B, H, Nq, Nkv, causal, req)
+    assert len(starts) == used
+    q, k, v, sm = make(name, B, H, Nq, Nkv, D, len(name))
+    k_i8, k_scale, _ = sage.sage_smooth_quant_k(to_dev(k), bk)
+    q_i8, q_scale = sage.sage_quant_q(to_dev(q), sm, bq)
+    v_i8t, v_scale = sage.sage_quant_v(to_dev(v))
+    o = sage.sage_attn_pv_int8_cross_split_fwd(q_i8, q_scale, k_i8, k_scale, v_i8t, v_scale, causal, sm, bq, bk, n_splits=req)
+    torch.cuda.synchronize()
+    kq, ks, _ = oracle.smooth_quant_k(k, bk)
+    qq, qs = oracle.quant_q(q, sm, bq)
+    vq, vs = oracle.quant_v(v)
+    assert np.array_equal(k_i8.cpu().numpy(), kq) and np.array_equal(q_i8.cpu().numpy(), qq)
+    assert np.array_equal(v_i8t.cpu().numpy()[..., :Nkv], vq.transpose(0, 1, 3, 2))
+    o_ref, big_l = oracle.attn_pv8_cross_split(qq, qs, kq, ks, vq, vs, causal, 128, 64, starts, gran_q=bq, gran_k=bk,
+                                               return_l=True)
+    err, cos, frac = assert_pv8_close(o.cpu().numpy(), o_ref, big_l, vs, name)
+    print(f"  max_abs {err:.2e} cos {cos:.7f} within 2e-3: {frac:.5f}", flush=True)
+
+
+def test_int8_second_product_one_chunk_is_the_unsplit_call_bit_for_bit():
+    q, k, v, sm = make("one8", 2, 2, 100, 777, 128, 2)
+    k_i8, k_scale, _ = sage.sage_smooth_quant_k(to_dev(k), 64)
+    q_i8, q_scale = sage.sage_quant_q(to_dev(q), sm, 128)
+    v_i8t, v_scale = sage.sage_quant_v(to_dev(v))
+    a = sage.sage_attn_pv_int8_cross_fwd(q_i8, q_scale, k_i8, k_scale, v_i8t, v_scale, True, sm, 128, 64)
+    b = sage.sage_attn_pv_int8_cross_split_fwd(q_i8, q_scale, k_i8, k_scale, v_i8t, v_scale, True, sm, 128, 64, n_splits=1)
+    torch.cuda.synchronize()
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+
+
+def test_int8_second_product_decode_at_the_headline_shape_sampled_slabs():
+    B, H, Nkv, D, Nq = 1, 32, 16384, 128, 64
+    q, k, v, sm = make("full8", B, H, Nq, Nkv, D, 8)
+    k_i8, k_scale, _ = sage.sage_smooth_quant_k(to_dev(k), 64)
+    q_i8, q_scale = sage.sage_quant_q(to_dev(q), sm, 128)
+    v_i8t, v_scale = sage.sage_quant_v(to_dev(v))
+    n = sage.sage_attn_split_count(B, H, Nq, Nkv, True, 0)
+    print(f"[case] INT8 PV split headline keys, Nq {Nq}: {n} chunks", flush=True)
+    o = sage.sage_attn_pv_int8_cross_split_fwd(q_i8, q_scale, k_i8, k_scale, v_i8t, v_scale, True, sm, 128, 64)
+    torch.cuda.synchronize()
+    o = o.cpu().numpy()
+    starts = chunk_starts(B, H, Nq, Nkv, True, n)      # the chosen count, requested explicitly, gives the same plan
+    assert len(starts) == n == 8
+    for h in (0, 13, 31):
+        kq, ks, _ = oracle.smooth_quant_k(k[:, h:h + 1], 64)
+        qq, qs = oracle.quant_q(q[:, h:h + 1], sm, 128)
+        vq, vs = oracle.quant_v(v[:, h:h + 1])
+        o_ref, big_l = oracle.attn_pv8_cross_split(qq, qs, kq, ks, vq, vs, True, 128, 64, starts, return_l=True)
+        err, cos, frac = assert_pv8_close(o[:, h:h + 1], o_ref, big_l, vs, f"head {h}")
+        print(f"  head {h}: max_abs {err:.2e} cos {cos:.7f} within 2e-3: {frac:.5f}", flush=True)
