@@ -378,11 +378,22 @@ def sage_attn_qk_i32_debug(q_i8, k_i8, s_i32=None, stream=None):
     return s_i32
 
 
-def sageattn(q, k, v, causal: bool = False, sm_scale: float | None = None, block_q: int = 128, block_k: int = 64):
-    """Convenience: the three library calls in order (pre-pass on K, pre-pass on Q, attention)."""
+def sageattn(q, k, v, causal: bool = False, sm_scale: float | None = None, block_q: int = 128, block_k: int = 64,
+             pv_int8: bool = False):
+    """Convenience: the library calls in order (pre-pass on K, on Q and, with pv_int8, on V; attention).
+    q [B,H,Nq,D] against k, v [B,H,Nkv,D]: equal lengths take the self-attention calls, different
+    lengths the calls that may split the keys over workgroups (end-aligned causal mask)."""
     D = q.shape[-1]
     if sm_scale is None:
         sm_scale = float(torch.tensor(1.0, dtype=torch.float32) / torch.sqrt(torch.tensor(float(D), dtype=torch.float32)))
     k_i8, k_scale, _ = sage_smooth_quant_k(k, block_k)
     q_i8, q_scale = sage_quant_q(q, sm_scale, block_q)
-    return sage_attn_fwd(q_i8, q_scale, k_i8, k_scale, v, causal, sm_scale, block_q, block_k)
+    same = q.shape[2] == k.shape[2]
+    if pv_int8:
+        v_i8t, v_scale = sage_quant_v(v)
+        if same:
+            return sage_attn_pv_int8_fwd(q_i8, q_scale, k_i8, k_scale, v_i8t, v_scale, causal, sm_scale, block_q, block_k)
+        return sage_attn_pv_int8_cross_split_fwd(q_i8, q_scale, k_i8, k_scale, v_i8t, v_scale, causal, sm_scale, block_q, block_k)
+    if same:
+        return sage_attn_fwd(q_i8, q_scale, k_i8, k_scale, v, causal, sm_scale, block_q, block_k)
+    return sage_attn_cross_split_fwd(q_i8, q_scale, k_i8, k_scale, v, causal, sm_scale, block_q, block_k)

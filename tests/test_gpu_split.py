@@ -190,3 +190,26 @@ def test_int8_second_product_decode_at_the_headline_shape_sampled_slabs():
         o_ref, big_l = oracle.attn_pv8_cross_split(qq, qs, kq, ks, vq, vs, True, 128, 64, starts, return_l=True)
         err, cos, frac = assert_pv8_close(o[:, h:h + 1], o_ref, big_l, vs, f"head {h}")
         print(f"  head {h}: max_abs {err:.2e} cos {cos:.7f} within 2e-3: {frac:.5f}", flush=True)
+
+
+def test_convenience_wrapper_routes_by_lengths_and_second_product():
+    """sageattn() only chains the library calls: its output is bit for bit that of the explicit chain."""
+    q, k, v, sm = make("wrap", 1, 4, 7, 4000, 128, 3)
+    qd, kd, vd = to_dev(q), to_dev(k), to_dev(v)
+    k_i8, k_scale, _ = sage.sage_smooth_quant_k(kd, 64)
+    q_i8, q_scale = sage.sage_quant_q(qd, sm, 128)
+    v_i8t, v_scale = sage.sage_quant_v(vd)
+    a = sage.sageattn(qd, kd, vd, True, sm)
+    b = sage.sage_attn_cross_split_fwd(q_i8, q_scale, k_i8, k_scale, vd, True, sm, 128, 64)
+    a8 = sage.sageattn(qd, kd, vd, True, sm, pv_int8=True)
+    b8 = sage.sage_attn_pv_int8_cross_split_fwd(q_i8, q_scale, k_i8, k_scale, v_i8t, v_scale, True, sm, 128, 64)
+    # equal lengths: the self-attention calls
+    kq_i8, kq_scale = sage.sage_quant_q(kd, sm, 128)
+    c = sage.sageattn(kd, kd, vd, False, sm)
+    d = sage.sage_attn_fwd(kq_i8, kq_scale, k_i8, k_scale, vd, False, sm, 128, 64)
+    c8 = sage.sageattn(kd, kd, vd, False, sm, pv_int8=True)
+    d8 = sage.sage_attn_pv_int8_fwd(kq_i8, kq_scale, k_i8, k_scale, v_i8t, v_scale, False, sm, 128, 64)
+    torch.cuda.synchronize()
+    assert sage.sage_attn_split_count(1, 4, 7, 4000, True, 0) > 1
+    for x, y in ((a, b), (a8, b8), (c, d), (c8, d8)):
+        assert torch.equal(x.view(torch.int16), y.view(torch.int16))
