@@ -102,39 +102,45 @@ int sage_rope_smooth_quant_k(const void* k_f16, const float* rope_cos, const flo
                                B, H, N, D, block_k, stream);
 }
 
-int sage_attn_fwd(const int8_t* q_i8, const float* q_scale, const int8_t* k_i8, const float* k_scale,
-                  const void* v_f16, void* o_f16, int B, int H, int N, int D, int causal,
-                  float sm_scale, int block_q, int block_k, void* stream) {
-    if (!q_i8 || !q_scale || !k_i8 || !k_scale || !v_f16 || !o_f16) return SAGE_ERR_NULL;
-    if (int e = check_shape(B, H, N, D)) return e;
-    if (!quant_block_ok(block_q)) return SAGE_ERR_UNSUPPORTED;
-    if (block_k != 1 && block_k != 64 && block_k != 128) return SAGE_ERR_UNSUPPORTED;
-    if (!std::isfinite(sm_scale) || !(sm_scale > 0.0f)) return SAGE_ERR_VALUE;
-    if (!aligned(q_i8, 16) || !aligned(k_i8, 16) || !aligned(v_f16, 16) || !aligned(o_f16, 16) ||
-        !aligned(q_scale, 4) || !aligned(k_scale, 4))
-        return SAGE_ERR_ALIGN;
-    hipError_t e = sage::launch_attn(q_i8, q_scale, k_i8, k_scale, v_f16, o_f16, nullptr, B * H, N, N, D,
-                                     causal ? 1 : 0, block_q, block_k, (hipStream_t)stream);
-    return e == hipSuccess ? SAGE_OK : SAGE_ERR_LAUNCH;
-}
-
-int sage_attn_cross_fwd(const int8_t* q_i8, const float* q_scale, const int8_t* k_i8, const float* k_scale,
-                        const void* v_f16, void* o_f16, int B, int H, int Nq, int Nkv, int D, int causal,
-                        float sm_scale, int block_q, int block_k, void* stream) {
-    if (!q_i8 || !q_scale || !k_i8 || !k_scale || !v_f16 || !o_f16) return SAGE_ERR_NULL;
+namespace {
+// The six attention entry points differ in the second product (v is V in fp16, or V^^T in INT8 with
+// v_scale), in whether the two lengths may differ, and in whether the keys are cut into chunks
+// (split: n_splits requested chunks and a workspace; otherwise one chunk, no workspace).
+int attn_impl(bool pv_int8, bool split, const int8_t* q_i8, const float* q_scale, const int8_t* k_i8,
+              const float* k_scale, const void* v, const float* v_scale, void* o_f16,
+              void* workspace, size_t workspace_bytes, int B, int H, int Nq, int Nkv, int D, int causal,
+              float sm_scale, int block_q, int block_k, int n_splits, void* stream) {
+    if (!q_i8 || !q_scale || !k_i8 || !k_scale || !v || !o_f16 || (pv_int8 && !v_scale)) return SAGE_ERR_NULL;
     if (int e = check_shape(B, H, Nq, D)) return e;
     if (int e = check_shape(B, H, Nkv, D)) return e;
     if (causal && Nq > Nkv) return SAGE_ERR_UNSUPPORTED;        // a query before the first key would see nothing
     if (!quant_block_ok(block_q)) return SAGE_ERR_UNSUPPORTED;
     if (block_k != 1 && block_k != 64 && block_k != 128) return SAGE_ERR_UNSUPPORTED;
+    if (split && n_splits < 0) return SAGE_ERR_VALUE;
     if (!std::isfinite(sm_scale) || !(sm_scale > 0.0f)) return SAGE_ERR_VALUE;
-    if (!aligned(q_i8, 16) || !aligned(k_i8, 16) || !aligned(v_f16, 16) || !aligned(o_f16, 16) ||
-        !aligned(q_scale, 4) || !aligned(k_scale, 4))
+    const size_t need = split ? sage_attn_split_workspace(B, H, Nq, Nkv, D, causal, n_splits) : 0;
+    if (need > 0 && !workspace) return SAGE_ERR_NULL;
+    if (workspace_bytes < need) return SAGE_ERR_WORKSPACE;
+    if (!aligned(q_i8, 16) || !aligned(k_i8, 16) || !aligned(v, 16) || !aligned(o_f16, 16) ||
+        !aligned(q_scale, 4) || !aligned(k_scale, 4) || (pv_int8 && !aligned(v_scale, 16)) ||
+        (need > 0 && !aligned(workspace, 16)))
         return SAGE_ERR_ALIGN;
-    hipError_t e = sage::launch_attn(q_i8, q_scale, k_i8, k_scale, v_f16, o_f16, nullptr, B * H, Nq, Nkv, D,
-                                     causal ? 1 : 0, block_q, block_k, (hipStream_t)stream);
+    const int c = causal ? 1 : 0, BH = B * H;
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t e;
+    if (pv_int8) {
+        const int8_t* vt = (const int8_t*)v;
+        e = split ? sage::launch_attn_pv8_split(q_i8, q_scale, k_i8, k_scale, vt, v_scale, o_f16, workspace, BH, Nq, Nkv, D, c,
+                                                block_q, block_k, n_splits, st)
+                  : sage::launch_attn_pv8(q_i8, q_scale, k_i8, k_scale, vt, v_scale, o_f16, BH, Nq, Nkv, D, c, block_q, block_k, st);
+    } else {
+        e = split ? sage::launch_attn_split(q_i8, q_scale, k_i8, k_scale, v, o_f16, workspace, BH, Nq, Nkv, D, c,
+                                            block_q, block_k, n_splits, st)
+                  : sage::launch_attn(q_i8, q_scale, k_i8, k_scale, v, o_f16, nullptr, BH, Nq, Nkv, D, c, block_q, block_k, st);
+    }
     return e == hipSuccess ? SAGE_OK : SAGE_ERR_LAUNCH;
 }
+}  // namespace
 
 int sage_attn_split_count(int B, int H, int Nq, int Nkv, int causal, int n_splits) {
     if (B <= 0 || H <= 0 || Nq <= 0 || Nkv <= 0 || n_splits < 0) return 0;
@@ -148,27 +154,42 @@ size_t sage_attn_split_workspace(int B, int H, int Nq, int Nkv, int D, int causa
     return (size_t)n * B * H * Nq * ((size_t)D * 2 + 4);
 }
 
+int sage_attn_fwd(const int8_t* q_i8, const float* q_scale, const int8_t* k_i8, const float* k_scale,
+                  const void* v_f16, void* o_f16, int B, int H, int N, int D, int causal,
+                  float sm_scale, int block_q, int block_k, void* stream) {
+    return attn_impl(false, false, q_i8, q_scale, k_i8, k_scale, v_f16, nullptr, o_f16, nullptr, 0,
+                     B, H, N, N, D, causal, sm_scale, block_q, block_k, 1, stream);
+}
+
+int sage_attn_cross_fwd(const int8_t* q_i8, const float* q_scale, const int8_t* k_i8, const float* k_scale,
+                        const void* v_f16, void* o_f16, int B, int H, int Nq, int Nkv, int D, int causal,
+                        float sm_scale, int block_q, int block_k, void* stream) {
+    return attn_impl(false, false, q_i8, q_scale, k_i8, k_scale, v_f16, nullptr, o_f16, nullptr, 0,
+                     B, H, Nq, Nkv, D, causal, sm_scale, block_q, block_k, 1, stream);
+}
+
 int sage_attn_cross_split_fwd(const int8_t* q_i8, const float* q_scale, const int8_t* k_i8, const float* k_scale,
                               const void* v_f16, void* o_f16, void* workspace, size_t workspace_bytes,
                               int B, int H, int Nq, int Nkv, int D, int causal, float sm_scale,
                               int block_q, int block_k, int n_splits, void* stream) {
-    if (!q_i8 || !q_scale || !k_i8 || !k_scale || !v_f16 || !o_f16) return SAGE_ERR_NULL;
-    if (int e = check_shape(B, H, Nq, D)) return e;
-    if (int e = check_shape(B, H, Nkv, D)) return e;
-    if (causal && Nq > Nkv) return SAGE_ERR_UNSUPPORTED;
-    if (!quant_block_ok(block_q)) return SAGE_ERR_UNSUPPORTED;
-    if (block_k != 1 && block_k != 64 && block_k != 128) return SAGE_ERR_UNSUPPORTED;
-    if (n_splits < 0) return SAGE_ERR_VALUE;
-    if (!std::isfinite(sm_scale) || !(sm_scale > 0.0f)) return SAGE_ERR_VALUE;
-    const size_t need = sage_attn_split_workspace(B, H, Nq, Nkv, D, causal, n_splits);
-    if (need > 0 && !workspace) return SAGE_ERR_NULL;
-    if (workspace_bytes < need) return SAGE_ERR_WORKSPACE;
-    if (!aligned(q_i8, 16) || !aligned(k_i8, 16) || !aligned(v_f16, 16) || !aligned(o_f16, 16) ||
-        !aligned(q_scale, 4) || !aligned(k_scale, 4) || (need > 0 && !aligned(workspace, 16)))
-        return SAGE_ERR_ALIGN;
-    hipError_t e = sage::launch_attn_split(q_i8, q_scale, k_i8, k_scale, v_f16, o_f16, workspace, B * H, Nq, Nkv, D,
-                                           causal ? 1 : 0, block_q, block_k, n_splits, (hipStream_t)stream);
-    return e == hipSuccess ? SAGE_OK : SAGE_ERR_LAUNCH;
+    return attn_impl(false, true, q_i8, q_scale, k_i8, k_scale, v_f16, nullptr, o_f16, workspace, workspace_bytes,
+                     B, H, Nq, Nkv, D, causal, sm_scale, block_q, block_k, n_splits, stream);
+}
+
+int sage_attn_pv_int8_fwd(const int8_t* q_i8, const float* q_scale, const int8_t* k_i8, const float* k_scale,
+                          const int8_t* v_i8t, const float* v_scale, void* o_f16,
+                          int B, int H, int N, int D, int causal, float sm_scale,
+                          int block_q, int block_k, void* stream) {
+    return attn_impl(true, false, q_i8, q_scale, k_i8, k_scale, v_i8t, v_scale, o_f16, nullptr, 0,
+                     B, H, N, N, D, causal, sm_scale, block_q, block_k, 1, stream);
+}
+
+int sage_attn_pv_int8_cross_fwd(const int8_t* q_i8, const float* q_scale, const int8_t* k_i8, const float* k_scale,
+                                const int8_t* v_i8t, const float* v_scale, void* o_f16,
+                                int B, int H, int Nq, int Nkv, int D, int causal, float sm_scale,
+                                int block_q, int block_k, void* stream) {
+    return attn_impl(true, false, q_i8, q_scale, k_i8, k_scale, v_i8t, v_scale, o_f16, nullptr, 0,
+                     B, H, Nq, Nkv, D, causal, sm_scale, block_q, block_k, 1, stream);
 }
 
 int sage_attn_pv_int8_cross_split_fwd(const int8_t* q_i8, const float* q_scale, const int8_t* k_i8, const float* k_scale,
@@ -176,23 +197,8 @@ int sage_attn_pv_int8_cross_split_fwd(const int8_t* q_i8, const float* q_scale, 
                                       void* workspace, size_t workspace_bytes,
                                       int B, int H, int Nq, int Nkv, int D, int causal, float sm_scale,
                                       int block_q, int block_k, int n_splits, void* stream) {
-    if (!q_i8 || !q_scale || !k_i8 || !k_scale || !v_i8t || !v_scale || !o_f16) return SAGE_ERR_NULL;
-    if (int e = check_shape(B, H, Nq, D)) return e;
-    if (int e = check_shape(B, H, Nkv, D)) return e;
-    if (causal && Nq > Nkv) return SAGE_ERR_UNSUPPORTED;
-    if (!quant_block_ok(block_q)) return SAGE_ERR_UNSUPPORTED;
-    if (block_k != 1 && block_k != 64 && block_k != 128) return SAGE_ERR_UNSUPPORTED;
-    if (n_splits < 0) return SAGE_ERR_VALUE;
-    if (!std::isfinite(sm_scale) || !(sm_scale > 0.0f)) return SAGE_ERR_VALUE;
-    const size_t need = sage_attn_split_workspace(B, H, Nq, Nkv, D, causal, n_splits);
-    if (need > 0 && !workspace) return SAGE_ERR_NULL;
-    if (workspace_bytes < need) return SAGE_ERR_WORKSPACE;
-    if (!aligned(q_i8, 16) || !aligned(k_i8, 16) || !aligned(v_i8t, 16) || !aligned(o_f16, 16) ||
-        !aligned(q_scale, 4) || !aligned(k_scale, 4) || !aligned(v_scale, 16) || (need > 0 && !aligned(workspace, 16)))
-        return SAGE_ERR_ALIGN;
-    hipError_t e = sage::launch_attn_pv8_split(q_i8, q_scale, k_i8, k_scale, v_i8t, v_scale, o_f16, workspace, B * H, Nq, Nkv,
-                                               D, causal ? 1 : 0, block_q, block_k, n_splits, (hipStream_t)stream);
-    return e == hipSuccess ? SAGE_OK : SAGE_ERR_LAUNCH;
+    return attn_impl(true, true, q_i8, q_scale, k_i8, k_scale, v_i8t, v_scale, o_f16, workspace, workspace_bytes,
+                     B, H, Nq, Nkv, D, causal, sm_scale, block_q, block_k, n_splits, stream);
 }
 
 size_t sage_quant_v_workspace(int B, int H, int N, int D) {
@@ -211,42 +217,6 @@ int sage_quant_v(const void* v_f16, int8_t* v_i8t, float* v_scale, void* workspa
     if (!aligned(v_f16, 16) || !aligned(v_i8t, 16) || !aligned(v_scale, 16) || !aligned(workspace, 4))
         return SAGE_ERR_ALIGN;
     hipError_t e = sage::launch_quant_v(v_f16, v_i8t, v_scale, (unsigned*)workspace, B * H, N, D, (hipStream_t)stream);
-    return e == hipSuccess ? SAGE_OK : SAGE_ERR_LAUNCH;
-}
-
-int sage_attn_pv_int8_fwd(const int8_t* q_i8, const float* q_scale, const int8_t* k_i8, const float* k_scale,
-                          const int8_t* v_i8t, const float* v_scale, void* o_f16,
-                          int B, int H, int N, int D, int causal, float sm_scale,
-                          int block_q, int block_k, void* stream) {
-    if (!q_i8 || !q_scale || !k_i8 || !k_scale || !v_i8t || !v_scale || !o_f16) return SAGE_ERR_NULL;
-    if (int e = check_shape(B, H, N, D)) return e;
-    if (!quant_block_ok(block_q)) return SAGE_ERR_UNSUPPORTED;
-    if (block_k != 1 && block_k != 64 && block_k != 128) return SAGE_ERR_UNSUPPORTED;
-    if (!std::isfinite(sm_scale) || !(sm_scale > 0.0f)) return SAGE_ERR_VALUE;
-    if (!aligned(q_i8, 16) || !aligned(k_i8, 16) || !aligned(v_i8t, 16) || !aligned(o_f16, 16) ||
-        !aligned(q_scale, 4) || !aligned(k_scale, 4) || !aligned(v_scale, 16))
-        return SAGE_ERR_ALIGN;
-    hipError_t e = sage::launch_attn_pv8(q_i8, q_scale, k_i8, k_scale, v_i8t, v_scale, o_f16, B * H, N, N, D,
-                                         causal ? 1 : 0, block_q, block_k, (hipStream_t)stream);
-    return e == hipSuccess ? SAGE_OK : SAGE_ERR_LAUNCH;
-}
-
-int sage_attn_pv_int8_cross_fwd(const int8_t* q_i8, const float* q_scale, const int8_t* k_i8, const float* k_scale,
-                                const int8_t* v_i8t, const float* v_scale, void* o_f16,
-                                int B, int H, int Nq, int Nkv, int D, int causal, float sm_scale,
-                                int block_q, int block_k, void* stream) {
-    if (!q_i8 || !q_scale || !k_i8 || !k_scale || !v_i8t || !v_scale || !o_f16) return SAGE_ERR_NULL;
-    if (int e = check_shape(B, H, Nq, D)) return e;
-    if (int e = check_shape(B, H, Nkv, D)) return e;
-    if (causal && Nq > Nkv) return SAGE_ERR_UNSUPPORTED;
-    if (!quant_block_ok(block_q)) return SAGE_ERR_UNSUPPORTED;
-    if (block_k != 1 && block_k != 64 && block_k != 128) return SAGE_ERR_UNSUPPORTED;
-    if (!std::isfinite(sm_scale) || !(sm_scale > 0.0f)) return SAGE_ERR_VALUE;
-    if (!aligned(q_i8, 16) || !aligned(k_i8, 16) || !aligned(v_i8t, 16) || !aligned(o_f16, 16) ||
-        !aligned(q_scale, 4) || !aligned(k_scale, 4) || !aligned(v_scale, 16))
-        return SAGE_ERR_ALIGN;
-    hipError_t e = sage::launch_attn_pv8(q_i8, q_scale, k_i8, k_scale, v_i8t, v_scale, o_f16, B * H, Nq, Nkv, D,
-                                         causal ? 1 : 0, block_q, block_k, (hipStream_t)stream);
     return e == hipSuccess ? SAGE_OK : SAGE_ERR_LAUNCH;
 }
 
