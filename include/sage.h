@@ -204,7 +204,8 @@ int sage_attn_cross_fwd(const int8_t* q_i8, const float* q_scale,
  *   workspace  device, >= sage_attn_split_workspace() bytes (same arguments), 16-byte aligned;
  *              scratch, contents undefined on entry and exit; may be NULL when that size is 0
  * sage_attn_split_count returns 0 for arguments the call would reject.
- * Everything else as sage_attn_cross_fwd; SAGE_ERR_VALUE for n_splits < 0.
+ * Everything else as sage_attn_cross_fwd; SAGE_ERR_VALUE for n_splits < 0, SAGE_ERR_SHAPE if B * H * chunks
+ * exceeds 2^30.
  */
 int sage_attn_split_count(int B, int H, int Nq, int Nkv, int causal, int n_splits);
 size_t sage_attn_split_workspace(int B, int H, int Nq, int Nkv, int D, int causal, int n_splits);

@@ -118,6 +118,8 @@ int attn_impl(bool pv_int8, bool split, const int8_t* q_i8, const float* q_scale
     if (block_k != 1 && block_k != 64 && block_k != 128) return SAGE_ERR_UNSUPPORTED;
     if (split && n_splits < 0) return SAGE_ERR_VALUE;
     if (!std::isfinite(sm_scale) || !(sm_scale > 0.0f)) return SAGE_ERR_VALUE;
+    // (slab, chunk) pairs are counted in an int by the kernels
+    if (split && (long long)B * H * sage_attn_split_count(B, H, Nq, Nkv, causal, n_splits) > (1ll << 30)) return SAGE_ERR_SHAPE;
     const size_t need = split ? sage_attn_split_workspace(B, H, Nq, Nkv, D, causal, n_splits) : 0;
     if (need > 0 && !workspace) return SAGE_ERR_NULL;
     if (workspace_bytes < need) return SAGE_ERR_WORKSPACE;

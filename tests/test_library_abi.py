@@ -135,6 +135,8 @@ def test_split_call_validates_and_its_chunk_plan_keeps_its_promises(lib):
     assert lib.sage_attn_pv_int8_cross_split_fwd(*head8, good, sz(64), 1, 1, 4, 4096, 64, 1, f(0.125), 128, 64, 4, None) == 4
     assert lib.sage_attn_pv_int8_cross_split_fwd(*head8, good, sz(1 << 30), 1, 1, 4, 4096, 64, 1, f(0.125), 128, 64, -1, None) == 7
     assert lib.sage_attn_pv_int8_cross_split_fwd(*head8, good, sz(1 << 30), 1, 1, 4097, 4096, 64, 1, f(0.125), 128, 64, 4, None) == 3
+    # 65535 slabs x 32768 chunks of 128 keys: more (slab, chunk) pairs than the kernels count
+    assert lib.sage_attn_cross_split_fwd(*head, good, sz(1 << 62), 255, 257, 1, 1 << 22, 64, 0, f(0.125), 128, 64, 1 << 15, None) == 2
     assert lib.sage_attn_split_count(1, 1, 4097, 4096, 1, 4) == 0
     assert lib.sage_attn_split_count(1, 1, 4, 4096, 1, 1) == 1 and lib.sage_attn_split_workspace(1, 1, 4, 4096, 64, 1, 1) == 0
     assert lib.sage_attn_split_workspace(2, 3, 4, 4096, 64, 1, 4) == 4 * 2 * 3 * 4 * (2 * 64 + 4)
