@@ -83,7 +83,7 @@ size_t sage_smooth_quant_k_workspace(int B, int H, int N, int D);
  *   k_f16   in  [B,H,N,D] fp16
  *   k_i8    out [B,H,N,D] int8
  *   k_scale out [B,H,ceil(N/block_k)] fp32 (delta_K)
- *   k_mean  out [B,H,D] fp32 (required)
+ *   k_mean  out [B,H,D] fp32, or NULL if the caller does not want the mean
  *   workspace   device scratch of at least sage_smooth_quant_k_workspace() bytes, 8-byte aligned;
  *               contents on entry are ignored, contents on return are unspecified.  Two calls
  *               that share a workspace must be ordered on the same stream.

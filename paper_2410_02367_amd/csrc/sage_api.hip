@@ -56,7 +56,7 @@ int quant_q_impl(const void* q_f16, const float* cs, const float* sn, bool rope,
 int smooth_quant_k_impl(const void* k_f16, const float* cs, const float* sn, bool rope, int8_t* k_i8,
                         float* k_scale, float* k_mean, void* workspace, size_t workspace_bytes,
                         int B, int H, int N, int D, int block_k, void* stream) {
-    if (!k_f16 || !k_i8 || !k_scale || !k_mean || !workspace || (rope && (!cs || !sn))) return SAGE_ERR_NULL;
+    if (!k_f16 || !k_i8 || !k_scale || !workspace || (rope && (!cs || !sn))) return SAGE_ERR_NULL;      // k_mean is optional
     if (int e = check_shape(B, H, N, D)) return e;
     if (!quant_block_ok(block_k)) return SAGE_ERR_UNSUPPORTED;
     if (workspace_bytes < sage_smooth_quant_k_workspace(B, H, N, D)) return SAGE_ERR_WORKSPACE;

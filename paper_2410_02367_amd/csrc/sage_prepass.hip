@@ -139,7 +139,7 @@ __global__ void __launch_bounds__(NT) quant_block_kernel(const _Float16* __restr
             double avg = (double)s / (double)N;
             float m = (float)(avg * 0x1p-24);
             s_mean[t] = m;
-            if (g == 0) k_mean[(size_t)bh * D + t] = m;
+            if (g == 0 && k_mean != nullptr) k_mean[(size_t)bh * D + t] = m;
         }
         __syncthreads();
 #pragma unroll
@@ -213,7 +213,7 @@ __global__ void __launch_bounds__(256) quant_token_kernel(const _Float16* __rest
             double avg = (double)s / (double)N;
             float m = (float)(avg * 0x1p-24);
             s_mean[t] = m;
-            if (blockIdx.x == 0) k_mean[(size_t)bh * D + t] = m;
+            if (blockIdx.x == 0 && k_mean != nullptr) k_mean[(size_t)bh * D + t] = m;
         }
         __syncthreads();
 #pragma unroll
@@ -311,7 +311,7 @@ __global__ void __launch_bounds__(256) k_small_kernel(const _Float16* __restrict
         const double avg = (double)sum / (double)N;
         const float m = (float)(avg * 0x1p-24);
         s_mean[t] = m;
-        k_mean[(size_t)bh * D + t] = m;
+        if (k_mean != nullptr) k_mean[(size_t)bh * D + t] = m;
     }
     __syncthreads();
     float mean[8];

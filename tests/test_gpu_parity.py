@@ -145,3 +145,27 @@ def test_host_side_errors_leave_no_side_effects():
         sage.sage_smooth_quant_k(q, 64, workspace=ws)
     assert e.value.status == 4
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("N,block_k", [(300, 64), (3000, 64), (3000, 1)])
+def test_k_mean_output_is_optional(N, block_k):
+    """sage_smooth_quant_k with k_mean = NULL (straight through the C ABI): same codes and scales as with it,
+    on the single-launch path for short sequences and on the three-launch path."""
+    import ctypes
+    w = si.custom("nomean", 2, 2, N, 128, False, seed=si.BASE_SEED + 60 + N)
+    _, k, _ = si.full(w)
+    kd = to_dev(k)
+    k_i8, k_scale, k_mean = sage.sage_smooth_quant_k(kd, block_k)
+    lib = sage.load()
+    B, H, D = w.B, w.H, w.D
+    k_i8_b = torch.full_like(k_i8, 5)
+    k_scale_b = torch.full_like(k_scale, -1.0)
+    ws = torch.empty(max(lib.sage_smooth_quant_k_workspace(B, H, N, D), 16), dtype=torch.uint8, device="cuda")
+    st = lib.sage_smooth_quant_k(ctypes.c_void_p(kd.data_ptr()), ctypes.c_void_p(k_i8_b.data_ptr()),
+                                 ctypes.c_void_p(k_scale_b.data_ptr()), None, ctypes.c_void_p(ws.data_ptr()), ws.numel(),
+                                 B, H, N, D, block_k, ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+    torch.cuda.synchronize()
+    assert st == 0
+    assert torch.equal(k_i8, k_i8_b) and torch.equal(k_scale.view(torch.int32), k_scale_b.view(torch.int32))
+    kq, ks, km = oracle.smooth_quant_k(k, block_k)
+    assert np.array_equal(k_i8_b.cpu().numpy(), kq) and np.array_equal(bits(k_mean.cpu().numpy()), bits(km))
