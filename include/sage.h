@@ -13,6 +13,9 @@
  * table of kernels.  The two sides are independent: any block_q goes with any block_k.
  * sage_quant_v and sage_attn_pv_int8_fwd are the same loop with Section 4.3's INT8 second product
  * (the -vB / -vT kernels of that table); sage_rope_* fuse RoPE into the two pre-pass calls.
+ * The *_cross_fwd calls take different numbers of queries and keys, and the *_cross_split_fwd calls
+ * cut the keys into chunks that run as separate workgroups (few queries against many keys); neither
+ * is in the paper, which states everything for equal lengths.
  *
  * Conventions shared by every call
  *   - All pointers are DEVICE pointers (HIP global memory) unless stated; the library never
