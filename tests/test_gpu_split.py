@@ -26,6 +26,8 @@ CASES = [
     ("per_token_scales_d64", 1, 3, 33, 1100, 64, False, 1, 1, 3, 3),
     ("cross_attention_nc", 1, 2, 200, 1000, 128, False, 128, 64, 8, 8),
     ("last_chunk_one_key", 1, 2, 3, 1025, 64, False, 128, 64, 8, 5),
+    ("per_token_decode", 1, 2, 9, 1500, 128, True, 1, 1, 4, 4),
+    ("per_token_decode_d64", 2, 2, 32, 1100, 64, False, 1, 1, 3, 3),
 ]
 
 
