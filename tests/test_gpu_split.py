@@ -215,3 +215,48 @@ def test_convenience_wrapper_routes_by_lengths_and_second_product():
     assert sage.sage_attn_split_count(1, 4, 7, 4000, True, 0) > 1
     for x, y in ((a, b), (a8, b8), (c, d), (c8, d8)):
         assert torch.equal(x.view(torch.int16), y.view(torch.int16))
+
+
+# ------------------------------------------------------------------ seeded sweep of split shapes
+
+SPLIT_GRANULARITIES = [(128, 64), (64, 64), (32, 128), (1, 1), (1, 64), (128, 1)]
+
+
+def sweep_cases(n=16, seed=20241003):
+    g = np.random.default_rng(seed)
+    out = []
+    for i in range(n):
+        Nkv = int(g.choice([257, 640, 1023, 1025, 1409, 2048, 2500, 3333]))
+        causal = bool(g.integers(0, 2))
+        Nq = int(g.choice([1, 2, 31, 33, 64, 129, 200]))
+        if causal:
+            Nq = min(Nq, Nkv)
+        bq, bk = SPLIT_GRANULARITIES[int(g.integers(0, len(SPLIT_GRANULARITIES)))]
+        out.append((i, int(g.integers(1, 3)), int(g.integers(1, 4)), Nq, Nkv, int(g.choice([64, 128])), causal, bq, bk,
+                    int(g.integers(2, 12))))
+    return out
+
+
+@pytest.mark.parametrize("i,B,H,Nq,Nkv,D,causal,bq,bk,req", sweep_cases(),
+                         ids=lambda v: str(int(v)) if isinstance(v, (bool, int)) else None)
+def test_random_split_shape(i, B, H, Nq, Nkv, D, causal, bq, bk, req):
+    n = sage.sage_attn_split_count(B, H, Nq, Nkv, causal, req)
+    print(f"[case] split sweep {i}: B{B} H{H} Nq{Nq} Nkv{Nkv} D{D} causal={causal} scales {bq}x{bk} chunks {req}->{n}", flush=True)
+    q, k, v, sm = make(f"sweep{i}", B, H, Nq, Nkv, D, 100 + i)
+    k_i8, k_scale, _ = sage.sage_smooth_quant_k(to_dev(k), bk)
+    q_i8, q_scale = sage.sage_quant_q(to_dev(q), sm, bq)
+    v_i8t, v_scale = sage.sage_quant_v(to_dev(v))
+    o = sage.sage_attn_cross_split_fwd(q_i8, q_scale, k_i8, k_scale, to_dev(v), causal, sm, bq, bk, n_splits=req)
+    o8 = sage.sage_attn_pv_int8_cross_split_fwd(q_i8, q_scale, k_i8, k_scale, v_i8t, v_scale, causal, sm, bq, bk, n_splits=req)
+    torch.cuda.synchronize()
+    kq, ks, _ = oracle.smooth_quant_k(k, bk)
+    qq, qs = oracle.quant_q(q, sm, bq)
+    vq, vs = oracle.quant_v(v)
+    assert np.array_equal(k_i8.cpu().numpy(), kq) and np.array_equal(q_i8.cpu().numpy(), qq)
+    lq, lk = (128, 64) if bq == 1 else (max(bq, 64), max(bk, 64) if bk != 1 else 64)
+    o_ref = oracle.attn_l2_cross(qq, qs, kq, ks, v, causal, lq, lk, gran_q=bq, gran_k=bk)
+    assert_output_close(o.cpu().numpy(), o_ref, f"split sweep {i}")
+    starts = chunk_starts(B, H, Nq, Nkv, causal, req)
+    o8_ref, big_l = oracle.attn_pv8_cross_split(qq, qs, kq, ks, vq, vs, causal, 128, 64, starts, gran_q=bq, gran_k=bk,
+                                                return_l=True)
+    assert_pv8_close(o8.cpu().numpy(), o8_ref, big_l, vs, f"split sweep {i} INT8 PV")
