@@ -1005,8 +1005,8 @@ hipError_t launch_attn(const int8_t* qq, const float* qscale, const int8_t* kq, 
 SplitPlan plan_split(int BH, int Nq, int N, int causal, int requested) {
     if (requested <= 0) {
         // One 128-row workgroup per CU (measured: 256 to 512 workgroups are the fastest at every
-        // shape tried, more lose to the fixed cost per workgroup and to the longer merge); chunks of
-        // at least 8 key tiles.
+        // shape tried; the launch is memory-bound from there on, and more chunks only add partial
+        // results to write and merge); chunks of at least 8 key tiles.
         const long wg = (long)BH * ((Nq + 127) / 128);
         long want = (256 + wg - 1) / wg;
         const long most = N / 512 < 64 ? N / 512 : 64;
@@ -1014,8 +1014,9 @@ SplitPlan plan_split(int BH, int Nq, int N, int causal, int requested) {
     }
     if (requested <= 1) return {1, 0, nullptr};
     // Every chunk but the last has `chunk` keys, a multiple of the 64-key tile and of the largest K
-    // block (128); the last takes the rest.  It starts at or before key N - Nq when causal (N - 1 otherwise), so
-    // that every row sees at least one key of every chunk and no partial result is empty.
+    // block (128); the last takes the rest.  It starts at or before key N - Nq when causal (N - 1
+    // otherwise), so that every row sees at least one key of every chunk and no partial result is
+    // empty (the merge relies on it: every lse is finite).
     const int chunk = 128 * ((N + 128 * requested - 1) / (128 * requested));
     const int limit = causal ? N - Nq : N - 1;
     const int fit = limit / chunk + 1;
