@@ -27,11 +27,80 @@ INT8_PEAK_TOPS = 5000.0      # MI355X dense INT8 MFMA, published
 FP16_PEAK_TFLOPS = 2500.0    # MI355X dense FP16 MFMA, published
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 
-# HBM bytes per attention launch from the hardware counters (FETCH_SIZE and WRITE_SIZE, one profiler
-# run each, scaled by what the same counter reads for a 1 GiB copy kernel); the profiler cannot run
-# inside this script, so the figure of the committed summary under profiles/ is carried here.
-ATTN_TRAFFIC_BYTES = {"cfg3_prefill16k": 511.0e6}
-ATTN_TRAFFIC_BYTES_INT8_PV = {"cfg3_prefill16k": 444.4e6}
+
+
+def profiled_traffic(workload: str, pv_int8: bool):
+    """HBM bytes per attention launch from the hardware counters (FETCH_SIZE and WRITE_SIZE, one profiler
+    run each, scaled by what the same counter reads for a 1 GiB copy kernel).  The profiler cannot run
+    inside this script, so the figure is read from the committed summary of that run under profiles/
+    (its line "traffic_bytes_per_launch = ..."); None when there is no summary for the workload."""
+    import re
+    name = f"hotpath_{workload}{'_int8_pv' if pv_int8 else ''}_hbm_traffic.txt"
+    path = os.path.join(ROOT, "profiles", name)
+    if not os.path.exists(path):
+        return None
+    m = re.search(r"^traffic_bytes_per_launch\s*=\s*([0-9.eE+]+)", open(path).read(), re.M)
+    return float(m.group(1)) if m else None
+
+
+# Probes of sage_microbench (include/sage.h): operations per instruction group
+PROBE_OPS = {0: 8 * 65536.0, 1: 8 * 32768.0, 2: 8 * 65536.0 + 16 * 32768.0, 4: 8 * 32768.0, 5: 8 * 32768.0,
+             6: 8 * 65536.0 + 16 * 32768.0}
+PROBE_NAMES = {0: "INT8 32x32x32 stream", 1: "FP16 32x32x16 stream", 2: "attention mix: 8 INT8 + 16 FP16, matrix only",
+               3: "softmax chunks only (24 per group)", 4: "FP16 matrix instruction + softmax chunk, one stream",
+               5: "FP16 matrix stream and softmax stream on separate wavefronts of a SIMD",
+               6: "attention step: 8 INT8 + 16 FP16 + 16 chunks + 8 maxima, one stream"}
+# matrix-pipe clocks per group (32 per 32x32 instruction) -- what a fully busy pipe needs
+PROBE_PIPE_CLOCKS = {0: 256, 1: 256, 2: 768, 4: 256, 5: 256, 6: 768}
+
+
+def run_probe(sage, torch, data, kind, waves, seconds, workgroups=1024):
+    """One probe launch sized to last about `seconds`; returns (ms, TOPS or None, mean shader-clock ticks per
+    group, implied clock in GHz from the two in-kernel counters)."""
+    def launch(iters):
+        out = torch.zeros((workgroups * 4 * waves, 4), dtype=torch.int64, device="cuda")
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        sage.sage_microbench(kind, waves, workgroups, iters, data, out)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1), out
+    ms, _ = launch(200)
+    iters = int(max(200, min(2.0e8, 200 * seconds * 1e3 / max(ms, 1e-3))))
+    launch(iters)                      # warm
+    ms, out = launch(iters)
+    o = out.cpu().numpy().astype(np.float64)
+    wavefronts = workgroups * 4 * waves
+    matrix_waves = wavefronts // 2 if kind == 5 else wavefronts
+    tops = PROBE_OPS[kind] * iters * matrix_waves / (ms * 1e-3) / 1e12 if kind in PROBE_OPS else None
+    ticks = float(o[:, 0].mean()) / iters
+    # the constant-rate counter runs at 100 MHz
+    ghz = float((o[:, 0] / np.maximum(o[:, 1], 1.0)).mean()) * 0.1
+    return ms, tops, ticks, ghz, iters
+
+
+def microbench(seconds: float):
+    """What the matrix pipe of this chip sustains with the attention kernel's own instructions (table on
+    stdout; not part of the one-line benchmark contract).  1024 workgroups = 4 per compute unit at one
+    wavefront per SIMD each, i.e. every SIMD holds 4 (or 8) probe wavefronts."""
+    import torch
+
+    import paper_2410_02367_amd as sage
+
+    torch.cuda.set_device(0)
+    g = torch.Generator(device="cuda").manual_seed(20241002)
+    data = torch.randint(-2 ** 31, 2 ** 31 - 1, (1024,), generator=g, device="cuda", dtype=torch.int64).to(torch.int32)
+    print(f"instruction-stream probes, about {seconds:g} s per launch, random operand bits; "
+          f"nominal peaks: INT8 {INT8_PEAK_TOPS:.0f} TOPS, FP16 {FP16_PEAK_TFLOPS:.0f} TFLOP/s at 2.4 GHz")
+    print("%-4s %-78s %5s %9s %9s %8s %10s %9s %8s" % ("kind", "probe", "waves", "ms", "TOPS", "% peak", "ticks/grp", "pipe busy", "GHz"))
+    for kind, waves in ((0, 1), (0, 2), (1, 1), (1, 2), (2, 1), (2, 2), (3, 1), (3, 2), (4, 1), (4, 2), (5, 2), (6, 1), (6, 2)):
+        # 256 workgroups: one per compute unit, `waves` wavefronts per SIMD
+        ms, tops, ticks, ghz, iters = run_probe(sage, torch, data, kind, waves, seconds, workgroups=256)
+        peak = {0: INT8_PEAK_TOPS, 1: FP16_PEAK_TFLOPS, 4: FP16_PEAK_TFLOPS, 5: FP16_PEAK_TFLOPS}.get(kind, INT8_PEAK_TOPS)
+        busy = PROBE_PIPE_CLOCKS[kind] * (1 if kind == 5 else waves) / ticks if kind in PROBE_PIPE_CLOCKS else float("nan")
+        print("%-4d %-78s %5d %9.2f %9s %8s %10.1f %9.3f %8.3f" % (
+            kind, PROBE_NAMES[kind], waves, ms, "%.0f" % tops if tops else "-",
+            "%.1f" % (100.0 * tops / peak) if tops else "-", ticks, busy, ghz), flush=True)
 
 
 def cpu_baseline(w, seconds_budget=20.0, per_token=False, gpu_out_head0=None, pv_int8=False):
@@ -244,6 +313,13 @@ def main():
                          "last Nq tokens of the workload as queries against all of its keys; comma-separated list of Nq")
     ap.add_argument("--rotate", type=int, default=1,
                     help="number of distinct input allocations used in turn (1 = every step reads the same buffers)")
+    ap.add_argument("--microbench", type=float, nargs="?", const=0.05, default=None, metavar="SECONDS",
+                    help="instead of the benchmark line, print what the matrix pipe sustains with the attention "
+                         "kernel's instructions (pure INT8 / FP16 streams, the attention mix, with and without the "
+                         "softmax arithmetic), each probe launch lasting about SECONDS (default 0.05)")
+    ap.add_argument("--sustain", type=float, default=1.0,
+                    help="after the timed steps, keep stepping for this many seconds and report that rate as well "
+                         "(extra key 'sustained'; 0 = skip)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one plain elementwise copy kernel of 1 GiB before the warm-up, so that a "
                          "hardware-counter run holds a kernel of known HBM traffic beside the library's kernels")
@@ -264,6 +340,9 @@ def main():
     if args.rotate < 1 or (args.graph and args.rotate > 1):
         print("bench.py: --rotate must be >= 1, and 1 with --graph (a captured step reads fixed buffers)", file=sys.stderr)
         sys.exit(2)
+    if args.microbench is not None:
+        microbench(args.microbench)
+        return
     if args.sweep:
         sweep(args.scales == "token", args.pv == "int8")
         return
@@ -368,6 +447,28 @@ def main():
     pre_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / args.steps
     assert bool(torch.isfinite(out[0, 0, :64].float()).all())
 
+    # the same steps for about --sustain seconds: what the chip holds once clocks and power have settled
+    sustained = None
+    if args.sustain > 0 and not args.graph:
+        n_sus = int(max(args.steps, min(20000, args.sustain * 1e3 / ms_per_step)))
+        ts0 = time.perf_counter()
+        for _ in range(n_sus):
+            step()
+        torch.cuda.synchronize()
+        ts1 = time.perf_counter()
+        sus_ms = (ts1 - ts0) * 1e3 / n_sus
+        sustained = {"steps": n_sus, "seconds": ts1 - ts0, "ms_per_step": sus_ms,
+                     "value": w.ops / (sus_ms * 1e-3) / 1e12, "unit": "TOPS"}
+
+    # what the matrix pipe sustains with this kernel's own instructions, measured now on this GPU:
+    # the pure INT8 stream (the peak `frac` is quoted against, as measured) and the kernel's instruction
+    # mix without anything else (the ceiling of this algorithm on this chip)
+    g = torch.Generator(device="cuda").manual_seed(20241002)
+    probe_data = torch.randint(-2 ** 31, 2 ** 31 - 1, (1024,), generator=g, device="cuda", dtype=torch.int64).to(torch.int32)
+    _, int8_measured, _, int8_ghz, _ = run_probe(sage, torch, probe_data, 0, 2, 0.05, workgroups=256)
+    mix_kind = 0 if pv_int8 else 2
+    _, mix_measured, _, mix_ghz, _ = run_probe(sage, torch, probe_data, mix_kind, 2, 0.05, workgroups=256)
+
     ops = w.ops
     value = ops / (ms_per_step * 1e-3) / 1e12
     attn_tops = ops / (attn_ms * 1e-3) / 1e12
@@ -399,9 +500,16 @@ def main():
             "bound": "mfma",
             "achieved": attn_tops,
             "peak": INT8_PEAK_TOPS,
-            "unit": "TFLOP/s",
+            "unit": "TOPS",
             "frac": attn_tops / INT8_PEAK_TOPS,
-            "traffic": None if per_token else (ATTN_TRAFFIC_BYTES_INT8_PV if pv_int8 else ATTN_TRAFFIC_BYTES).get(w.name),
+            "frac_of_measured_peak": attn_tops / int8_measured,
+            "frac_of_blended_ceiling": attn_tops / (INT8_PEAK_TOPS if pv_int8 else INT8_PEAK_TOPS * 2 / 3),
+            "frac_of_measured_ceiling": attn_tops / mix_measured,
+            "measured": {"int8_stream_tops": int8_measured, "int8_stream_ghz": int8_ghz,
+                         "kernel_mix_stream_tops": mix_measured, "kernel_mix_stream_ghz": mix_ghz,
+                         "how": "sage_microbench kinds 0 and " + str(mix_kind) + ", 2 wavefronts per SIMD on every SIMD, "
+                                "about 50 ms each, run after the timed steps (see profiles/mfma_peak_microbench.txt)"},
+            "traffic": None if per_token else profiled_traffic(w.name, pv_int8),
             "traffic_unit": "bytes per launch (algorithmic: %.1f MB)" % ((5.0 if pv_int8 else 6.0) * B * H * N * D / 1e6),
             "kernel": "sage_attn_pv8_kernel" if pv_int8 else "sage_attn_kernel",
             "note": ("achieved = counted ops (all INT8) / mean attention-kernel time from HIP events on the launch "
@@ -425,6 +533,8 @@ def main():
         },
         "paper_context": "paper reports ~2.1x over FlashAttention2 and ~2.7x over xformers on RTX4090 (340 TOPS, 52% of its INT8 peak)",
     }
+    if sustained is not None:
+        result["sustained"] = sustained
     if not args.no_cpu_baseline and not args.rope:      # the oracle leg times the headline path only
         del qd, kd, vd
         result["cpu_baseline"] = cpu_baseline(w, per_token=per_token, gpu_out_head0=out[0, 0].cpu().numpy(), pv_int8=pv_int8)

@@ -26,7 +26,8 @@
  *   - The caller owns every buffer.  Outputs are fully overwritten, inputs are never written.
  *   - Tensor pointers must be 16-byte aligned, scale/mean pointers 4-byte aligned.
  *   - Inputs must be finite.  N is any positive value up to 2^23 (it need not be a multiple of a
- *     block size: the last block is short).  D is 64 or 128.
+ *     block size: the last block is short).  D is 64 or 128.  B * H (the number of (batch, head)
+ *     slabs) is at most 65535; more is SAGE_ERR_SHAPE.
  *   - Return value: SAGE_OK or an error code below.  Arguments are validated on the host before
  *     anything is launched, so a failing call has no device side effects.  Nothing throws or aborts.
  *
@@ -54,7 +55,7 @@ extern "C" {
 enum {
     SAGE_OK = 0,
     SAGE_ERR_NULL = 1,        /* a required pointer is NULL                                    */
-    SAGE_ERR_SHAPE = 2,       /* B, H, N or D <= 0, N > 2^23, or B*H*N*D overflows             */
+    SAGE_ERR_SHAPE = 2,       /* B, H, N or D <= 0, N > 2^23, B*H > 65535, or B*H*N*D overflows */
     SAGE_ERR_UNSUPPORTED = 3, /* D not in {64,128} or a block size the kernels do not cover    */
     SAGE_ERR_WORKSPACE = 4,   /* workspace_bytes smaller than the call's *_workspace() size   */
     SAGE_ERR_ALIGN = 5,       /* a pointer is not aligned as required                          */
@@ -64,6 +65,19 @@ enum {
 
 /* Human-readable name of a status code (host pointer to a static string; never NULL). */
 const char* sage_status_string(int status);
+
+/*
+ * Build identity: the SHA-256 (64 hex digits, host pointer to a static string) of the source files
+ * the library was compiled from, so that a caller can refuse a binary that does not belong to the
+ * sources beside it.  "unknown" if the build did not provide it.
+ */
+const char* sage_source_hash(void);
+
+/*
+ * The softmax scale of Section 4.6 when the caller has none of its own: 1 / sqrt(D), the fp32
+ * division of 1 by the fp32 square root (0 for D <= 0).  Host-only helper; nothing is launched.
+ */
+float sage_default_sm_scale(int D);
 
 /*
  * psi_Q(Q * sm_scale): Section 3.2 (per-block quantizer), Section 4.6 (scale folded into Q),
@@ -77,7 +91,11 @@ const char* sage_status_string(int status);
 int sage_quant_q(const void* q_f16, int8_t* q_i8, float* q_scale,
                  int B, int H, int N, int D, float sm_scale, int block_q, void* stream);
 
-/* Bytes of device scratch sage_smooth_quant_k needs for this shape (exact column sums). */
+/*
+ * Bytes of device scratch sage_smooth_quant_k needs for this shape: the exact column sums of K over
+ * chunks of tokens, at most 64 per (batch, head) slab, as 64-bit integers ([B*H, chunks, D]).
+ * 0 for sequences short enough to be handled in one launch (and for arguments the call rejects).
+ */
 size_t sage_smooth_quant_k_workspace(int B, int H, int N, int D);
 
 /*
@@ -89,7 +107,8 @@ size_t sage_smooth_quant_k_workspace(int B, int H, int N, int D);
  *   k_mean  out [B,H,D] fp32, or NULL if the caller does not want the mean
  *   workspace   device scratch of at least sage_smooth_quant_k_workspace() bytes, 8-byte aligned;
  *               contents on entry are ignored, contents on return are unspecified.  Two calls
- *               that share a workspace must be ordered on the same stream.
+ *               that share a workspace must be ordered on the same stream.  May be NULL when that
+ *               size is 0.
  *   block_k     tokens per scale: 1 (per-token quantizer), 32, 64 or 128
  */
 int sage_smooth_quant_k(const void* k_f16, int8_t* k_i8, float* k_scale, float* k_mean,
@@ -249,9 +268,36 @@ int sage_attn_pv_int8_cross_split_fwd(const int8_t* q_i8, const float* q_scale,
  * Test hook: the raw int32 scores S^ = Q^ K^^T (Algorithm 1, the Matmul inside the S update)
  * produced by the same matrix-instruction code path as sage_attn_fwd, without mask.
  *   s_i32   out [B,H,N,N] int32 -- O(N^2) memory: meant for small N or for sub-problems.
+ *   block_q, block_k   as in sage_attn_fwd (validated the same way; the scores themselves do not
+ *                      depend on them: no scale is applied)
+ *   wg_rows   query rows per workgroup: 128 (4 wavefronts) or 256 (8 wavefronts) -- the two shapes
+ *             the attention kernel is built in; 0 leaves the choice to the launcher as sage_attn_fwd
+ *             does.  Other values: SAGE_ERR_UNSUPPORTED.
  */
 int sage_attn_qk_i32_debug(const int8_t* q_i8, const int8_t* k_i8, int32_t* s_i32,
-                           int B, int H, int N, int D, void* stream);
+                           int B, int H, int N, int D, int block_q, int block_k, int wg_rows, void* stream);
+
+/*
+ * Measurement hook: instruction-stream probes of the matrix pipe, for the roofline the attention
+ * kernels are quoted against (Section 5, "Kernel Speed", compares the kernel with the peak of the
+ * GPU's INT8 matrix unit; this gives the rate gfx950 sustains with the same instructions).  One
+ * launch of `workgroups` workgroups of 4 * waves_per_simd wavefronts; every wavefront repeats a fixed
+ * group of instructions `iters` times:
+ *   kind 0  8 INT8 32x32x32 matrix instructions        (8 * 65536 operations per group)
+ *   kind 1  8 FP16 32x32x16 matrix instructions        (8 * 32768)
+ *   kind 2  8 INT8 + 16 FP16: the matrix work of one 32-query x 64-key step of Algorithm 1 at D = 128
+ *   kind 3  24 softmax chunks (2 fma, 2 exp2, 1 FP16 pack each), no matrix instruction
+ *   kind 4  8 x (one FP16 matrix instruction + one chunk) in one instruction stream
+ *   kind 5  wavefronts 0-3 of a workgroup run kind 1's group, wavefronts 4-7 (the same SIMDs) 8 chunks;
+ *           needs waves_per_simd = 2
+ *   kind 6  kind 2's instructions with 16 chunks and 8 three-way maxima spread between them
+ *   data    in  1024 int32 of arbitrary (random) bits: the operands; 16-byte aligned
+ *   out     out 4 uint64 per wavefront ([workgroups * 4 * waves_per_simd][4]): shader-clock ticks of the
+ *           loop, constant-rate-counter ticks of the loop, a checksum, 0
+ * Errors as everywhere; SAGE_ERR_UNSUPPORTED for an unknown kind or waves_per_simd not in {1, 2}.
+ */
+int sage_microbench(int kind, int waves_per_simd, int workgroups, int iters,
+                    const int32_t* data, uint64_t* out, void* stream);
 
 #ifdef __cplusplus
 }

@@ -17,6 +17,8 @@ from .binding import (  # noqa: F401
     sage_attn_qk_i32_debug,
     sage_attn_split_count,
     sage_attn_split_workspace,
+    sage_default_sm_scale,
+    sage_microbench,
     sage_quant_q,
     sage_quant_v,
     sage_quant_v_pitch,
@@ -25,6 +27,7 @@ from .binding import (  # noqa: F401
     sage_rope_smooth_quant_k,
     sage_smooth_quant_k,
     sage_smooth_quant_k_workspace,
+    sage_source_hash,
     sage_status_string,
     sageattn,
 )

@@ -10,13 +10,13 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libsage.so")
 _lib = None
 
-EXPORTS = ("sage_status_string", "sage_quant_q", "sage_smooth_quant_k_workspace",
+EXPORTS = ("sage_status_string", "sage_source_hash", "sage_default_sm_scale", "sage_quant_q", "sage_smooth_quant_k_workspace",
            "sage_smooth_quant_k", "sage_rope_quant_q", "sage_rope_smooth_quant_k",
            "sage_attn_fwd", "sage_attn_qk_i32_debug",
            "sage_quant_v_workspace", "sage_quant_v_pitch", "sage_quant_v", "sage_attn_pv_int8_fwd",
            "sage_attn_cross_fwd", "sage_attn_pv_int8_cross_fwd",
            "sage_attn_split_count", "sage_attn_split_workspace", "sage_attn_cross_split_fwd",
-           "sage_attn_pv_int8_cross_split_fwd")
+           "sage_attn_pv_int8_cross_split_fwd", "sage_microbench")
 
 
 class SageError(RuntimeError):
@@ -30,17 +30,30 @@ def lib_path() -> str:
 
 
 def load() -> ctypes.CDLL:
-    """Load the built library; builds it first only if no built library exists."""
+    """Load the built library.  A library that is missing, or that was built from other sources than
+    the ones beside it (its embedded source hash says so), is rebuilt first where the compiler
+    exists; elsewhere that is an error -- kernels are never run from a stale binary, and there is no
+    other code path to fall back to."""
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(_LIB_PATH):
-        from . import build as _build
+    from . import build as _build
+    if _build.is_stale():
+        if not _build.have_compiler():
+            raise RuntimeError(f"{_LIB_PATH} is missing or was not built from the present sources "
+                               f"(embedded hash {_build.built_hash()}, sources {_build.source_hash()}), "
+                               "and there is no hipcc to rebuild it")
         _build.build()
     lib = ctypes.CDLL(_LIB_PATH)
+    lib.sage_source_hash.restype = ctypes.c_char_p
+    lib.sage_source_hash.argtypes = []
+    if lib.sage_source_hash().decode() != _build.source_hash():
+        raise RuntimeError(f"{_LIB_PATH}: the loaded library reports another source hash than the file holds")
     c_int, c_float, c_void_p, c_size_t = ctypes.c_int, ctypes.c_float, ctypes.c_void_p, ctypes.c_size_t
     lib.sage_status_string.restype = ctypes.c_char_p
     lib.sage_status_string.argtypes = [c_int]
+    lib.sage_default_sm_scale.restype = c_float
+    lib.sage_default_sm_scale.argtypes = [c_int]
     lib.sage_quant_q.restype = c_int
     lib.sage_quant_q.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_float, c_int, c_void_p]
     lib.sage_smooth_quant_k_workspace.restype = c_size_t
@@ -58,7 +71,7 @@ def load() -> ctypes.CDLL:
     lib.sage_attn_fwd.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                   c_int, c_int, c_int, c_int, c_int, c_float, c_int, c_int, c_void_p]
     lib.sage_attn_qk_i32_debug.restype = c_int
-    lib.sage_attn_qk_i32_debug.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_void_p]
+    lib.sage_attn_qk_i32_debug.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int, c_int, c_int, c_void_p]
     lib.sage_attn_cross_fwd.restype = c_int
     lib.sage_attn_cross_fwd.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                         c_int, c_int, c_int, c_int, c_int, c_int, c_float, c_int, c_int, c_void_p]
@@ -81,12 +94,24 @@ def load() -> ctypes.CDLL:
     lib.sage_attn_pv_int8_fwd.restype = c_int
     lib.sage_attn_pv_int8_fwd.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                           c_int, c_int, c_int, c_int, c_int, c_float, c_int, c_int, c_void_p]
+    lib.sage_microbench.restype = c_int
+    lib.sage_microbench.argtypes = [c_int, c_int, c_int, c_int, c_void_p, c_void_p, c_void_p]
     _lib = lib
     return lib
 
 
 def sage_status_string(status: int) -> str:
     return load().sage_status_string(int(status)).decode()
+
+
+def sage_source_hash() -> str:
+    """The hash of the sources the loaded library was built from."""
+    return load().sage_source_hash().decode()
+
+
+def sage_default_sm_scale(D: int) -> float:
+    """1 / sqrt(D) as the fp32 value the library uses when the caller names no softmax scale."""
+    return float(load().sage_default_sm_scale(int(D)))
 
 
 def _stream(stream) -> int:
@@ -366,16 +391,33 @@ def sage_attn_pv_int8_cross_fwd(q_i8, q_scale, k_i8, k_scale, v_i8t, v_scale, ca
     return out
 
 
-def sage_attn_qk_i32_debug(q_i8, k_i8, s_i32=None, stream=None):
-    """Raw int32 scores Q^ K^^T [B,H,N,N] through the attention kernel's MFMA path (test hook)."""
+def sage_attn_qk_i32_debug(q_i8, k_i8, s_i32=None, block_q: int = 128, block_k: int = 64, wg_rows: int = 0, stream=None):
+    """Raw int32 scores Q^ K^^T [B,H,N,N] through the attention kernel's MFMA path (test hook);
+    wg_rows = 128 / 256 names the workgroup shape, 0 leaves it to the launcher."""
     B, H, N, D = q_i8.shape
     if s_i32 is None:
         s_i32 = torch.empty((B, H, N, N), dtype=torch.int32, device=q_i8.device)
     st = load().sage_attn_qk_i32_debug(_dev(q_i8, torch.int8, "q_i8"), _dev(k_i8, torch.int8, "k_i8"),
-                                       _dev(s_i32, torch.int32, "s_i32"), B, H, N, D, _stream(stream))
+                                       _dev(s_i32, torch.int32, "s_i32"), B, H, N, D, int(block_q), int(block_k),
+                                       int(wg_rows), _stream(stream))
     if st != 0:
         raise SageError(st, "sage_attn_qk_i32_debug")
     return s_i32
+
+
+def sage_microbench(kind: int, waves_per_simd: int, workgroups: int, iters: int, data, out=None, stream=None):
+    """One launch of an instruction-stream probe (see include/sage.h) -> out [wavefronts, 4] uint64 as int64:
+    shader-clock ticks, constant-rate ticks, checksum, 0.  data: 1024 int32 of random bits on the device."""
+    waves = workgroups * 4 * waves_per_simd
+    if out is None:
+        out = torch.empty((waves, 4), dtype=torch.int64, device=data.device)
+    if data.numel() < 1024 or out.numel() < 4 * waves:
+        raise ValueError("sage_microbench: data needs 1024 words, out 4 per wavefront")
+    st = load().sage_microbench(int(kind), int(waves_per_simd), int(workgroups), int(iters),
+                                _dev(data, torch.int32, "data"), _dev(out, torch.int64, "out"), _stream(stream))
+    if st != 0:
+        raise SageError(st, "sage_microbench")
+    return out
 
 
 def sageattn(q, k, v, causal: bool = False, sm_scale: float | None = None, block_q: int = 128, block_k: int = 64,
@@ -385,7 +427,7 @@ def sageattn(q, k, v, causal: bool = False, sm_scale: float | None = None, block
     lengths the calls that may split the keys over workgroups (end-aligned causal mask)."""
     D = q.shape[-1]
     if sm_scale is None:
-        sm_scale = float(torch.tensor(1.0, dtype=torch.float32) / torch.sqrt(torch.tensor(float(D), dtype=torch.float32)))
+        sm_scale = sage_default_sm_scale(D)
     k_i8, k_scale, _ = sage_smooth_quant_k(k, block_k)
     q_i8, q_scale = sage_quant_q(q, sm_scale, block_q)
     same = q.shape[2] == k.shape[2]

@@ -8,7 +8,8 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsage.so")
-SOURCES = ["sage_api.hip", "sage_prepass.hip", "sage_prepass_v.hip", "sage_attn.hip", "sage_attn_pv8.hip"]
+SOURCES = ["sage_api.hip", "sage_prepass.hip", "sage_prepass_v.hip", "sage_attn.hip", "sage_attn_pv8.hip",
+           "sage_microbench.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -26,10 +27,49 @@ def hipcc() -> str:
     return "hipcc"
 
 
+HASH_MARKER = b"SAGE_SOURCE_HASH="
+
+
+def source_files() -> list:
+    """Everything the library is compiled from: the kernel sources and headers, and the public header."""
+    names = sorted(f for f in os.listdir(CSRC) if f.endswith((".hip", ".h")))
+    return [os.path.join(CSRC, f) for f in names] + [os.path.join(HERE, "..", "include", "sage.h")]
+
+
+def source_hash() -> str:
+    """SHA-256 over the names and contents of source_files(); compiled into the library, so that a
+    built library can be matched against the sources beside it whatever the file times say."""
+    import hashlib
+    h = hashlib.sha256()
+    for path in source_files():
+        h.update(os.path.basename(path).encode() + b"\0")
+        with open(path, "rb") as f:
+            h.update(f.read())
+        h.update(b"\0")
+    return h.hexdigest()
+
+
+def built_hash(path: str = LIB):
+    """The source hash a built library carries (read from the file, nothing is loaded), or None."""
+    if not os.path.exists(path):
+        return None
+    with open(path, "rb") as f:
+        blob = f.read()
+    at = blob.find(HASH_MARKER)
+    if at < 0:
+        return None
+    digest = blob[at + len(HASH_MARKER): at + len(HASH_MARKER) + 64]
+    try:
+        return digest.decode("ascii")
+    except UnicodeDecodeError:
+        return None
+
+
 def build(verbose: bool = False, extra=()) -> str:
     """Compile every kernel for gfx950 (cross-compiles without a GPU) and return the library path."""
     tmp = LIB + ".tmp.%d" % os.getpid()
-    cmd = [hipcc(), *HIPCC_FLAGS, *extra, "-o", tmp, *[os.path.join(CSRC, s) for s in SOURCES]]
+    cmd = [hipcc(), *HIPCC_FLAGS, *extra, f'-DSAGE_SOURCE_HASH="{source_hash()}"', "-o", tmp,
+           *[os.path.join(CSRC, s) for s in SOURCES]]
     try:
         res = subprocess.run(cmd, capture_output=True, text=True)
         noise = "packed-fp32-ops"
@@ -224,11 +264,14 @@ def verify_attention_isa(extra=()) -> None:
 
 
 def is_stale() -> bool:
-    if not os.path.exists(LIB):
-        return True
-    lib_t = os.path.getmtime(LIB)
-    deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC)] + [os.path.join(HERE, "..", "include", "sage.h")]
-    return any(os.path.getmtime(d) > lib_t for d in deps if os.path.exists(d))
+    """True when there is no built library or it was not built from the sources as they are now."""
+    return built_hash() != source_hash()
+
+
+def have_compiler() -> bool:
+    import shutil
+    cc = hipcc()
+    return os.path.exists(cc) if os.path.isabs(cc) else shutil.which(cc) is not None
 
 
 if __name__ == "__main__":

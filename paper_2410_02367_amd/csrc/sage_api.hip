@@ -10,7 +10,7 @@ bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) %
 int check_shape(int B, int H, int N, int D) {
     if (B <= 0 || H <= 0 || N <= 0 || D <= 0) return SAGE_ERR_SHAPE;
     if (N > (1 << 23)) return SAGE_ERR_SHAPE;
-    if ((long long)B * H > 65535) return SAGE_ERR_SHAPE;
+    if ((long long)B * H > 65535) return SAGE_ERR_SHAPE;          // slabs are a grid dimension of the pre-pass
     // B*H*N*D must stay below 2^62 (N*N*B*H for the dump is the caller's concern)
     long double elems = (long double)B * H * (long double)N * D;
     if (elems > 4.0e18L) return SAGE_ERR_SHAPE;
@@ -23,7 +23,19 @@ bool quant_block_ok(int b) { return b == 1 || b == 32 || b == 64 || b == 128; }
 
 }  // namespace
 
+#ifndef SAGE_SOURCE_HASH
+#define SAGE_SOURCE_HASH "unknown"
+#endif
+
 extern "C" {
+
+const char* sage_source_hash(void) {
+    // the marker stays in the binary, so that the hash can also be read from the file without loading it
+    static const char tagged[] = "SAGE_SOURCE_HASH=" SAGE_SOURCE_HASH;
+    return tagged + sizeof("SAGE_SOURCE_HASH=") - 1;
+}
+
+float sage_default_sm_scale(int D) { return D > 0 ? 1.0f / std::sqrt((float)D) : 0.0f; }
 
 const char* sage_status_string(int status) {
     switch (status) {
@@ -56,10 +68,12 @@ int quant_q_impl(const void* q_f16, const float* cs, const float* sn, bool rope,
 int smooth_quant_k_impl(const void* k_f16, const float* cs, const float* sn, bool rope, int8_t* k_i8,
                         float* k_scale, float* k_mean, void* workspace, size_t workspace_bytes,
                         int B, int H, int N, int D, int block_k, void* stream) {
-    if (!k_f16 || !k_i8 || !k_scale || !workspace || (rope && (!cs || !sn))) return SAGE_ERR_NULL;      // k_mean is optional
+    if (!k_f16 || !k_i8 || !k_scale || (rope && (!cs || !sn))) return SAGE_ERR_NULL;      // k_mean is optional
     if (int e = check_shape(B, H, N, D)) return e;
     if (!quant_block_ok(block_k)) return SAGE_ERR_UNSUPPORTED;
-    if (workspace_bytes < sage_smooth_quant_k_workspace(B, H, N, D)) return SAGE_ERR_WORKSPACE;
+    const size_t need = sage_smooth_quant_k_workspace(B, H, N, D);
+    if (need > 0 && !workspace) return SAGE_ERR_NULL;
+    if (workspace_bytes < need) return SAGE_ERR_WORKSPACE;
     if (!aligned(k_f16, 16) || !aligned(k_i8, 16) || !aligned(k_scale, 4) || !aligned(k_mean, 4) ||
         !aligned(workspace, 8))
         return SAGE_ERR_ALIGN;
@@ -82,9 +96,8 @@ int sage_rope_quant_q(const void* q_f16, const float* rope_cos, const float* rop
 }
 
 size_t sage_smooth_quant_k_workspace(int B, int H, int N, int D) {
-    (void)N;
-    if (B <= 0 || H <= 0 || D <= 0) return 0;
-    return (size_t)B * H * D * sizeof(long long);
+    if (B <= 0 || H <= 0 || N <= 0 || D <= 0 || (long long)B * H > 65535) return 0;
+    return (size_t)sage::plan_colsum(B * H, N).parts * B * H * D * sizeof(long long);
 }
 
 int sage_smooth_quant_k(const void* k_f16, int8_t* k_i8, float* k_scale, float* k_mean,
@@ -222,14 +235,29 @@ int sage_quant_v(const void* v_f16, int8_t* v_i8t, float* v_scale, void* workspa
     return e == hipSuccess ? SAGE_OK : SAGE_ERR_LAUNCH;
 }
 
+int sage_microbench(int kind, int waves_per_simd, int workgroups, int iters,
+                    const int32_t* data, uint64_t* out, void* stream) {
+    if (!data || !out) return SAGE_ERR_NULL;
+    if (kind < 0 || kind > 6 || (waves_per_simd != 1 && waves_per_simd != 2)) return SAGE_ERR_UNSUPPORTED;
+    if (kind == 5 && waves_per_simd != 2) return SAGE_ERR_UNSUPPORTED;
+    if (workgroups <= 0 || workgroups > (1 << 20) || iters <= 0) return SAGE_ERR_SHAPE;
+    if (!aligned(data, 16) || !aligned(out, 8)) return SAGE_ERR_ALIGN;
+    hipError_t e = sage::launch_microbench(kind, waves_per_simd, workgroups, iters, (const int*)data,
+                                           (unsigned long long*)out, (hipStream_t)stream);
+    return e == hipSuccess ? SAGE_OK : SAGE_ERR_LAUNCH;
+}
+
 int sage_attn_qk_i32_debug(const int8_t* q_i8, const int8_t* k_i8, int32_t* s_i32,
-                           int B, int H, int N, int D, void* stream) {
+                           int B, int H, int N, int D, int block_q, int block_k, int wg_rows, void* stream) {
     if (!q_i8 || !k_i8 || !s_i32) return SAGE_ERR_NULL;
     if (int e = check_shape(B, H, N, D)) return e;
+    if (!quant_block_ok(block_q)) return SAGE_ERR_UNSUPPORTED;
+    if (block_k != 1 && block_k != 64 && block_k != 128) return SAGE_ERR_UNSUPPORTED;
+    if (wg_rows != 0 && wg_rows != 128 && wg_rows != 256) return SAGE_ERR_UNSUPPORTED;
     if (!aligned(q_i8, 16) || !aligned(k_i8, 16) || !aligned(s_i32, 4)) return SAGE_ERR_ALIGN;
     // scales are not read by the dump path; pass the tensor pointers as placeholders of valid memory
     hipError_t e = sage::launch_attn(q_i8, (const float*)q_i8, k_i8, (const float*)k_i8, nullptr, nullptr, s_i32,
-                                     B * H, N, N, D, 0, 128, 64, (hipStream_t)stream);
+                                     B * H, N, N, D, 0, block_q, block_k, (hipStream_t)stream, wg_rows);
     return e == hipSuccess ? SAGE_OK : SAGE_ERR_LAUNCH;
 }
 

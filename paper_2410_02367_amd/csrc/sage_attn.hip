@@ -972,7 +972,7 @@ static hipError_t launch_dn(const int8_t* qq, const float* qscale, const int8_t*
 template <int D>
 static hipError_t launch_d(const int8_t* qq, const float* qscale, const int8_t* kq, const float* kscale,
                            const void* v, void* o, int32_t* sdump, int BH, int Nq, int N, int causal,
-                           int block_q, int block_k, const SplitPlan& sp, hipStream_t st) {
+                           int block_q, int block_k, const SplitPlan& sp, hipStream_t st, int wg_rows = 0) {
     // 256-row workgroups (8 wavefronts sharing one set of LDS tiles) for long sequences at D = 128;
     // 128-row workgroups, two or three per CU, for D = 64, whenever the larger tile would leave CUs
     // without work (fewer than two workgroups per CU), and for short sequences, where a workgroup
@@ -982,17 +982,19 @@ static hipError_t launch_d(const int8_t* qq, const float* qscale, const int8_t* 
     const long big_tiles = (long)BH * sp.n_splits * ((Nq + 8 * WROWS - 1) / (8 * WROWS));
     const int n_seen = sp.n_splits > 1 ? sp.chunk : N;           // keys a workgroup walks
     const bool short_seq = n_seen <= 2048 || (causal && n_seen <= 4096);
-    const bool small = QS == 1 && (D == 64 || ((big_tiles < 2 * 256 || short_seq) && block_k != 1 && !sdump));
+    bool small = QS == 1 && (D == 64 || ((big_tiles < 2 * 256 || short_seq) && block_k != 1 && !sdump));
+    // the score dump may name the workgroup shape, so that a test reaches every instantiation
+    if (sdump && wg_rows != 0) small = wg_rows == 4 * WROWS;
     if (small) return launch_dn<D, 4>(qq, qscale, kq, kscale, v, o, sdump, BH, Nq, N, causal, block_q, block_k, sp, st);
     return launch_dn<D, 8>(qq, qscale, kq, kscale, v, o, sdump, BH, Nq, N, causal, block_q, block_k, sp, st);
 }
 
 hipError_t launch_attn(const int8_t* qq, const float* qscale, const int8_t* kq, const float* kscale,
                        const void* v, void* o, int32_t* sdump, int BH, int Nq, int N, int D, int causal,
-                       int block_q, int block_k, hipStream_t st) {
+                       int block_q, int block_k, hipStream_t st, int wg_rows) {
     const SplitPlan whole = {1, 0, nullptr};
-    if (D == 64) return launch_d<64>(qq, qscale, kq, kscale, v, o, sdump, BH, Nq, N, causal, block_q, block_k, whole, st);
-    return launch_d<128>(qq, qscale, kq, kscale, v, o, sdump, BH, Nq, N, causal, block_q, block_k, whole, st);
+    if (D == 64) return launch_d<64>(qq, qscale, kq, kscale, v, o, sdump, BH, Nq, N, causal, block_q, block_k, whole, st, wg_rows);
+    return launch_d<128>(qq, qscale, kq, kscale, v, o, sdump, BH, Nq, N, causal, block_q, block_k, whole, st, wg_rows);
 }
 
 // ---- split over the keys ------------------------------------------------------------------------
@@ -1017,6 +1019,11 @@ SplitPlan plan_split(int BH, int Nq, int N, int causal, int requested) {
     // block (128); the last takes the rest.  It starts at or before key N - Nq when causal (N - 1
     // otherwise), so that every row sees at least one key of every chunk and no partial result is
     // empty (the merge relies on it: every lse is finite).
+    // A chunk is at least one group of 128 keys, so a request beyond the number of groups is the same
+    // plan as that number (and 128 * requested then cannot leave the int range: N <= 2^23).
+    const int groups = (N + 127) / 128;
+    if (requested > groups) requested = groups;
+    if (requested <= 1) return {1, 0, nullptr};
     const int chunk = 128 * ((N + 128 * requested - 1) / (128 * requested));
     const int limit = causal ? N - Nq : N - 1;
     const int fit = limit / chunk + 1;

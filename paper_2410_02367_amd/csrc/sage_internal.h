@@ -9,15 +9,23 @@ namespace sage {
 // applied to the input rows on the fly, or both null for none.
 hipError_t launch_quant_q(const void* q, int8_t* qq, float* qscale, int BH, int N, int D,
                           float sm_scale, int block, const float* cs, const float* sn, hipStream_t st);
+// parts: scratch for the partial column sums, plan_colsum(BH, N).parts * BH * D 64-bit words
+// (sequences short enough for the single-launch kernel use none: parts = 0).
+struct ColsumPlan {
+    int parts;      // partial sums per (batch, head) slab
+    int chunk;      // tokens per partial sum
+};
+ColsumPlan plan_colsum(int BH, int N);
 hipError_t launch_smooth_quant_k(const void* k, int8_t* kq, float* kscale, float* kmean,
-                                 long long* sums, int BH, int N, int D, int block,
+                                 long long* parts, int BH, int N, int D, int block,
                                  const float* cs, const float* sn, hipStream_t st);
 
 // Fused attention (MFMA-bound): Nq query rows against N keys per slab.  sdump != nullptr selects the
-// int32 score dump.
+// int32 score dump; for the dump, wg_rows (128 or 256) names the workgroup shape instead of leaving
+// it to the launcher (0).
 hipError_t launch_attn(const int8_t* qq, const float* qscale, const int8_t* kq, const float* kscale,
                        const void* v, void* o, int32_t* sdump, int BH, int Nq, int N, int D, int causal,
-                       int block_q, int block_k, hipStream_t st);
+                       int block_q, int block_k, hipStream_t st, int wg_rows = 0);
 
 // The same with the keys of a slab cut into chunks (for few query rows): partial results per chunk in
 // `workspace` (n_splits * BH * Nq * (2 D + 4) bytes), then a merge into o.  plan_split() resolves the
@@ -45,5 +53,10 @@ hipError_t launch_quant_v(const void* v, int8_t* vt, float* vscale, unsigned* am
 hipError_t launch_attn_pv8(const int8_t* qq, const float* qscale, const int8_t* kq, const float* kscale,
                            const int8_t* vt, const float* vscale, void* o, int BH, int Nq, int N, int D, int causal,
                            int block_q, int block_k, hipStream_t st);
+
+// Instruction-stream probes (sage_microbench.hip): kind 0..6, 1 or 2 wavefronts per SIMD, `out` takes
+// four 64-bit words per wavefront.
+hipError_t launch_microbench(int kind, int waves_per_simd, int workgroups, int iters, const int* data,
+                             unsigned long long* out, hipStream_t st);
 
 }  // namespace sage

@@ -9,7 +9,9 @@
 //
 // Every fp16 value is an integer multiple of 2^-24, so the column sum is accumulated as an
 // integer count of 2^-24 units; the result does not depend on how tokens are split over
-// threads, workgroups or atomics.  One fp64 division and one rounding to fp32 give the mean.
+// threads and workgroups.  One fp64 division and one rounding to fp32 give the mean.
+// The K side is two launches: partial column sums per chunk of tokens, then the quantizer, whose
+// workgroups add the partial sums of their slab (no clearing pass, no atomics).
 #include "sage_internal.h"
 #include <hip/hip_fp16.h>
 
@@ -51,54 +53,80 @@ __device__ __forceinline__ h8 load_row8(const _Float16* __restrict__ row, int c8
     }
 }
 
-__global__ void __launch_bounds__(256) zero_sums_kernel(long long* sums, int n) {
-    int i = blockIdx.x * 256 + threadIdx.x;
-    if (i < n) sums[i] = 0;
-}
-
-// grid (ceil(N / CHUNK), BH); CHUNK = 32 rows per thread * (256 / (D/8)) row groups.
+// Exact column sums, first level: the workgroup (chunk p, slab bh) of grid (P, BH) sums the rows
+// p * chunk .. of its slab and leaves the D sums as 64-bit integers at part[(bh * P + p) * D ..];
+// the quantizer kernels add the P partial sums of their slab themselves (integer addition: any order
+// gives the same bits).  No atomics, nothing to clear beforehand, every word of the result written.
+// `chunk` is a multiple of BATCH * RG rows.  A thread owns one 16-byte column group of every RG-th row
+// and fetches BATCH rows at a time, all loads issued before the first is used (rows past the end are
+// fetched from the last row and not added); its two 32-bit partial sums per column (integer part
+// and 24-bit fraction) are folded into 64-bit ones after every batch, long before they could overflow
+// (8 * 65504 and 8 * 2^24).
 template <int D, bool ROPE>
 __global__ void __launch_bounds__(256) k_colsum_kernel(const _Float16* __restrict__ k,
-                                                       long long* __restrict__ sums, int N,
+                                                       long long* __restrict__ part_out, int N, int chunk,
                                                        const float* __restrict__ cs, const float* __restrict__ sn) {
     constexpr int VPR = D / 8;          // 16-byte vectors per token row
     constexpr int RG = 256 / VPR;       // row groups per workgroup
-    constexpr int RPT = 32;             // rows per thread: keeps the int32 partials far from overflow
-    constexpr int CHUNK = RG * RPT;
+    constexpr int BATCH = 8;            // rows per thread in flight
     const int t = threadIdx.x, c8 = t % VPR, rg = t / VPR;
-    const int bh = blockIdx.y;
-    const int row_base = blockIdx.x * CHUNK + rg;
+    const int bh = blockIdx.y, P = gridDim.x;
+    const int row_begin = blockIdx.x * chunk;
+    const int row_end = row_begin + chunk < N ? row_begin + chunk : N;
     const _Float16* base = k + ((size_t)bh * N) * D;
 
-    int acc_hi[8], acc_lo[8];
+    long long acc[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) { acc_hi[e] = 0; acc_lo[e] = 0; }
-#pragma unroll 8
-    for (int i = 0; i < RPT; ++i) {
-        int r = row_base + i * RG;
-        if (r < N) {
-            h8 x = load_row8<D, ROPE>(base + (size_t)r * D, c8, cs + (size_t)r * (D / 2), sn + (size_t)r * (D / 2));
+    for (int e = 0; e < 8; ++e) acc[e] = 0;
+    for (int r0 = row_begin + rg; r0 < row_end; r0 += BATCH * RG) {
+        h8 x[BATCH];
+#pragma unroll
+        for (int i = 0; i < BATCH; ++i) {
+            const int r = r0 + i * RG;
+            const int rc = r < N ? r : N - 1;
+            x[i] = load_row8<D, ROPE>(base + (size_t)rc * D, c8, cs + (size_t)rc * (D / 2), sn + (size_t)rc * (D / 2));
+        }
+        int acc_hi[8], acc_lo[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { acc_hi[e] = 0; acc_lo[e] = 0; }
+#pragma unroll
+        for (int i = 0; i < BATCH; ++i) {
+            const bool live = r0 + i * RG < row_end;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                float f = (float)x[e];
-                float hi = __builtin_truncf(f);          // integer part, |hi| <= 65504
-                float lo = f - hi;                       // exact; a multiple of 2^-24 below 1
-                acc_hi[e] += (int)hi;
-                acc_lo[e] += (int)(lo * 16777216.0f);    // exact integer below 2^24
+                const float f = (float)x[i][e];
+                const float hi = __builtin_truncf(f);          // integer part, |hi| <= 65504
+                const float lo = f - hi;                       // exact; a multiple of 2^-24 below 1
+                acc_hi[e] += live ? (int)hi : 0;
+                acc_lo[e] += live ? (int)(lo * 16777216.0f) : 0;    // exact integer below 2^24
             }
         }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] += (long long)acc_hi[e] * 16777216ll + (long long)acc_lo[e];
     }
     __shared__ long long part[RG][D];
 #pragma unroll
-    for (int e = 0; e < 8; ++e)
-        part[rg][c8 * 8 + e] = (long long)acc_hi[e] * 16777216ll + (long long)acc_lo[e];
+    for (int e = 0; e < 8; ++e) part[rg][c8 * 8 + e] = acc[e];
     __syncthreads();
     if (t < D) {
         long long s = 0;
 #pragma unroll 4
         for (int g = 0; g < RG; ++g) s += part[g][t];
-        atomicAdd((unsigned long long*)(sums + (size_t)bh * D + t), (unsigned long long)s);
+        part_out[((size_t)bh * P + blockIdx.x) * D + t] = s;
     }
+}
+
+// mean[c] of a slab from its P partial column sums: exact integer total, one fp64 division, one
+// rounding to fp32 (thread c < D of the workgroup; the others return 0).
+template <int D>
+__device__ __forceinline__ float slab_mean(const long long* __restrict__ parts, int bh, int P, int N, int c) {
+    if (c >= D) return 0.0f;
+    const long long* p = parts + (size_t)bh * P * D + c;
+    long long s = 0;
+#pragma unroll 4
+    for (int i = 0; i < P; ++i) s += p[(size_t)i * D];
+    const double avg = (double)s / (double)N;
+    return (float)(avg * 0x1p-24);
 }
 
 template <int NT = 256>
@@ -113,105 +141,48 @@ __device__ __forceinline__ float wg_max(float v, float* red) {
     return m;
 }
 
-// One workgroup of NT threads per quantization block of `block` tokens x D channels;
-// block * D = 8 * NT * LPT.  IS_K: x - mean (mean derived from the exact sums); else x * sm_scale.
+// Per-block quantizer: a workgroup of NT threads takes quantization blocks g = blockIdx.x,
+// blockIdx.x + gridDim.x, ... of its slab, one at a time; a block is `block` tokens x D channels,
+// block * D = 8 * NT * LPT.  IS_K: x - mean (the mean formed once per workgroup from the partial
+// column sums -- which is why a workgroup walks several blocks); else x * sm_scale.  All LPT loads
+// of a block are issued before the first is used (rows past the end of the block are fetched from
+// its last row and ignored).
 template <int D, int LPT, bool IS_K, bool ROPE, int NT = 256>
 __global__ void __launch_bounds__(NT) quant_block_kernel(const _Float16* __restrict__ x,
                                                           int8_t* __restrict__ xq,
                                                           float* __restrict__ scale,
                                                           float* __restrict__ k_mean,
-                                                          const long long* __restrict__ sums,
+                                                          const long long* __restrict__ parts, int P,
                                                           int N, int block, float sm_scale,
                                                           const float* __restrict__ cs, const float* __restrict__ sn) {
     constexpr int VPR = D / 8;
     constexpr int RSTEP = NT / VPR;
     const int t = threadIdx.x, c8 = t % VPR, rbase = t / VPR;
-    const int g = blockIdx.x, bh = blockIdx.y, nblk = gridDim.x;
-    const int row0 = g * block;
-    const int rows = (N - row0 < block) ? (N - row0) : block;
+    const int bh = blockIdx.y, nblk = (N + block - 1) / block;
 
     __shared__ float s_mean[D];
-    __shared__ float s_red[NT / 64];
+    __shared__ float s_red[2][NT / 64];
+    // the LPT rows of block g that this thread owns (rows past the end of the block: its last row)
+    auto load_block = [&](int g, h8 (&raw)[LPT]) {
+        const int row0 = g * block;
+        const int rows = (N - row0 < block) ? (N - row0) : block;
+        const _Float16* xb = x + ((size_t)bh * N + row0) * D;
+#pragma unroll
+        for (int i = 0; i < LPT; ++i) {
+            const int r = rbase + i * RSTEP;
+            const int rc = r < rows ? r : rows - 1;
+            raw[i] = load_row8<D, ROPE>(xb + (size_t)rc * D, c8, cs + (size_t)(row0 + rc) * (D / 2),
+                                        sn + (size_t)(row0 + rc) * (D / 2));
+        }
+    };
+    h8 raw[LPT], ahead[LPT];
+    int g = blockIdx.x;            // the launcher never starts more workgroups than there are blocks
+    load_block(g, raw);            // in flight while the mean is formed
+
     float mean[8];
     if (IS_K) {
         if (t < D) {
-            long long s = sums[(size_t)bh * D + t];
-            double avg = (double)s / (double)N;
-            float m = (float)(avg * 0x1p-24);
-            s_mean[t] = m;
-            if (g == 0 && k_mean != nullptr) k_mean[(size_t)bh * D + t] = m;
-        }
-        __syncthreads();
-#pragma unroll
-        for (int e = 0; e < 8; ++e) mean[e] = s_mean[c8 * 8 + e];
-    }
-
-    const size_t slab = ((size_t)bh * N + row0) * D + c8 * 8;
-    h8 raw[LPT];
-    float amax = 0.0f;
-#pragma unroll
-    for (int i = 0; i < LPT; ++i) {
-        int r = rbase + i * RSTEP;
-        if (r < rows) {
-            raw[i] = load_row8<D, ROPE>(x + slab - c8 * 8 + (size_t)r * D, c8, cs + (size_t)(row0 + r) * (D / 2),
-                                        sn + (size_t)(row0 + r) * (D / 2));
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                float f = (float)raw[i][e];
-                f = IS_K ? (f - mean[e]) : (f * sm_scale);
-                amax = __builtin_fmaxf(amax, __builtin_fabsf(f));
-            }
-        }
-    }
-    amax = wg_max<NT>(amax, s_red);
-    const float delta = amax / 127.0f;
-    const float rcp = amax > 0.0f ? 127.0f / amax : 0.0f;
-    if (t == 0) scale[(size_t)bh * nblk + g] = delta;
-
-#pragma unroll
-    for (int i = 0; i < LPT; ++i) {
-        int r = rbase + i * RSTEP;
-        if (r < rows) {
-            unsigned w[2] = {0u, 0u};
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                float f = (float)raw[i][e];
-                f = IS_K ? (f - mean[e]) : (f * sm_scale);
-                float q = __builtin_rintf(f * rcp);                 // round half to even
-                q = __builtin_fminf(__builtin_fmaxf(q, -127.0f), 127.0f);
-                w[e >> 2] |= ((unsigned)((int)q) & 0xffu) << (8 * (e & 3));
-            }
-            *(uint2*)(xq + slab + (size_t)r * D) = make_uint2(w[0], w[1]);
-        }
-    }
-}
-
-// Per-token quantizer (Section 3.2): one scale per token row.  D/8 adjacent lanes own a row
-// (16 bytes each); the row's absmax is a butterfly over those lanes.  A workgroup covers
-// TOK_ROWS consecutive tokens, TOK_LPT rows per thread, all loads issued before the first use.
-constexpr int TOK_LPT = 8;
-template <int D, bool IS_K, bool ROPE>
-__global__ void __launch_bounds__(256) quant_token_kernel(const _Float16* __restrict__ x,
-                                                          int8_t* __restrict__ xq,
-                                                          float* __restrict__ scale,
-                                                          float* __restrict__ k_mean,
-                                                          const long long* __restrict__ sums,
-                                                          int N, float sm_scale,
-                                                          const float* __restrict__ cs, const float* __restrict__ sn) {
-    constexpr int VPR = D / 8;
-    constexpr int RSTEP = 256 / VPR;
-    constexpr int ROWS = RSTEP * TOK_LPT;
-    const int t = threadIdx.x, c8 = t % VPR, rbase = t / VPR;
-    const int bh = blockIdx.y;
-    const int row0 = blockIdx.x * ROWS;
-
-    __shared__ float s_mean[D];
-    float mean[8];
-    if (IS_K) {
-        if (t < D) {
-            long long s = sums[(size_t)bh * D + t];
-            double avg = (double)s / (double)N;
-            float m = (float)(avg * 0x1p-24);
+            const float m = slab_mean<D>(parts, bh, P, N, t);
             s_mean[t] = m;
             if (blockIdx.x == 0 && k_mean != nullptr) k_mean[(size_t)bh * D + t] = m;
         }
@@ -220,51 +191,130 @@ __global__ void __launch_bounds__(256) quant_token_kernel(const _Float16* __rest
         for (int e = 0; e < 8; ++e) mean[e] = s_mean[c8 * 8 + e];
     }
 
-    const size_t slab = ((size_t)bh * N + row0) * D + c8 * 8;
-    h8 raw[TOK_LPT];
-#pragma unroll
-    for (int i = 0; i < TOK_LPT; ++i) {
-        int r = rbase + i * RSTEP;
-        raw[i] = (h8){0, 0, 0, 0, 0, 0, 0, 0};
-        if (row0 + r < N)
-            raw[i] = load_row8<D, ROPE>(x + slab - c8 * 8 + (size_t)r * D, c8, cs + (size_t)(row0 + r) * (D / 2),
-                                        sn + (size_t)(row0 + r) * (D / 2));
-    }
-#pragma unroll
-    for (int i = 0; i < TOK_LPT; ++i) {
-        const int r = rbase + i * RSTEP;
-        float f[8];
+    for (int turn = 0; g < nblk; g += gridDim.x, turn ^= 1) {
+        const int row0 = g * block;
+        const int rows = (N - row0 < block) ? (N - row0) : block;
+        const size_t slab = ((size_t)bh * N + row0) * D + c8 * 8;
+        // the next block of this workgroup is requested before this one is reduced and stored
+        const bool more = g + (int)gridDim.x < nblk;
+        if (more) load_block(g + gridDim.x, ahead);
         float amax = 0.0f;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            f[e] = (float)raw[i][e];
-            f[e] = IS_K ? (f[e] - mean[e]) : (f[e] * sm_scale);
-            amax = __builtin_fmaxf(amax, __builtin_fabsf(f[e]));
-        }
+        for (int i = 0; i < LPT; ++i) {
 #pragma unroll
-        for (int off = VPR / 2; off >= 1; off >>= 1) amax = __builtin_fmaxf(amax, __shfl_xor(amax, off, 64));
+            for (int e = 0; e < 8; ++e) {       // a clamped row repeats a row of the block: the maximum is unchanged
+                float f = (float)raw[i][e];
+                f = IS_K ? (f - mean[e]) : (f * sm_scale);
+                amax = __builtin_fmaxf(amax, __builtin_fabsf(f));
+            }
+        }
+        amax = wg_max<NT>(amax, s_red[turn]);       // alternating buffers: one barrier per block is enough
         const float delta = amax / 127.0f;
         const float rcp = amax > 0.0f ? 127.0f / amax : 0.0f;
-        if (row0 + r < N) {
-            if (c8 == 0) scale[(size_t)bh * N + row0 + r] = delta;
-            unsigned w[2] = {0u, 0u};
+        if (t == 0) scale[(size_t)bh * nblk + g] = delta;
+
+#pragma unroll
+        for (int i = 0; i < LPT; ++i) {
+            const int r = rbase + i * RSTEP;
+            if (r < rows) {
+                unsigned w[2] = {0u, 0u};
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    float f = (float)raw[i][e];
+                    f = IS_K ? (f - mean[e]) : (f * sm_scale);
+                    float q = __builtin_rintf(f * rcp);                 // round half to even
+                    q = __builtin_fminf(__builtin_fmaxf(q, -127.0f), 127.0f);
+                    w[e >> 2] |= ((unsigned)((int)q) & 0xffu) << (8 * (e & 3));
+                }
+                *(uint2*)(xq + slab + (size_t)r * D) = make_uint2(w[0], w[1]);
+            }
+        }
+        if (more) {
+#pragma unroll
+            for (int i = 0; i < LPT; ++i) raw[i] = ahead[i];
+        }
+    }
+}
+
+// Per-token quantizer (Section 3.2): one scale per token row.  D/8 adjacent lanes own a row
+// (16 bytes each); the row's absmax is a butterfly over those lanes.  A workgroup takes groups of
+// TOK_ROWS consecutive tokens (group blockIdx.x, blockIdx.x + gridDim.x, ...), TOK_LPT rows per
+// thread, all loads of a group issued before the first use (rows past N fetched from row N - 1 and
+// not stored).
+constexpr int TOK_LPT = 8;
+template <int D, bool IS_K, bool ROPE>
+__global__ void __launch_bounds__(256) quant_token_kernel(const _Float16* __restrict__ x,
+                                                          int8_t* __restrict__ xq,
+                                                          float* __restrict__ scale,
+                                                          float* __restrict__ k_mean,
+                                                          const long long* __restrict__ parts, int P,
+                                                          int N, float sm_scale,
+                                                          const float* __restrict__ cs, const float* __restrict__ sn) {
+    constexpr int VPR = D / 8;
+    constexpr int RSTEP = 256 / VPR;
+    constexpr int ROWS = RSTEP * TOK_LPT;
+    const int t = threadIdx.x, c8 = t % VPR, rbase = t / VPR;
+    const int bh = blockIdx.y, ngrp = (N + ROWS - 1) / ROWS;
+
+    __shared__ float s_mean[D];
+    float mean[8];
+    if (IS_K) {
+        if (t < D) {
+            const float m = slab_mean<D>(parts, bh, P, N, t);
+            s_mean[t] = m;
+            if (blockIdx.x == 0 && k_mean != nullptr) k_mean[(size_t)bh * D + t] = m;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int e = 0; e < 8; ++e) mean[e] = s_mean[c8 * 8 + e];
+    }
+
+    for (int grp = blockIdx.x; grp < ngrp; grp += gridDim.x) {
+        const int row0 = grp * ROWS;
+        const _Float16* xs = x + (size_t)bh * N * D;
+        h8 raw[TOK_LPT];
+#pragma unroll
+        for (int i = 0; i < TOK_LPT; ++i) {
+            const int r = row0 + rbase + i * RSTEP;
+            const int rc = r < N ? r : N - 1;
+            raw[i] = load_row8<D, ROPE>(xs + (size_t)rc * D, c8, cs + (size_t)rc * (D / 2), sn + (size_t)rc * (D / 2));
+        }
+#pragma unroll
+        for (int i = 0; i < TOK_LPT; ++i) {
+            const int r = row0 + rbase + i * RSTEP;
+            float f[8];
+            float amax = 0.0f;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                float q = __builtin_rintf(f[e] * rcp);                 // round half to even
-                q = __builtin_fminf(__builtin_fmaxf(q, -127.0f), 127.0f);
-                w[e >> 2] |= ((unsigned)((int)q) & 0xffu) << (8 * (e & 3));
+                f[e] = (float)raw[i][e];
+                f[e] = IS_K ? (f[e] - mean[e]) : (f[e] * sm_scale);
+                amax = __builtin_fmaxf(amax, __builtin_fabsf(f[e]));
             }
-            *(uint2*)(xq + slab + (size_t)r * D) = make_uint2(w[0], w[1]);
+#pragma unroll
+            for (int off = VPR / 2; off >= 1; off >>= 1) amax = __builtin_fmaxf(amax, __shfl_xor(amax, off, 64));
+            const float delta = amax / 127.0f;
+            const float rcp = amax > 0.0f ? 127.0f / amax : 0.0f;
+            if (r < N) {
+                if (c8 == 0) scale[(size_t)bh * N + r] = delta;
+                unsigned w[2] = {0u, 0u};
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    float q = __builtin_rintf(f[e] * rcp);                 // round half to even
+                    q = __builtin_fminf(__builtin_fmaxf(q, -127.0f), 127.0f);
+                    w[e >> 2] |= ((unsigned)((int)q) & 0xffu) << (8 * (e & 3));
+                }
+                *(uint2*)(xq + ((size_t)bh * N + r) * D + c8 * 8) = make_uint2(w[0], w[1]);
+            }
         }
     }
 }
 
 // Short sequences (N <= SMALL_N): the whole K pre-pass of one (batch, head) slab in ONE workgroup
 // and one launch -- exact column sums, mean, then the quantization blocks one after the other
-// (the slab is re-read from cache).  Three launches of a few microseconds each become one; the
+// (the slab is re-read from cache).  The launches of a few microseconds each become one; the
 // results are the same bits (the integer sum does not depend on how it is split).  Beyond a few
-// blocks per slab the serial loop over blocks loses against the three wide launches (measured:
-// faster at N = 197, slower at N = 1105), hence the low limit.
+// blocks per slab the serial loop over blocks loses against the wide launches (measured: faster
+// at N = 197, slower at N = 1105), hence the low limit.
 constexpr int SMALL_N = 512;
 template <int D, bool ROPE>
 __global__ void __launch_bounds__(256) k_small_kernel(const _Float16* __restrict__ k,
@@ -378,25 +428,35 @@ __global__ void __launch_bounds__(256) k_small_kernel(const _Float16* __restrict
     }
 }
 
+// Workgroups per slab of the quantizer kernels: enough to fill the chip a few times over, few
+// enough that a workgroup of the K side walks several blocks per read of the partial sums.
+static int quant_groups(int BH, int units) {
+    const int want = (2048 + BH - 1) / BH;
+    return units < want ? units : want;
+}
+
 template <int D, bool IS_K, bool ROPE>
-static hipError_t launch_quant(const void* x, int8_t* xq, float* scale, float* mean, const long long* sums,
+static hipError_t launch_quant(const void* x, int8_t* xq, float* scale, float* mean, const long long* parts, int P,
                                int BH, int N, int block, float sm_scale, const float* cs, const float* sn,
                                hipStream_t st) {
     const _Float16* xp = (const _Float16*)x;
     if (block == 1) {
         constexpr int ROWS = (256 / (D / 8)) * TOK_LPT;
-        quant_token_kernel<D, IS_K, ROPE><<<dim3((N + ROWS - 1) / ROWS, BH), 256, 0, st>>>(xp, xq, scale, mean, sums, N, sm_scale, cs, sn);
+        const int ngrp = (N + ROWS - 1) / ROWS;
+        quant_token_kernel<D, IS_K, ROPE><<<dim3(IS_K ? quant_groups(BH, ngrp) : ngrp, BH), 256, 0, st>>>(
+            xp, xq, scale, mean, parts, P, N, sm_scale, cs, sn);
         return hipGetLastError();
     }
-    dim3 grid((N + block - 1) / block, BH);
-#define SAGE_QUANT(LPT) quant_block_kernel<D, LPT, IS_K, ROPE><<<grid, 256, 0, st>>>(xp, xq, scale, mean, sums, N, block, sm_scale, cs, sn)
+    const int nblk = (N + block - 1) / block;
+    dim3 grid(quant_groups(BH, nblk), BH);
+#define SAGE_QUANT(LPT) quant_block_kernel<D, LPT, IS_K, ROPE><<<grid, 256, 0, st>>>(xp, xq, scale, mean, parts, P, N, block, sm_scale, cs, sn)
     switch (block * D / 2048) {
         case 1: SAGE_QUANT(1); break;
         case 2: SAGE_QUANT(2); break;
         case 4: SAGE_QUANT(4); break;
         // the largest block (128 tokens x 128 channels) runs with 512 threads of 4 rows each: twice the
         // loads in flight per block and half the work per thread behind the block-wide maximum
-        case 8: quant_block_kernel<D, 4, IS_K, ROPE, 512><<<grid, 512, 0, st>>>(xp, xq, scale, mean, sums, N, block, sm_scale, cs, sn); break;
+        case 8: quant_block_kernel<D, 4, IS_K, ROPE, 512><<<grid, 512, 0, st>>>(xp, xq, scale, mean, parts, P, N, block, sm_scale, cs, sn); break;
         default: return hipErrorInvalidValue;
     }
 #undef SAGE_QUANT
@@ -406,7 +466,7 @@ static hipError_t launch_quant(const void* x, int8_t* xq, float* scale, float* m
 template <int D, bool ROPE>
 static hipError_t quant_q_d(const void* q, int8_t* qq, float* qscale, int BH, int N, float sm_scale, int block,
                             const float* cs, const float* sn, hipStream_t st) {
-    return launch_quant<D, false, ROPE>(q, qq, qscale, nullptr, nullptr, BH, N, block, sm_scale, cs, sn, st);
+    return launch_quant<D, false, ROPE>(q, qq, qscale, nullptr, nullptr, 0, BH, N, block, sm_scale, cs, sn, st);
 }
 
 // cs, sn: RoPE tables [N, D/2] (both null: no rotation)
@@ -419,22 +479,39 @@ hipError_t launch_quant_q(const void* q, int8_t* qq, float* qscale, int BH, int 
                 : quant_q_d<128, false>(q, qq, qscale, BH, N, sm_scale, block, cs, sn, st);
 }
 
+// How the tokens of a slab are cut for the first level of the column sums: about 512 workgroups in
+// all (two per compute unit keep enough loads in flight), at most 64 partial sums per slab (every
+// quantizer workgroup adds them up again), chunks of whole 256-row batches and at least 512 rows.
+ColsumPlan plan_colsum(int BH, int N) {
+    if (N <= SMALL_N) return {0, 0};                    // single-launch kernel, no partial sums
+    const int want = (512 + BH - 1) / BH;
+    long chunk = (N + want - 1) / want;
+    chunk = 256 * ((chunk + 255) / 256);
+    if (chunk < 512) chunk = 512;
+    int P = (int)((N + chunk - 1) / chunk);
+    if (P > 64) {
+        chunk = 256 * (((N + 63) / 64 + 255) / 256);
+        P = (int)((N + chunk - 1) / chunk);
+    }
+    return {P, (int)chunk};
+}
+
 template <int D, bool ROPE>
-static hipError_t smooth_quant_k_d(const void* k, int8_t* kq, float* kscale, float* kmean, long long* sums,
+static hipError_t smooth_quant_k_d(const void* k, int8_t* kq, float* kscale, float* kmean, long long* parts,
                                    int BH, int N, int block, const float* cs, const float* sn, hipStream_t st) {
-    constexpr int CHUNK = (256 / (D / 8)) * 32;
-    k_colsum_kernel<D, ROPE><<<dim3((N + CHUNK - 1) / CHUNK, BH), 256, 0, st>>>((const _Float16*)k, sums, N, cs, sn);
+    const ColsumPlan cp = plan_colsum(BH, N);
+    k_colsum_kernel<D, ROPE><<<dim3(cp.parts, BH), 256, 0, st>>>((const _Float16*)k, parts, N, cp.chunk, cs, sn);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    return launch_quant<D, true, ROPE>(k, kq, kscale, kmean, sums, BH, N, block, 1.0f, cs, sn, st);
+    return launch_quant<D, true, ROPE>(k, kq, kscale, kmean, parts, cp.parts, BH, N, block, 1.0f, cs, sn, st);
 }
 
 hipError_t launch_smooth_quant_k(const void* k, int8_t* kq, float* kscale, float* kmean,
-                                 long long* sums, int BH, int N, int D, int block,
+                                 long long* parts, int BH, int N, int D, int block,
                                  const float* cs, const float* sn, hipStream_t st) {
+    const bool rope = cs != nullptr;
     if (N <= SMALL_N) {
         const _Float16* kp = (const _Float16*)k;
-        const bool rope = cs != nullptr;
         if (D == 64) {
             if (rope) k_small_kernel<64, true><<<BH, 256, 0, st>>>(kp, kq, kscale, kmean, N, block, cs, sn);
             else k_small_kernel<64, false><<<BH, 256, 0, st>>>(kp, kq, kscale, kmean, N, block, cs, sn);
@@ -444,15 +521,10 @@ hipError_t launch_smooth_quant_k(const void* k, int8_t* kq, float* kscale, float
         }
         return hipGetLastError();
     }
-    int n = BH * D;
-    zero_sums_kernel<<<(n + 255) / 256, 256, 0, st>>>(sums, n);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    const bool rope = cs != nullptr;
-    if (D == 64) return rope ? smooth_quant_k_d<64, true>(k, kq, kscale, kmean, sums, BH, N, block, cs, sn, st)
-                             : smooth_quant_k_d<64, false>(k, kq, kscale, kmean, sums, BH, N, block, cs, sn, st);
-    return rope ? smooth_quant_k_d<128, true>(k, kq, kscale, kmean, sums, BH, N, block, cs, sn, st)
-                : smooth_quant_k_d<128, false>(k, kq, kscale, kmean, sums, BH, N, block, cs, sn, st);
+    if (D == 64) return rope ? smooth_quant_k_d<64, true>(k, kq, kscale, kmean, parts, BH, N, block, cs, sn, st)
+                             : smooth_quant_k_d<64, false>(k, kq, kscale, kmean, parts, BH, N, block, cs, sn, st);
+    return rope ? smooth_quant_k_d<128, true>(k, kq, kscale, kmean, parts, BH, N, block, cs, sn, st)
+                : smooth_quant_k_d<128, false>(k, kq, kscale, kmean, parts, BH, N, block, cs, sn, st);
 }
 
 }  // namespace sage

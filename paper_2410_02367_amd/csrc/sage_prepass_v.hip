@@ -34,15 +34,18 @@ __global__ void __launch_bounds__(256) v_absmax_kernel(const _Float16* __restric
     float m[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) m[e] = 0.0f;
+    // all loads of a thread are issued before the first is used; a row past the end is fetched from
+    // the last row instead, which leaves the maximum unchanged
+    vh8 x[RPT];
 #pragma unroll
     for (int i = 0; i < RPT; ++i) {
         const int r = row_base + i * RG;
-        if (r < N) {
-            const vh8 x = *(const vh8*)(base + (size_t)r * D + c8 * 8);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) m[e] = __builtin_fmaxf(m[e], __builtin_fabsf((float)x[e]));
-        }
+        x[i] = *(const vh8*)(base + (size_t)(r < N ? r : N - 1) * D + c8 * 8);
     }
+#pragma unroll
+    for (int i = 0; i < RPT; ++i)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) m[e] = __builtin_fmaxf(m[e], __builtin_fabsf((float)x[i][e]));
     __shared__ float part[RG][D];
 #pragma unroll
     for (int e = 0; e < 8; ++e) part[rg][c8 * 8 + e] = m[e];
@@ -81,9 +84,12 @@ __global__ void __launch_bounds__(256) v_quant_transpose_kernel(const _Float16* 
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int row = tile * ROWS + 4 * g + i;
+        // rows past the end: fetched from the last row, then zeroed (no load sits behind a branch)
+        x[i] = *(const vh8*)(base + (size_t)(row < N ? row : N - 1) * D + c8 * 8);
+        if (row >= N) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) x[i][e] = (_Float16)0.0f;
-        if (row < N) x[i] = *(const vh8*)(base + (size_t)row * D + c8 * 8);
+            for (int e = 0; e < 8; ++e) x[i][e] = (_Float16)0.0f;
+        }
     }
 #pragma unroll
     for (int e = 0; e < 8; ++e) {

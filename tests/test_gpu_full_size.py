@@ -67,12 +67,14 @@ def test_full_size_parity(name, n_heads, n_blocks):
 
     # ---- int32 scores of one head on sampled rows
     b, h = heads[-1]
-    s_dev = sage.sage_attn_qk_i32_debug(q_i8[b:b + 1, h:h + 1].contiguous(), k_i8[b:b + 1, h:h + 1].contiguous())
-    torch.cuda.synchronize()
-    for row0 in sorted({0, (w.N // 2) // 32 * 32, max(0, w.N - 40)}):
-        nrows = min(40, w.N - row0)
-        ref = oracle.qk_i32(qq[b, h], kq[b, h], row0, nrows)
-        got = s_dev[0, 0, row0:row0 + nrows].cpu().numpy()
-        assert np.array_equal(got, ref), f"int32 scores differ at rows {row0}.."
-    del s_dev
+    q1, k1 = q_i8[b:b + 1, h:h + 1].contiguous(), k_i8[b:b + 1, h:h + 1].contiguous()
+    for wg_rows in (256, 128):       # both workgroup shapes of the attention kernel
+        s_dev = sage.sage_attn_qk_i32_debug(q1, k1, block_q=w.block_q, block_k=w.block_k, wg_rows=wg_rows)
+        torch.cuda.synchronize()
+        for row0 in sorted({0, (w.N // 2) // 32 * 32, max(0, w.N - 40)}):
+            nrows = min(40, w.N - row0)
+            ref = oracle.qk_i32(qq[b, h], kq[b, h], row0, nrows)
+            got = s_dev[0, 0, row0:row0 + nrows].cpu().numpy()
+            assert np.array_equal(got, ref), f"int32 scores differ at rows {row0}.. (workgroup rows {wg_rows})"
+        del s_dev
     print(f"  int32 dump ok {time.time() - t0:.1f}s", flush=True)

@@ -38,13 +38,16 @@ def test_small_workloads_full_parity(w):
     q, k, v = si.full(w)
     (q_i8, q_scale, k_i8, k_scale, k_mean), (qq, qs, kq, ks, km) = assert_prepass_bit_exact(
         q, k, w.sm_scale, w.block_q, w.block_k)
-    # int32 scores through the attention kernel's MFMA path
-    s_gpu = sage.sage_attn_qk_i32_debug(q_i8, k_i8)
-    torch.cuda.synchronize()
-    s_gpu = s_gpu.cpu().numpy()
-    for b in range(w.B):
-        for h in range(w.H):
-            assert np.array_equal(s_gpu[b, h], oracle.qk_i32(qq[b, h], kq[b, h])), "int32 scores differ"
+    # int32 scores through the attention kernel's MFMA path, in both workgroup shapes the kernel is
+    # built in (4 and 8 wavefronts) and in the one the launcher picks for this shape
+    s_ref = [[oracle.qk_i32(qq[b, h], kq[b, h]) for h in range(w.H)] for b in range(w.B)]
+    for wg_rows in (128, 256, 0):
+        s_gpu = sage.sage_attn_qk_i32_debug(q_i8, k_i8, block_q=w.block_q, block_k=w.block_k, wg_rows=wg_rows)
+        torch.cuda.synchronize()
+        s_gpu = s_gpu.cpu().numpy()
+        for b in range(w.B):
+            for h in range(w.H):
+                assert np.array_equal(s_gpu[b, h], s_ref[b][h]), f"int32 scores differ (workgroup rows {wg_rows})"
     # output
     o_gpu = sage.sage_attn_fwd(q_i8, q_scale, k_i8, k_scale, to_dev(v), w.causal, w.sm_scale, w.block_q, w.block_k)
     torch.cuda.synchronize()
@@ -140,9 +143,12 @@ def test_host_side_errors_leave_no_side_effects():
     with pytest.raises(sage.SageError) as e:
         sage.sage_quant_q(q96, 0.125, block_q=64)
     assert e.value.status == 3
+    # a sequence long enough to need scratch for its partial column sums, and a workspace too small for them
+    k_long = torch.zeros((1, 1, 1024, 64), dtype=torch.float16, device="cuda")
+    assert sage.sage_smooth_quant_k_workspace(1, 1, 1024, 64) > 8
     ws = torch.zeros(1, dtype=torch.int64, device="cuda")
     with pytest.raises(sage.SageError) as e:
-        sage.sage_smooth_quant_k(q, 64, workspace=ws)
+        sage.sage_smooth_quant_k(k_long, 64, workspace=ws)
     assert e.value.status == 4
     torch.cuda.synchronize()
 
@@ -150,7 +156,7 @@ def test_host_side_errors_leave_no_side_effects():
 @pytest.mark.parametrize("N,block_k", [(300, 64), (3000, 64), (3000, 1)])
 def test_k_mean_output_is_optional(N, block_k):
     """sage_smooth_quant_k with k_mean = NULL (straight through the C ABI): same codes and scales as with it,
-    on the single-launch path for short sequences and on the three-launch path."""
+    on the single-launch path for short sequences and on the two-launch path."""
     import ctypes
     w = si.custom("nomean", 2, 2, N, 128, False, seed=si.BASE_SEED + 60 + N)
     _, k, _ = si.full(w)

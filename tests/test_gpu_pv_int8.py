@@ -7,7 +7,7 @@ compute differently (hardware exp2 against libm expf), so a code can differ by o
 one code of one key is worth at most delta_V[c] / l in the output (l = the row's softmax denominator
 relative to its maximum, returned by the oracle).  The bar is therefore
     |O_gpu - O_oracle| <= 2e-3 + 2 delta_V[c] / l[row]      for every element,
-    |O_gpu - O_oracle| <= 2e-3                              for at least 99.9 % of the elements,
+    |O_gpu - O_oracle| <= 2e-3                              for all but at most 1 element in 100 000,
     cosine >= 0.9999."""
 import time
 
@@ -60,14 +60,19 @@ def assert_v_quant_bit_exact(v):
 
 
 def assert_pv8_close(o_gpu, o_ref, l_ref, vs, what):
+    """The bar of the FP16-product kernels (max-abs 2e-3, cosine 0.9999), except that a code of P~ may
+    fall on the other side of a rounding boundary in the two implementations (the decision hangs on the
+    last bits of an fp32 exponential): such an element may be off by up to two codes of one key,
+    2 * delta_V[c] / l, and at most one element in 100 000 may need that allowance."""
     a = o_gpu.astype(np.float64); b = o_ref.astype(np.float64)
     assert np.all(np.isfinite(a)), f"{what}: non-finite output"
     diff = np.abs(a - b)
     tol = ABS_TOL + 2.0 * vs[..., None, :].astype(np.float64) / l_ref[..., :, None].astype(np.float64)
     worst = float((diff - tol).max())
     assert worst <= 0.0, f"{what}: an element is {worst:.3e} beyond 2e-3 + two codes"
-    frac = float(np.mean(diff <= ABS_TOL))
-    assert frac >= 0.999, f"{what}: only {frac:.5f} of the elements within {ABS_TOL}"
+    beyond = int(np.count_nonzero(diff > ABS_TOL))
+    frac = 1.0 - beyond / diff.size
+    assert beyond <= diff.size // 100000, f"{what}: {beyond} of {diff.size} elements beyond {ABS_TOL} (only {frac:.6f} within)"
     cos = float((a * b).sum() / (np.sqrt((a * a).sum()) * np.sqrt((b * b).sum())))
     assert cos >= COS_TOL, f"{what}: cosine {cos:.7f} < {COS_TOL}"
     return float(diff.max()), cos, frac

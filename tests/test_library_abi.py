@@ -44,9 +44,19 @@ def test_status_strings(lib):
 
 
 def test_workspace_query(lib):
-    assert lib.sage_smooth_quant_k_workspace(1, 2, 256, 64) == 2 * 64 * 8
-    assert lib.sage_smooth_quant_k_workspace(1, 8, 131072, 128) == 8 * 128 * 8
+    """Partial column sums: [B*H, chunks, D] 64-bit words, chunks of whole 256-row batches (at least 512
+    rows), about 512 chunks over all slabs and never more than 64 per slab; none for short sequences."""
+    assert lib.sage_smooth_quant_k_workspace(1, 2, 256, 64) == 0
+    assert lib.sage_smooth_quant_k_workspace(1, 2, 512, 64) == 0
+    assert lib.sage_smooth_quant_k_workspace(1, 2, 513, 64) == 2 * 2 * 64 * 8
+    assert lib.sage_smooth_quant_k_workspace(1, 32, 16384, 128) == 16 * 32 * 128 * 8
+    assert lib.sage_smooth_quant_k_workspace(1, 8, 131072, 128) == 64 * 8 * 128 * 8
+    assert lib.sage_smooth_quant_k_workspace(4, 32, 4096, 128) == 4 * 128 * 128 * 8
+    assert lib.sage_smooth_quant_k_workspace(1, 1, 1 << 23, 128) == 64 * 128 * 8
     assert lib.sage_smooth_quant_k_workspace(0, 8, 10, 128) == 0
+    for B, H, N, D in ((2, 30, 17776, 64), (1, 1, 100000, 64), (3, 7, 5000, 128), (1, 1, 513, 128)):
+        chunks = lib.sage_smooth_quant_k_workspace(B, H, N, D) // (B * H * D * 8)
+        assert 1 <= chunks <= 64 and lib.sage_smooth_quant_k_workspace(B, H, N, D) == chunks * B * H * D * 8
 
 
 def test_host_validation_rejects_bad_arguments_before_any_launch(lib):
@@ -56,7 +66,7 @@ def test_host_validation_rejects_bad_arguments_before_any_launch(lib):
     # NULL pointers
     assert lib.sage_quant_q(None, good, good, 1, 1, 64, 64, f(0.125), 64, None) == 1
     assert lib.sage_attn_fwd(good, good, good, good, None, good, 1, 1, 64, 64, 0, f(0.125), 128, 64, None) == 1
-    assert lib.sage_smooth_quant_k(good, good, good, good, None, 0, 1, 1, 64, 64, 64, None) == 1
+    assert lib.sage_smooth_quant_k(good, good, good, good, None, 0, 1, 1, 1024, 64, 64, None) == 1
     # shapes
     assert lib.sage_quant_q(good, good, good, 0, 1, 64, 64, f(0.125), 64, None) == 2
     assert lib.sage_quant_q(good, good, good, 1, 1, (1 << 23) + 1, 64, f(0.125), 64, None) == 2
@@ -67,15 +77,19 @@ def test_host_validation_rejects_bad_arguments_before_any_launch(lib):
     assert lib.sage_quant_q(good, good, good, 1, 1, 64, 64, f(float("inf")), 64, None) == 7
     assert lib.sage_attn_fwd(good, good, good, good, good, good, 1, 1, 64, 64, 0, f(-1.0), 128, 64, None) == 7
     # workspace, alignment
-    assert lib.sage_smooth_quant_k(good, good, good, good, good, 8, 1, 1, 64, 64, 64, None) == 4
+    assert lib.sage_smooth_quant_k(good, good, good, good, good, 8, 1, 1, 1024, 64, 64, None) == 4
     assert lib.sage_quant_q(odd, good, good, 1, 1, 64, 64, f(0.125), 64, None) == 5
-    assert lib.sage_attn_qk_i32_debug(good, odd, good, 1, 1, 64, 64, None) == 5
+    assert lib.sage_attn_qk_i32_debug(good, odd, good, 1, 1, 64, 64, 128, 64, 0, None) == 5
+    assert lib.sage_attn_qk_i32_debug(good, good, good, 1, 1, 64, 64, 128, 32, 0, None) == 3
+    assert lib.sage_attn_qk_i32_debug(good, good, good, 1, 1, 64, 64, 128, 64, 64, None) == 3
+    # more (batch, head) slabs than the documented limit
+    assert lib.sage_quant_q(good, good, good, 256, 256, 64, 64, f(0.125), 64, None) == 2
     # the fused-RoPE calls: tables required and 16-byte aligned, everything else as the unfused calls
     assert lib.sage_rope_quant_q(good, None, good, good, good, 1, 1, 64, 64, f(0.125), 64, None) == 1
     assert lib.sage_rope_quant_q(good, good, odd, good, good, 1, 1, 64, 64, f(0.125), 64, None) == 5
     assert lib.sage_rope_quant_q(good, good, good, good, good, 1, 1, 64, 64, f(0.125), 48, None) == 3
     assert lib.sage_rope_smooth_quant_k(good, good, None, good, good, good, good, 1 << 20, 1, 1, 64, 64, 64, None) == 1
-    assert lib.sage_rope_smooth_quant_k(good, good, good, good, good, good, good, 8, 1, 1, 64, 64, 64, None) == 4
+    assert lib.sage_rope_smooth_quant_k(good, good, good, good, good, good, good, 8, 1, 1, 1024, 64, 64, None) == 4
     assert lib.sage_rope_smooth_quant_k(good, odd, good, good, good, good, good, 1 << 20, 1, 1, 64, 64, 64, None) == 5
 
 
@@ -140,6 +154,15 @@ def test_split_call_validates_and_its_chunk_plan_keeps_its_promises(lib):
     assert lib.sage_attn_split_count(1, 1, 4097, 4096, 1, 4) == 0
     assert lib.sage_attn_split_count(1, 1, 4, 4096, 1, 1) == 1 and lib.sage_attn_split_workspace(1, 1, 4, 4096, 64, 1, 1) == 0
     assert lib.sage_attn_split_workspace(2, 3, 4, 4096, 64, 1, 4) == 4 * 2 * 3 * 4 * (2 * 64 + 4)
+    # a request far beyond the number of 128-key groups is the plan of that number (and must not
+    # overflow the host arithmetic): 4096 keys are 32 groups
+    for huge in (1 << 24, 1 << 25, (1 << 31) - 1):
+        assert lib.sage_attn_split_count(1, 1, 4, 4096, 1, huge) == 32
+        assert lib.sage_attn_split_count(1, 1, 4, 4096, 0, huge) == 32
+        assert lib.sage_attn_split_workspace(1, 1, 4, 4096, 64, 1, huge) == 32 * 4 * (2 * 64 + 4)
+        assert lib.sage_attn_cross_split_fwd(*head, good, sz(64), 1, 1, 4, 4096, 64, 1, f(0.125), 128, 64, huge, None) == 4
+        assert lib.sage_attn_pv_int8_cross_split_fwd(*head8, good, sz(64), 1, 1, 4, 4096, 64, 1, f(0.125), 128, 64, huge, None) == 4
+        assert lib.sage_attn_split_count(1, 1, 1, 1, 0, huge) == 1
     g = np.random.default_rng(20241002)
     for _ in range(3000):
         Nkv = int(g.integers(1, 40000))
