@@ -60,7 +60,8 @@ enum {
     SAGE_ERR_WORKSPACE = 4,   /* workspace_bytes smaller than the call's *_workspace() size   */
     SAGE_ERR_ALIGN = 5,       /* a pointer is not aligned as required                          */
     SAGE_ERR_LAUNCH = 6,      /* the HIP runtime reported an error at launch                   */
-    SAGE_ERR_VALUE = 7        /* sm_scale not finite or not positive                           */
+    SAGE_ERR_VALUE = 7,       /* sm_scale not finite or not positive                           */
+    SAGE_ERR_SCRATCH = 8      /* sage_smooth_quant_k_noalloc: shape beyond the static scratch  */
 };
 
 /* Human-readable name of a status code (host pointer to a static string; never NULL). */
@@ -114,6 +115,27 @@ size_t sage_smooth_quant_k_workspace(int B, int H, int N, int D);
 int sage_smooth_quant_k(const void* k_f16, int8_t* k_i8, float* k_scale, float* k_mean,
                         void* workspace, size_t workspace_bytes,
                         int B, int H, int N, int D, int block_k, void* stream);
+
+/*
+ * sage_smooth_quant_k for callers that cannot allocate device memory or carry a workspace around:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * kernels, same results bit for bit; the partial column sums go to a buffer that is part of the
+ * library's device image (SAGE_NOALLOC_SCRATCH_BYTES = 4 MiB, held by every GPU the
+ * library runs on until the process ends) instead of a caller-supplied workspace.  The call allocates
+ * and frees nothing.
+ *   - Shapes whose sage_smooth_quant_k_workspace() exceeds the limit are refused with
+ *     SAGE_ERR_SCRATCH before anything is launched (the limit covers B*H*chunks*D <= 524288, e.g.
+ *     every configuration with B*H <= 64 at D = 128).
+ *   - All calls on one GPU share that GPU's buffer: calls that may overlap in time (different
+ *     streams, or threads) race on it and must be ordered by the caller.  Nothing needs clearing
+ *     between calls: every word that is read was written by the same call.
+ *   - The first call on a device looks up the buffer's address (hipGetSymbolAddress, once per
+ *     device, under a lock); SAGE_ERR_LAUNCH if that fails.
+ * All other arguments, limits and error codes as sage_smooth_quant_k.
+ */
+#define SAGE_NOALLOC_SCRATCH_BYTES (4u << 20)
+int sage_smooth_quant_k_noalloc(const void* k_f16, int8_t* k_i8, float* k_scale, float* k_mean,
+                                int B, int H, int N, int D, int block_k, void* stream);
 
 /*
  * The two pre-pass calls with the rotary position embedding applied on the fly -- Section 4.6

@@ -26,6 +26,8 @@ from .binding import (  # noqa: F401
     sage_rope_quant_q,
     sage_rope_smooth_quant_k,
     sage_smooth_quant_k,
+    NOALLOC_SCRATCH_BYTES,
+    sage_smooth_quant_k_noalloc,
     sage_smooth_quant_k_workspace,
     sage_source_hash,
     sage_status_string,

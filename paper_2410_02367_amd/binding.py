@@ -11,7 +11,7 @@ _LIB_PATH = os.path.join(_HERE, "libsage.so")
 _lib = None
 
 EXPORTS = ("sage_status_string", "sage_source_hash", "sage_default_sm_scale", "sage_quant_q", "sage_smooth_quant_k_workspace",
-           "sage_smooth_quant_k", "sage_rope_quant_q", "sage_rope_smooth_quant_k",
+           "sage_smooth_quant_k", "sage_smooth_quant_k_noalloc", "sage_rope_quant_q", "sage_rope_smooth_quant_k",
            "sage_attn_fwd", "sage_attn_qk_i32_debug",
            "sage_quant_v_workspace", "sage_quant_v_pitch", "sage_quant_v", "sage_attn_pv_int8_fwd",
            "sage_attn_cross_fwd", "sage_attn_pv_int8_cross_fwd",
@@ -61,6 +61,8 @@ def load() -> ctypes.CDLL:
     lib.sage_smooth_quant_k.restype = c_int
     lib.sage_smooth_quant_k.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t,
                                         c_int, c_int, c_int, c_int, c_int, c_void_p]
+    lib.sage_smooth_quant_k_noalloc.restype = c_int
+    lib.sage_smooth_quant_k_noalloc.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int, c_void_p]
     lib.sage_rope_quant_q.restype = c_int
     lib.sage_rope_quant_q.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                       c_int, c_int, c_int, c_int, c_float, c_int, c_void_p]
@@ -216,6 +218,27 @@ def sage_smooth_quant_k(k: torch.Tensor, block_k: int = 64, k_i8=None, k_scale=N
                                     workspace.data_ptr(), ws_bytes, B, H, N, D, int(block_k), _stream(stream))
     if st != 0:
         raise SageError(st, "sage_smooth_quant_k")
+    return k_i8, k_scale, k_mean
+
+
+NOALLOC_SCRATCH_BYTES = 4 << 20     # SAGE_NOALLOC_SCRATCH_BYTES of include/sage.h
+
+
+def sage_smooth_quant_k_noalloc(k: torch.Tensor, block_k: int = 64, k_i8=None, k_scale=None, k_mean=None, stream=None):
+    """sage_smooth_quant_k without a workspace argument: the library call allocates nothing (its scratch is a
+    static device array); pass k_i8 / k_scale / k_mean as well and neither does this wrapper."""
+    B, H, N, D = k.shape
+    if k_i8 is None:
+        k_i8 = torch.empty((B, H, N, D), dtype=torch.int8, device=k.device)
+    if k_scale is None:
+        k_scale = torch.empty((B, H, _nblk(N, block_k)), dtype=torch.float32, device=k.device)
+    if k_mean is None:
+        k_mean = torch.empty((B, H, D), dtype=torch.float32, device=k.device)
+    st = load().sage_smooth_quant_k_noalloc(_dev(k, torch.float16, "k"), _dev(k_i8, torch.int8, "k_i8"),
+                                            _dev(k_scale, torch.float32, "k_scale"), _dev(k_mean, torch.float32, "k_mean"),
+                                            B, H, N, D, int(block_k), _stream(stream))
+    if st != 0:
+        raise SageError(st, "sage_smooth_quant_k_noalloc")
     return k_i8, k_scale, k_mean
 
 

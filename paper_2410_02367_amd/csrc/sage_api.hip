@@ -2,6 +2,7 @@
 #include "../../include/sage.h"
 #include "sage_internal.h"
 #include <cmath>
+#include <mutex>
 
 namespace {
 
@@ -47,6 +48,7 @@ const char* sage_status_string(int status) {
         case SAGE_ERR_ALIGN: return "SAGE_ERR_ALIGN: pointer alignment";
         case SAGE_ERR_LAUNCH: return "SAGE_ERR_LAUNCH: HIP launch failed";
         case SAGE_ERR_VALUE: return "SAGE_ERR_VALUE: sm_scale must be finite and positive";
+        case SAGE_ERR_SCRATCH: return "SAGE_ERR_SCRATCH: the shape needs more scratch than the library's static buffer holds";
         default: return "SAGE_ERR_UNKNOWN";
     }
 }
@@ -105,6 +107,44 @@ int sage_smooth_quant_k(const void* k_f16, int8_t* k_i8, float* k_scale, float* 
                         int B, int H, int N, int D, int block_k, void* stream) {
     return smooth_quant_k_impl(k_f16, nullptr, nullptr, false, k_i8, k_scale, k_mean, workspace, workspace_bytes,
                                B, H, N, D, block_k, stream);
+}
+
+// ---- sage_smooth_quant_k for callers that cannot allocate: the partial column sums live in a
+// file-scope device array instead of a caller-supplied workspace.
+namespace {
+constexpr size_t SCRATCH_BYTES = SAGE_NOALLOC_SCRATCH_BYTES;
+constexpr int SCRATCH_MAX_DEVICES = 64;
+__device__ __align__(256) unsigned char scratch[SCRATCH_BYTES];
+// Every device holds its own copy of the array at its own address; `scratch` itself is only a
+// host-side handle and must never be handed to a kernel or a copy.
+void* scratch_addr[SCRATCH_MAX_DEVICES];
+std::mutex scratch_mutex;
+
+// Device address of this device's copy of `scratch` (looked up once per device), or null on error.
+void* scratch_on_current_device() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= SCRATCH_MAX_DEVICES) return nullptr;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (scratch_addr[dev] == nullptr) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        scratch_addr[dev] = p;
+    }
+    return scratch_addr[dev];
+}
+}  // namespace
+
+int sage_smooth_quant_k_noalloc(const void* k_f16, int8_t* k_i8, float* k_scale, float* k_mean,
+                                int B, int H, int N, int D, int block_k, void* stream) {
+    if (int e = check_shape(B, H, N, D)) return e;
+    const size_t need = sage_smooth_quant_k_workspace(B, H, N, D);
+    if (need > SCRATCH_BYTES) return SAGE_ERR_SCRATCH;
+    void* ws = nullptr;
+    if (need > 0) {
+        ws = scratch_on_current_device();
+        if (ws == nullptr) return SAGE_ERR_LAUNCH;
+    }
+    return smooth_quant_k_impl(k_f16, nullptr, nullptr, false, k_i8, k_scale, k_mean, ws, need, B, H, N, D, block_k, stream);
 }
 
 int sage_rope_smooth_quant_k(const void* k_f16, const float* rope_cos, const float* rope_sin,
