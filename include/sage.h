@@ -313,6 +313,13 @@ int sage_attn_qk_i32_debug(const int8_t* q_i8, const int8_t* k_i8, int32_t* s_i3
  *   kind 5  wavefronts 0-3 of a workgroup run kind 1's group, wavefronts 4-7 (the same SIMDs) 8 chunks;
  *           needs waves_per_simd = 2
  *   kind 6  kind 2's instructions with 16 chunks and 8 three-way maxima spread between them
+ *   kind 7  24 LDS reads of 16 bytes per lane (1 KB per wavefront each): the kernel's K^ operand reads
+ *   kind 8  48 transposing LDS reads of 8 bytes per lane: the kernel's V^T operand reads (24 KB per group)
+ *   kind 9  kind 6 with the A operand of every matrix instruction read from LDS three instructions
+ *           ahead of its use, as the attention kernel reads them
+ *   kind 10 16 of the 4x4x4 FP16 matrix instructions the kernel takes its row sums with
+ *   kind 11 4 x (4 FP16 32x32x16 + 2 of the 4x4x4): the P~V part of a step with its row sums
+ *   kind 12 4 x (4 FP16 32x32x16 + 1 FP16 16x16x32);  kind 13  4 x 5 FP16 32x32x16 (other ways to the row sums)
  *   data    in  1024 int32 of arbitrary (random) bits: the operands; 16-byte aligned
  *   out     out 4 uint64 per wavefront ([workgroups * 4 * waves_per_simd][4]): shader-clock ticks of the
  *           loop, constant-rate-counter ticks of the loop, a checksum, 0

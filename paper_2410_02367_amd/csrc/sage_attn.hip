@@ -9,7 +9,7 @@
 //   directly and bypass the register file.
 //   Scores are computed TRANSPOSED, S^T = K^ Q^^T, with the 32x32x32 INT8 matrix instruction: each
 //   lane then owns one query column and 16 keys per 32-key sub-tile, so
-//     - row max / row sum need one cross-lane step (lane <-> lane+32),
+//     - the row maximum needs one cross-lane step (lane <-> lane+32), the row sum none (see l_mfma),
 //     - the exponentiated scores are already in the register layout the FP16 32x32x16 instruction
 //       wants for its B operand (P~^T), and O^T = V^T P~^T accumulates with the rescale factor
 //       being a per-lane scalar.
@@ -39,7 +39,7 @@
 // Register files
 //   The matrix instructions are written as inline assembly so that the register file of every
 //   operand is chosen by hand: O^T (QS*DT*16 registers), the row sums, the resident Q^ operands
-//   and the ones operand are pinned in the accumulator file (AGPRs) -- only matrix instructions
+//   and the row-sum selector operand are pinned in the accumulator file (AGPRs) -- only matrix instructions
 //   touch them in the steady state, so there are no AGPR<->VGPR moves at all -- while scores, P~,
 //   LDS operands and staging data are ordinary variables in VGPRs.
 //   The O^T / row-sum statements name their accumulator as an INPUT and update that register
@@ -70,10 +70,10 @@
 //     finish_max(), raise_maximum());
 //   - the row maximum is taken on the raw accumulators with integer max;
 //   - P~ is packed to FP16 with the packed round-to-nearest-even convert; the row sum l comes from
-//     two small (4x4x4, quarter-length) matrix instructions per 16 keys with an all-ones operand,
-//     each adding four of a lane's own FP16 P~ values in fp32: l is exactly the sum of the FP16 P~
-//     that multiplies V, and costs no VALU issue slots.  (Dot-product instructions such as
-//     v_dot2c run on the matrix pipe as well, but block it for VALU work -- measured.)
+//     one 16x16x32 FP16 matrix instruction per 16 keys whose A operand selects, for every query, the
+//     contraction blocks that hold its keys (see l_mfma): l is exactly the sum of the FP16 P~ that
+//     multiplies V, and costs no VALU issue slot.  (Dot-product instructions such as v_dot2c run on the
+//     matrix pipe as well, but block it for VALU work -- measured.)
 #include "sage_internal.h"
 #include <type_traits>
 #include <utility>
@@ -163,13 +163,19 @@ __device__ __forceinline__ void qk_mfma_next(v16i& acc, const v4i& a, const v4i&
 __device__ __forceinline__ void pv_mfma(const v16f& acc, const v8h& a, const v8h& b) {
     asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : : "a"(acc), "v"(a), "v"(b));
 }
-// Row sums: the 4x4x4 instruction (16 independent 4x4 blocks, one per group of four lanes) with
-// an all-ones A operand leaves, in each of a lane's four result registers, the sum of the lane's
-// OWN four B values (checked on hardware) -- a per-lane fp32 sum of four FP16 numbers that costs
-// no VALU slot and a quarter of the matrix-pipe time of a 32x32x16 instruction.  acc += that sum;
+// Row sums on the matrix pipe: ONE 16x16x32 FP16 instruction per 16-key group.  Its B operand is the
+// group's P~^T operand as it stands (lane l: query l % 32, the 8 keys of half l / 32).  Read in the
+// 16x16x32 layout the same registers are "column l % 16, contraction block l / 16": blocks 0 and 2 hold
+// the two key halves of query l % 16, blocks 1 and 3 those of query 16 + l % 16.  The A operand `sel`
+// has ones in the blocks of the row's parity and zeros in the others (row i: blocks with the parity of
+// i), so result row i of column c is the complete 16-key sum of query c (i even) or 16 + c (i odd); a
+// lane's result registers 0 and 1 (rows 4 (l / 16) + 0, + 1 of column l % 16) are the row sums of the
+// queries l % 16 and 16 + l % 16, and the one that is the lane's own query is selected in the epilogue.
+// No VALU slot, no cross-lane step, 18 clocks of the matrix pipe in the stream of 32-clock
+// instructions (measured; two of the 4x4x4 instructions, which did this before, took 27).  acc += sums;
 // same in-place convention as pv_mfma.
-__device__ __forceinline__ void l_mfma(const v4f& acc, const v2i& ones, const v2i& b) {
-    asm volatile("v_mfma_f32_4x4x4_16b_f16 %0, %1, %2, %0" : : "a"(acc), "a"(ones), "v"(b));
+__device__ __forceinline__ void l_mfma(const v4f& acc, const v4i& sel, const v4i& b) {
+    asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : : "a"(acc), "a"(sel), "v"(b));
 }
 // One 16-byte-per-lane load from global memory straight into LDS: lane l lands at LDS byte address
 // lds_addr + 16*l (lds_addr wave-uniform).  Written as assembly because the compiler, which cannot
@@ -291,10 +297,9 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
         }
     }
     v16f acc_o[QS][DT];      // O^T accumulators
-    // Row sums l, accumulated on the matrix pipe.  A lane sums the P~ of its own 16 keys per
-    // 32-key block (the other 16 are with lane +-32: added in the epilogue); two accumulators take
-    // turns so that two row-sum instructions issued back to back do not depend on each other.
-    v4f acc_l[QS][2];
+    // Row sums l, accumulated on the matrix pipe (see l_mfma): registers 0 and 1 hold the sums of the
+    // queries lane % 16 and 16 + lane % 16 over all keys so far.
+    v4f acc_l[QS];
 #pragma unroll
     for (int qs = 0; qs < QS; ++qs) {
 #pragma unroll
@@ -303,14 +308,13 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
             for (int r = 0; r < 16; ++r) acc_o[qs][dt][r] = 0.0f;
             pin_a(acc_o[qs][dt]);
         }
-#pragma unroll
-        for (int e = 0; e < 2; ++e) {
-            acc_l[qs][e] = (v4f){0.0f, 0.0f, 0.0f, 0.0f};
-            pin_a(acc_l[qs][e]);
-        }
+        acc_l[qs] = (v4f){0.0f, 0.0f, 0.0f, 0.0f};
+        pin_a(acc_l[qs]);
     }
-    v2i ones2 = {0x3C003C00, 0x3C003C00};     // FP16 (1, 1) pairs
-    pin_a(ones2);
+    // selector operand of the row-sum instruction: FP16 ones in the contraction blocks of the row's parity
+    const int sel_word = (((lane >> 4) ^ lane) & 1) ? 0 : 0x3C003C00;
+    v4i sel = {sel_word, sel_word, sel_word, sel_word};
+    pin_a(sel);
     const float* __restrict__ ksc_bh = ksc + (size_t)bh * nbk + (k0 >> shift_k);
 
     // kv tiles visited by the workgroup (T) and by this wavefront (Tw <= T: tiles above the
@@ -479,8 +483,7 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
         });
         static_for<QS>([&](auto QSI) {
             constexpr int qs = IDX(QSI);
-            l_mfma(acc_l[qs][0], ones2, __builtin_shufflevector(pk[qs][s][u], pk[qs][s][u], 0, 1));
-            l_mfma(acc_l[qs][1], ones2, __builtin_shufflevector(pk[qs][s][u], pk[qs][s][u], 2, 3));
+            l_mfma(acc_l[qs], sel, pk[qs][s][u]);
         });
     };
 
@@ -620,8 +623,7 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
         finish_max();
 #pragma unroll
         for (int qs = 0; qs < QS; ++qs) {
-            refresh(acc_l[qs][0]);
-            refresh(acc_l[qs][1]);
+            refresh(acc_l[qs]);
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt) refresh(acc_o[qs][dt]);
         }
@@ -632,11 +634,8 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
                 m_new = __builtin_fmaf(-MAGIC_F, sc[qs], __builtin_fmaf(MAGIC_F, sc[qs], m_new));
             const float alpha = __builtin_amdgcn_exp2f(m_run[qs] - m_new);
             m_run[qs] = m_new;
-#pragma unroll
-            for (int e = 0; e < 2; ++e) {
-                acc_l[qs][e] *= alpha;
-                pin_a(acc_l[qs][e]);
-            }
+            acc_l[qs] *= alpha;        // the register of the lane's own query is the one that counts
+            pin_a(acc_l[qs]);
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt) {
 #pragma unroll
@@ -708,9 +707,7 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
         constexpr int grp_su = IDX(G);
         static_for<QS>([&](auto QSI) {
             constexpr int qs = IDX(QSI);
-            const v4i& p = pk[qs][grp_su >> 1][grp_su & 1];
-            l_mfma(acc_l[qs][0], ones2, __builtin_shufflevector(p, p, 0, 1));
-            l_mfma(acc_l[qs][1], ones2, __builtin_shufflevector(p, p, 2, 3));
+            l_mfma(acc_l[qs], sel, pk[qs][grp_su >> 1][grp_su & 1]);
         });
         __builtin_amdgcn_sched_barrier(0);
     };
@@ -914,12 +911,10 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
 #pragma unroll
     for (int qs = 0; qs < QS; ++qs) {
         const int q_row = qrow0 + 32 * qs + ql;
-        refresh(acc_l[qs][0]);
-        refresh(acc_l[qs][1]);
+        refresh(acc_l[qs]);
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) refresh(acc_o[qs][dt]);
-        const float l_half = acc_l[qs][0][0] + acc_l[qs][1][0];            // this lane's keys
-        const float l_row = l_half + as_f32(swap32i(as_i32(l_half)));       // + those of the lane 32 away
+        const float l_row = (lane & 16) ? acc_l[qs][1] : acc_l[qs][0];       // the lane's own query, all keys
         const float inv = 1.0f / l_row;
         if (q_row < Nq) {
             if (lse != nullptr && g == 0) lse[slab_o + q_row] = m_run[qs] + __builtin_amdgcn_logf(l_row);

@@ -21,6 +21,14 @@
 //                              (needs an even number of wavefronts per SIMD)
 //   kind 6  step-shaped        the attention step's whole mix in one stream: 8 INT8 + 16 FP16 matrix
 //                              instructions, each followed by its share of the 16 chunks + 8 3-way maxima
+//   kind 7  LDS reads, 16 B    24 x ds_read_b128 per group (1 KB per wavefront each: a K^ operand), no other work
+//   kind 8  LDS reads, transp. 48 x ds_read_b64_tr_b16 per group (two make one 1 KB V^T operand)
+//   kind 9  step + operands    kind 6 with every matrix instruction's A operand read from LDS three
+//                              instructions ahead, as the attention kernel does (8 x b128, 32 x tr_b16)
+//   kind 10 small matrix instr 16 x v_mfma_f32_4x4x4_16b_f16 per group (the kernel's row-sum instruction)
+//   kind 11 P~V with row sums  4 x (4 FP16 32x32x16 + 2 of the 4x4x4) per group, as the kernel issues them
+//   kind 12 ... 16x16x32       4 x (4 FP16 32x32x16 + 1 v_mfma_f32_16x16x32_f16) per group
+//   kind 13 ... 32x32x16       4 x (4 + 1 FP16 32x32x16) per group
 #include "sage_internal.h"
 
 namespace sage {
@@ -35,6 +43,15 @@ __device__ __forceinline__ void mb_i8(mb_v16i& acc, const mb_v4i& a, const mb_v4
 }
 __device__ __forceinline__ void mb_f16(mb_v16f& acc, const mb_v8h& a, const mb_v8h& b) {
     asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+}
+
+typedef float mb_v4f __attribute__((ext_vector_type(4)));
+typedef int mb_v2i __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void mb_small(mb_v4f& acc, const mb_v2i& a, const mb_v2i& b) {
+    asm volatile("v_mfma_f32_4x4x4_16b_f16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ void mb_mid(mb_v4f& acc, const mb_v8h& a, const mb_v8h& b) {
+    asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
 }
 
 // The softmax of two scores, x -> FP16(exp2(x * sc + bias)), cut into the three stages the attention
@@ -60,9 +77,31 @@ struct SoftmaxPipe {
     }
 };
 
+typedef short mb_v4s __attribute__((ext_vector_type(4)));
+#define MB_LDS(T, p) ((__attribute__((address_space(3))) T*)(p))
+
+// LDS byte offsets of the attention kernel's operand reads at D = 128 (64-key tiles, rows of 128 / 256
+// bytes, 16-byte chunks XOR-swizzled by the row): K^ operand of 32-key half `half`, contraction step ks;
+// first of the two 8-byte transposing reads of the V^T operand of 16-key group grp_su, channel block dt
+// (the second lies 8 rows = 2048 bytes further).
+__device__ __forceinline__ int k_operand_at(int lane, int half, int ks) {
+    const int ql = lane & 31, g = lane >> 5;
+    return half * 4096 + ql * 128 + (((2 * ks + g) ^ ((ql >> 1) & 7)) << 4);
+}
+__device__ __forceinline__ int v_operand_at(int lane, int grp_su, int dt) {
+    const int grp = lane >> 4, li = lane & 15, v_row = 4 * (grp >> 1) + (li >> 2);
+    const int chunk = (4 * dt + 2 * (grp & 1) + ((li & 3) >> 1)) ^ (4 * (v_row & 3));
+    return 16 * grp_su * 256 + v_row * 256 + chunk * 16 + (li & 1) * 8;
+}
+
 template <int KIND>
 __global__ void __launch_bounds__(512) microbench_kernel(const int* __restrict__ data, unsigned long long* __restrict__ out,
                                                          int iters) {
+    // 48 KB: a 64-key K^ tile (8 KB) and V tile (16 KB) of the attention kernel at D = 128, twice
+    __shared__ __attribute__((aligned(1024))) unsigned char tile[KIND >= 7 && KIND <= 9 ? 49152 : 16];
+    if constexpr (KIND >= 7 && KIND <= 9) {
+        for (int i = threadIdx.x; i < 49152 / 4; i += blockDim.x) ((int*)tile)[i] = data[i & 1023] & 0x3BFF3BFF;
+    }
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int nwaves = blockDim.x >> 6;
@@ -88,6 +127,8 @@ __global__ void __launch_bounds__(512) microbench_kernel(const int* __restrict__
 #pragma unroll
     for (int n = 0; n < 3; ++n) { sp.xs[n][0] = -0.25f * (float)(lane & 7); sp.xs[n][1] = -0.125f * (float)(lane & 15); }
     sp.in0 = -0.5f - (float)(lane & 3); sp.in1 = -0.75f; sp.sc = 1.001f; sp.bias = -0.5f;
+    mb_v4f cl[2] = {{0.0f, 0.0f, 0.0f, 0.0f}, {0.0f, 0.0f, 0.0f, 0.0f}};
+    const mb_v2i one2 = {0x3C003C00, 0x3C003C00}, bl = {ah[0], ah[1]}, bl2 = {ah[2], ah[3]};
     int mx = lane, mu = lane ^ 5, mv = 63 - lane;       // operands of the three-way maxima (never matrix results)
 
     __syncthreads();
@@ -128,6 +169,63 @@ __global__ void __launch_bounds__(512) microbench_kernel(const int* __restrict__
 #pragma unroll
                 for (int n = 0; n < 8; ++n) mb_f16(cf[n & 3], af, bf);
             }
+        } else if constexpr (KIND == 10) {
+#pragma unroll
+            for (int n = 0; n < 16; ++n) mb_small(cl[n & 1], one2, n & 1 ? bl2 : bl);
+        } else if constexpr (KIND >= 11 && KIND <= 13) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+#pragma unroll
+                for (int n = 0; n < 4; ++n) mb_f16(cf[n], af, bf);
+                if constexpr (KIND == 11) { mb_small(cl[0], one2, bl); mb_small(cl[1], one2, bl2); }
+                else if constexpr (KIND == 12) mb_mid(cl[g & 1], af, bf);
+                else mb_f16(cf[g & 3], af, bf);
+            }
+        } else if constexpr (KIND == 7) {
+            // the K^ operand reads of the attention kernel: 32-key half h, contraction step ks -> row lane % 32,
+            // 16-byte chunk 2 ks + lane / 32, swizzled by the row
+            mb_v4i r[4];
+#pragma unroll
+            for (int n = 0; n < 24; ++n) {
+                r[n & 3] = *(const mb_v4i*)(tile + k_operand_at(lane, (n >> 2) & 1, n & 3) + (n >> 3) * 8192);
+                asm volatile("" : : "v"(r[n & 3]));
+            }
+        } else if constexpr (KIND == 8) {
+            // the V^T operand reads: two transposing 8-byte reads per operand
+            mb_v4s r[4];
+#pragma unroll
+            for (int n = 0; n < 24; ++n) {
+                const int at = 16384 + v_operand_at(lane, (n >> 2) & 3, n & 3) + (n >> 4) * 8192;      // all inside the 48 KB
+                r[n & 3] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(MB_LDS(mb_v4s, tile + at));
+                asm volatile("" : : "v"(r[n & 3]));
+                r[(n + 2) & 3] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(MB_LDS(mb_v4s, tile + at + 2048));
+                asm volatile("" : : "v"(r[(n + 2) & 3]));
+            }
+        } else if constexpr (KIND == 9) {
+            mb_v4i ring[4];
+            auto fetch = [&](int n) {          // operand of matrix instruction n of the group
+                if (n % 3 == 2) {
+                    const int q = n / 3;                             // index among the 8 INT8 instructions
+                    ring[n & 3] = *(const mb_v4i*)(tile + k_operand_at(lane, q >> 2, q & 3));
+                } else {
+                    const int m = n - n / 3;                         // index among the 16 FP16 instructions
+                    const int at = 16384 + v_operand_at(lane, m >> 2, m & 3);
+                    mb_v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(MB_LDS(mb_v4s, tile + at));
+                    mb_v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(MB_LDS(mb_v4s, tile + at + 2048));
+                    ring[n & 3] = __builtin_bit_cast(mb_v4i, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+                }
+            };
+            if (it == 0) { fetch(0); fetch(1); fetch(2); }
+#pragma unroll
+            for (int n = 0; n < 24; ++n) {
+                if (n % 3 == 2) mb_i8(ci[n & 3], ring[n & 3], b8);
+                else mb_f16(cf[n & 3], __builtin_bit_cast(mb_v8h, ring[n & 3]), bf);
+                fetch((n + 3) % 24);
+                __builtin_amdgcn_sched_barrier(0);
+                if (n % 3 != 2) sp.tick(n);
+                else { asm volatile("" : "+v"(mu), "+v"(mv)); mx = max(max(mx, mu), mv); asm volatile("" : "+v"(mx)); }
+                __builtin_amdgcn_sched_barrier(0);
+            }
         } else {
             // 24 matrix instructions; chunks behind 16 of them, three-way integer maxima behind the other 8
 #pragma unroll
@@ -145,7 +243,8 @@ __global__ void __launch_bounds__(512) microbench_kernel(const int* __restrict__
     // checksum (keeps every accumulator alive); 12 wait states after the last matrix instruction
     asm volatile("s_nop 11" : "+v"(ci[0]), "+v"(ci[1]), "+v"(ci[2]), "+v"(ci[3]));
     asm volatile("s_nop 11" : "+v"(cf[0]), "+v"(cf[1]), "+v"(cf[2]), "+v"(cf[3]));
-    float sum = 0.0f;
+    asm volatile("s_nop 11" : "+v"(cl[0]), "+v"(cl[1]));
+    float sum = cl[0][0] + cl[1][0] + cl[0][3] + cl[1][2];
     int isum = mx;
 #pragma unroll
     for (int n = 0; n < 4; ++n) {
@@ -174,6 +273,13 @@ hipError_t launch_microbench(int kind, int waves_per_simd, int workgroups, int i
         case 4: microbench_kernel<4><<<workgroups, threads, 0, st>>>(data, out, iters); break;
         case 5: microbench_kernel<5><<<workgroups, threads, 0, st>>>(data, out, iters); break;
         case 6: microbench_kernel<6><<<workgroups, threads, 0, st>>>(data, out, iters); break;
+        case 7: microbench_kernel<7><<<workgroups, threads, 0, st>>>(data, out, iters); break;
+        case 8: microbench_kernel<8><<<workgroups, threads, 0, st>>>(data, out, iters); break;
+        case 9: microbench_kernel<9><<<workgroups, threads, 0, st>>>(data, out, iters); break;
+        case 10: microbench_kernel<10><<<workgroups, threads, 0, st>>>(data, out, iters); break;
+        case 11: microbench_kernel<11><<<workgroups, threads, 0, st>>>(data, out, iters); break;
+        case 12: microbench_kernel<12><<<workgroups, threads, 0, st>>>(data, out, iters); break;
+        case 13: microbench_kernel<13><<<workgroups, threads, 0, st>>>(data, out, iters); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
