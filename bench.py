@@ -483,6 +483,20 @@ def main():
     _, int8_measured, _, int8_ghz, _ = run_probe(sage, torch, probe_data, 0, 2, 0.05, workgroups=256)
     mix_kind = 0 if pv_int8 else 2
     _, mix_measured, _, mix_ghz, _ = run_probe(sage, torch, probe_data, mix_kind, 2, 0.05, workgroups=256)
+    # what a plain device-to-device copy of 1 GiB reaches on this GPU (read + written bytes per second): the
+    # practical HBM rate the pre-pass is compared with, beside the published peak
+    cx = torch.ones(1 << 28, dtype=torch.int32, device="cuda")
+    cy = torch.empty_like(cx)
+    copy_ms = []
+    for _ in range(4):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        cy.copy_(cx)
+        e1.record()
+        torch.cuda.synchronize()
+        copy_ms.append(e0.elapsed_time(e1))
+    copy_gbs = 2.0 * cx.numel() * 4 / (min(copy_ms[1:]) * 1e-3) / 1e9
+    del cx, cy
 
     ops = w.ops
     value = ops / (ms_per_step * 1e-3) / 1e12
@@ -540,6 +554,8 @@ def main():
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": (13.0 if pv_int8 else 8.0) * B * H * N * D / (pre_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "measured_copy_gbs": copy_gbs,
+            "frac_of_measured_copy": (13.0 if pv_int8 else 8.0) * B * H * N * D / (pre_ms * 1e-3) / 1e9 / copy_gbs,
             "note": "algorithmic bytes: Q 2 read + 1 written, K 2 + 2 read (mean is a global dependency) + 1 written "
                     "= 8 B per element pair" + (", V 2 + 2 read (the channel maximum is a global dependency) + 1 written = 13"
                                                 if pv_int8 else "")

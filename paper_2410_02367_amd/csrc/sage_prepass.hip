@@ -57,11 +57,11 @@ __device__ __forceinline__ h8 load_row8(const _Float16* __restrict__ row, int c8
 // p * chunk .. of its slab and leaves the D sums as 64-bit integers at part[(bh * P + p) * D ..];
 // the quantizer kernels add the P partial sums of their slab themselves (integer addition: any order
 // gives the same bits).  No atomics, nothing to clear beforehand, every word of the result written.
-// `chunk` is a multiple of BATCH * RG rows.  A thread owns one 16-byte column group of every RG-th row
+// A thread owns one 16-byte column group of every RG-th row
 // and fetches BATCH rows at a time, all loads issued before the first is used (rows past the end are
 // fetched from the last row and not added); its two 32-bit partial sums per column (integer part
 // and 24-bit fraction) are folded into 64-bit ones after every batch, long before they could overflow
-// (8 * 65504 and 8 * 2^24).
+// (8 * 65504 and 8 * 2^24 stay far below 2^31).
 template <int D, bool ROPE>
 __global__ void __launch_bounds__(256) k_colsum_kernel(const _Float16* __restrict__ k,
                                                        long long* __restrict__ part_out, int N, int chunk,
