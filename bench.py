@@ -46,7 +46,7 @@ def profiled_traffic(workload: str, pv_int8: bool):
 # Probes of sage_microbench (include/sage.h): operations per instruction group
 PROBE_OPS = {0: 8 * 65536.0, 1: 8 * 32768.0, 2: 8 * 65536.0 + 16 * 32768.0, 4: 8 * 32768.0, 5: 8 * 32768.0,
              6: 8 * 65536.0 + 16 * 32768.0, 9: 8 * 65536.0 + 16 * 32768.0,
-             11: 16 * 32768.0, 12: 16 * 32768.0, 13: 16 * 32768.0}      # kinds 11 to 13: the 16 P~V instructions only
+             11: 16 * 32768.0, 12: 16 * 32768.0, 13: 16 * 32768.0, 14: 8 * 65536.0}      # kinds 11 to 13: the 16 P~V instructions only
 PROBE_NAMES = {0: "INT8 32x32x32 stream", 1: "FP16 32x32x16 stream", 2: "attention mix: 8 INT8 + 16 FP16, matrix only",
                3: "softmax chunks only (24 per group)", 4: "FP16 matrix instruction + softmax chunk, one stream",
                5: "FP16 matrix stream and softmax stream on separate wavefronts of a SIMD",
@@ -57,9 +57,10 @@ PROBE_NAMES = {0: "INT8 32x32x32 stream", 1: "FP16 32x32x16 stream", 2: "attenti
                10: "16 x 4x4x4 FP16 matrix instruction (the row-sum instruction)",
                11: "4 x (4 FP16 32x32x16 + 2 of the 4x4x4): P~V with row sums",
                12: "4 x (4 FP16 32x32x16 + 1 FP16 16x16x32)",
-               13: "4 x (4 + 1 FP16 32x32x16)"}
+               13: "4 x (4 + 1 FP16 32x32x16)",
+               14: "INT8 32x32x32 stream, one accumulator (dependent chain)"}
 # matrix-pipe clocks per group (32 per 32x32 instruction) -- what a fully busy pipe needs
-PROBE_PIPE_CLOCKS = {0: 256, 1: 256, 2: 768, 4: 256, 5: 256, 6: 768, 9: 768, 11: 512, 12: 512, 13: 512}
+PROBE_PIPE_CLOCKS = {0: 256, 1: 256, 2: 768, 4: 256, 5: 256, 6: 768, 9: 768, 11: 512, 12: 512, 13: 512, 14: 256}
 # LDS bytes a wavefront reads per group (kinds 7 to 9)
 PROBE_LDS_BYTES = {7: 24 * 1024, 8: 24 * 1024, 9: 24 * 1024}
 
@@ -103,10 +104,10 @@ def microbench(seconds: float):
     print(f"instruction-stream probes, about {seconds:g} s per launch, random operand bits; "
           f"nominal peaks: INT8 {INT8_PEAK_TOPS:.0f} TOPS, FP16 {FP16_PEAK_TFLOPS:.0f} TFLOP/s at 2.4 GHz")
     print("%-4s %-78s %5s %9s %9s %8s %10s %9s %8s" % ("kind", "probe", "waves", "ms", "TOPS", "% peak", "ticks/grp", "pipe busy", "GHz"))
-    for kind, waves in ((0, 1), (0, 2), (1, 1), (1, 2), (2, 1), (2, 2), (3, 1), (3, 2), (4, 1), (4, 2), (5, 2), (6, 1), (6, 2), (7, 1), (7, 2), (8, 1), (8, 2), (9, 1), (9, 2), (10, 1), (11, 1), (11, 2), (12, 1), (12, 2), (13, 1)):
+    for kind, waves in ((0, 1), (0, 2), (1, 1), (1, 2), (2, 1), (2, 2), (3, 1), (3, 2), (4, 1), (4, 2), (5, 2), (6, 1), (6, 2), (7, 1), (7, 2), (8, 1), (8, 2), (9, 1), (9, 2), (10, 1), (11, 1), (11, 2), (12, 1), (12, 2), (13, 1), (14, 1), (14, 2)):
         # 256 workgroups: one per compute unit, `waves` wavefronts per SIMD
         ms, tops, ticks, ghz, iters = run_probe(sage, torch, data, kind, waves, seconds, workgroups=256)
-        peak = {0: INT8_PEAK_TOPS, 1: FP16_PEAK_TFLOPS, 4: FP16_PEAK_TFLOPS, 5: FP16_PEAK_TFLOPS, 11: FP16_PEAK_TFLOPS,
+        peak = {0: INT8_PEAK_TOPS, 14: INT8_PEAK_TOPS, 1: FP16_PEAK_TFLOPS, 4: FP16_PEAK_TFLOPS, 5: FP16_PEAK_TFLOPS, 11: FP16_PEAK_TFLOPS,
                 12: FP16_PEAK_TFLOPS, 13: FP16_PEAK_TFLOPS}.get(kind, INT8_PEAK_TOPS)
         busy = PROBE_PIPE_CLOCKS[kind] * (1 if kind == 5 else waves) / ticks if kind in PROBE_PIPE_CLOCKS else float("nan")
         lds = ""

@@ -320,6 +320,7 @@ int sage_attn_qk_i32_debug(const int8_t* q_i8, const int8_t* k_i8, int32_t* s_i3
  *   kind 10 16 of the 4x4x4 FP16 matrix instructions the kernel takes its row sums with
  *   kind 11 4 x (4 FP16 32x32x16 + 2 of the 4x4x4): the P~V part of a step with its row sums
  *   kind 12 4 x (4 FP16 32x32x16 + 1 FP16 16x16x32);  kind 13  4 x 5 FP16 32x32x16 (other ways to the row sums)
+ *   kind 14 kind 0 with all 8 instructions accumulating into one register block (a dependent chain)
  *   data    in  1024 int32 of arbitrary (random) bits: the operands; 16-byte aligned
  *   out     out 4 uint64 per wavefront ([workgroups * 4 * waves_per_simd][4]): shader-clock ticks of the
  *           loop, constant-rate-counter ticks of the loop, a checksum, 0

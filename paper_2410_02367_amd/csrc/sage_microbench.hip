@@ -29,6 +29,8 @@
 //   kind 11 P~V with row sums  4 x (4 FP16 32x32x16 + 2 of the 4x4x4) per group, as the kernel issues them
 //   kind 12 ... 16x16x32       4 x (4 FP16 32x32x16 + 1 v_mfma_f32_16x16x32_f16) per group
 //   kind 13 ... 32x32x16       4 x (4 + 1 FP16 32x32x16) per group
+//   kind 14 dependent chain    8 x INT8 32x32x32 into ONE accumulator (each instruction's C is the one before's D),
+//                              as the four contraction steps of a K^ Q^^T block follow each other
 #include "sage_internal.h"
 
 namespace sage {
@@ -169,6 +171,9 @@ __global__ void __launch_bounds__(512) microbench_kernel(const int* __restrict__
 #pragma unroll
                 for (int n = 0; n < 8; ++n) mb_f16(cf[n & 3], af, bf);
             }
+        } else if constexpr (KIND == 14) {
+#pragma unroll
+            for (int n = 0; n < 8; ++n) mb_i8(ci[0], a8, b8);
         } else if constexpr (KIND == 10) {
 #pragma unroll
             for (int n = 0; n < 16; ++n) mb_small(cl[n & 1], one2, n & 1 ? bl2 : bl);
@@ -280,6 +285,7 @@ hipError_t launch_microbench(int kind, int waves_per_simd, int workgroups, int i
         case 11: microbench_kernel<11><<<workgroups, threads, 0, st>>>(data, out, iters); break;
         case 12: microbench_kernel<12><<<workgroups, threads, 0, st>>>(data, out, iters); break;
         case 13: microbench_kernel<13><<<workgroups, threads, 0, st>>>(data, out, iters); break;
+        case 14: microbench_kernel<14><<<workgroups, threads, 0, st>>>(data, out, iters); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
