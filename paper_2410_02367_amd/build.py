@@ -245,14 +245,26 @@ def check_pv8_asm(text: str) -> list:
     return problems
 
 
+def check_no_spills(text: str) -> list:
+    """The pre-pass kernels hold a quantization block in registers; a register spill would turn the
+    one pass over memory they are built around into several.  Returns the kernels that touch scratch."""
+    import re
+    problems = []
+    for m in re.finditer(r"^(_ZN4sage\w+):.*?^\.Lfunc_end\d+:", text, re.S | re.M):
+        if "scratch_" in m.group(0):
+            problems.append(f"{m.group(1)}: scratch access (register spill)")
+    return problems
+
+
 def verify_attention_isa(extra=()) -> None:
-    """Compiles the attention sources to assembly and raises RuntimeError if check_attention_asm() or
-    check_pv8_asm() objects."""
+    """Compiles the kernel sources to assembly and raises RuntimeError if check_attention_asm(),
+    check_pv8_asm() or check_no_spills() objects."""
     import tempfile
     flags = [f for f in HIPCC_FLAGS if f not in ("-shared", "-fPIC")]
     problems = []
     with tempfile.TemporaryDirectory() as tmp:
-        for src, check in (("sage_attn.hip", check_attention_asm), ("sage_attn_pv8.hip", check_pv8_asm)):
+        for src, check in (("sage_attn.hip", check_attention_asm), ("sage_attn_pv8.hip", check_pv8_asm),
+                           ("sage_prepass.hip", check_no_spills), ("sage_prepass_v.hip", check_no_spills)):
             out = os.path.join(tmp, src + ".s")
             cmd = [hipcc(), *flags, *extra, "-S", "--cuda-device-only", "-o", out, os.path.join(CSRC, src)]
             res = subprocess.run(cmd, capture_output=True, text=True)

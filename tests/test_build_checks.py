@@ -124,3 +124,34 @@ def test_pv8_scratch_and_compiler_use_of_m0_are_reported():
     bad = PV8_CLEAN.replace("\ts_endpgm\n", "\tscratch_load_dword v1, off, off\n\ts_mov_b32 m0, s9\n\ts_endpgm\n")
     problems = check_pv8_asm(fake_pv8(bad))
     assert any("scratch access" in p for p in problems) and any("use of m0" in p for p in problems)
+
+
+def test_spill_check_names_the_kernel_that_touches_scratch():
+    from paper_2410_02367_amd.build import check_no_spills
+    clean = "_ZN4sage15k_colsum_kernelILi64EEEv:\n\tv_add_u32 v0, v1, v2\n\ts_endpgm\n.Lfunc_end0:\n"
+    assert check_no_spills(clean) == []
+    spilling = clean.replace("\tv_add_u32 v0, v1, v2\n", "\tscratch_store_dword off, v3, off offset:4\n")
+    problems = check_no_spills(clean + spilling.replace("k_colsum", "k_small").replace("func_end0", "func_end1"))
+    assert len(problems) == 1 and "k_small" in problems[0]
+
+
+def test_source_hash_guard_tells_a_foreign_binary_from_ours(tmp_path):
+    """The library carries the hash of the sources it was built from; a file without the marker, or with
+    another hash, is not ours."""
+    from paper_2410_02367_amd import build
+    h = build.source_hash()
+    assert len(h) == 64 and h == build.source_hash()
+    good = tmp_path / "good.so"
+    good.write_bytes(b"\x7fELF junk " + build.HASH_MARKER + h.encode() + b"\0 more")
+    assert build.built_hash(str(good)) == h
+    other = tmp_path / "other.so"
+    other.write_bytes(b"\x7fELF junk " + build.HASH_MARKER + (b"0" * 64) + b"\0")
+    assert build.built_hash(str(other)) == "0" * 64 != h
+    assert build.built_hash(str(tmp_path / "missing.so")) is None
+    bare = tmp_path / "bare.so"
+    bare.write_bytes(b"\x7fELF no marker here")
+    assert build.built_hash(str(bare)) is None
+    # the library in the tree belongs to the sources in the tree (load() would rebuild or refuse otherwise)
+    from paper_2410_02367_amd import binding
+    binding.load()
+    assert not build.is_stale() and binding.sage_source_hash() == h

@@ -29,6 +29,9 @@ SMALL = [
     si.custom("one_past_a_tile", 1, 2, 257, 128, True, 128, 64, seed=si.BASE_SEED + 22),
     # 512 tokens is the last size whose K pre-pass runs as a single launch, 513 the first that does not
     si.custom("single_launch_limit", 1, 3, 513, 64, False, 128, 64, seed=si.BASE_SEED + 23),
+    si.custom("single_launch_blocks_128", 2, 2, 500, 128, False, 128, 128, seed=si.BASE_SEED + 25),
+    si.custom("two_launch_blocks_128", 1, 2, 2049, 128, True, 128, 128, seed=si.BASE_SEED + 24),
+    si.custom("blocks_32", 1, 2, 700, 64, True, 32, 64, seed=si.BASE_SEED + 26),
 ]
 
 

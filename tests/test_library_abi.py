@@ -175,3 +175,17 @@ def test_split_call_validates_and_its_chunk_plan_keeps_its_promises(lib):
         if n > 1 and req > 0:        # the chunk length follows from the requested count
             chunk = 128 * -(-Nkv // (128 * req))
             assert (n - 1) * chunk <= (Nkv - Nq if causal else Nkv - 1), (Nq, Nkv, causal, req, n)
+
+
+def test_microbench_call_validates_its_arguments(lib):
+    good = ctypes.c_void_p(0x1000)
+    odd = ctypes.c_void_p(0x1004)
+    assert lib.sage_microbench(0, 1, 256, 10, None, good, None) == 1
+    assert lib.sage_microbench(99, 1, 256, 10, good, good, None) == 3
+    assert lib.sage_microbench(0, 3, 256, 10, good, good, None) == 3
+    assert lib.sage_microbench(5, 1, 256, 10, good, good, None) == 3       # the split probe needs two wavefronts per SIMD
+    assert lib.sage_microbench(0, 1, 0, 10, good, good, None) == 2
+    assert lib.sage_microbench(0, 1, 256, 0, good, good, None) == 2
+    assert lib.sage_microbench(0, 1, 256, 10, odd, good, None) == 5
+    assert lib.sage_default_sm_scale(64) == 0.125 and lib.sage_default_sm_scale(0) == 0.0
+    assert abs(lib.sage_default_sm_scale(128) - 128 ** -0.5) < 1e-8
