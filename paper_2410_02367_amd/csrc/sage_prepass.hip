@@ -57,11 +57,8 @@ __device__ __forceinline__ h8 load_row8(const _Float16* __restrict__ row, int c8
 // p * chunk .. of its slab and leaves the D sums as 64-bit integers at part[(bh * P + p) * D ..];
 // the quantizer kernels add the P partial sums of their slab themselves (integer addition: any order
 // gives the same bits).  No atomics, nothing to clear beforehand, every word of the result written.
-// A thread owns one 16-byte column group of every RG-th row
-// and fetches BATCH rows at a time, all loads issued before the first is used (rows past the end are
-// fetched from the last row and not added); its two 32-bit partial sums per column (integer part
-// and 24-bit fraction) are folded into 64-bit ones after every batch, long before they could overflow
-// (8 * 65504 and 8 * 2^24 stay far below 2^31).
+// A thread owns one 16-byte column group of every RG-th row and fetches BATCH rows at a time, all loads
+// issued before the first is used (rows past the end are fetched from the last row and not added).
 template <int D, bool ROPE>
 __global__ void __launch_bounds__(256) k_colsum_kernel(const _Float16* __restrict__ k,
                                                        long long* __restrict__ part_out, int N, int chunk,
@@ -75,34 +72,53 @@ __global__ void __launch_bounds__(256) k_colsum_kernel(const _Float16* __restric
     const int row_end = row_begin + chunk < N ? row_begin + chunk : N;
     const _Float16* base = k + ((size_t)bh * N) * D;
 
-    long long acc[8];
+    // A thread's partial sums are carried in fp64: every fp16 value is a multiple of 2^-24 below 2^16 in
+    // magnitude, a thread adds at most 2^13 of them (chunk <= 2^17 rows, RG >= 16 row groups), so every
+    // intermediate sum is a multiple of 2^-24 below 2^29 -- 53 bits, exact in fp64.  Three VALU
+    // instructions per element (two conversions, one addition) instead of eight for an integer split,
+    // which is what lets this kernel run at the memory rate.
+    static_assert(RG >= 16, "at most 2^13 rows per thread in a chunk of 2^17");
+    double acc_d[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) acc[e] = 0;
-    for (int r0 = row_begin + rg; r0 < row_end; r0 += BATCH * RG) {
+    for (int e = 0; e < 8; ++e) acc_d[e] = 0.0;
+    // whole batches first (no row needs a check: every chunk but a slab's last is whole batches), then
+    // at most one ragged batch whose rows past the end are fetched from the last row and not added
+    const int whole = row_begin + (row_end - row_begin) / (BATCH * RG) * (BATCH * RG);
+    for (int r0 = row_begin + rg; r0 < whole; r0 += BATCH * RG) {
         h8 x[BATCH];
 #pragma unroll
         for (int i = 0; i < BATCH; ++i) {
             const int r = r0 + i * RG;
-            const int rc = r < N ? r : N - 1;
-            x[i] = load_row8<D, ROPE>(base + (size_t)rc * D, c8, cs + (size_t)rc * (D / 2), sn + (size_t)rc * (D / 2));
+            x[i] = load_row8<D, ROPE>(base + (size_t)r * D, c8, cs + (size_t)r * (D / 2), sn + (size_t)r * (D / 2));
         }
-        int acc_hi[8], acc_lo[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) { acc_hi[e] = 0; acc_lo[e] = 0; }
+        for (int i = 0; i < BATCH; ++i)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc_d[e] += (double)(float)x[i][e];
+    }
+    if (whole < row_end) {
+        h8 x[BATCH];
 #pragma unroll
         for (int i = 0; i < BATCH; ++i) {
-            const bool live = r0 + i * RG < row_end;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const float f = (float)x[i][e];
-                const float hi = __builtin_truncf(f);          // integer part, |hi| <= 65504
-                const float lo = f - hi;                       // exact; a multiple of 2^-24 below 1
-                acc_hi[e] += live ? (int)hi : 0;
-                acc_lo[e] += live ? (int)(lo * 16777216.0f) : 0;    // exact integer below 2^24
-            }
+            const int r = whole + rg + i * RG;
+            const int rc = r < row_end ? r : row_end - 1;
+            x[i] = load_row8<D, ROPE>(base + (size_t)rc * D, c8, cs + (size_t)rc * (D / 2), sn + (size_t)rc * (D / 2));
         }
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc[e] += (long long)acc_hi[e] * 16777216ll + (long long)acc_lo[e];
+        for (int i = 0; i < BATCH; ++i) {
+            const double live = whole + rg + i * RG < row_end ? 1.0 : 0.0;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc_d[e] += live * (double)(float)x[i][e];
+        }
+    }
+    // exact conversion to a count of 2^-24 units: |v| < 2^53 is split into a 27-bit and a 26-bit part
+    long long acc[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const double v = acc_d[e] * 16777216.0;
+        const double hi = __builtin_trunc(v * 0x1p-26);
+        const double lo = v - hi * 0x1p26;
+        acc[e] = (long long)(int)hi * (1ll << 26) + (long long)(int)lo;
     }
     __shared__ long long part[RG][D];
 #pragma unroll
