@@ -46,6 +46,7 @@ def profiled_traffic(workload: str, pv_int8: bool):
 # Probes of sage_microbench (include/sage.h): operations per instruction group
 PROBE_OPS = {0: 8 * 65536.0, 1: 8 * 32768.0, 2: 8 * 65536.0 + 16 * 32768.0, 4: 8 * 32768.0, 5: 8 * 32768.0,
              6: 8 * 65536.0 + 16 * 32768.0, 9: 8 * 65536.0 + 16 * 32768.0,
+             15: 8 * 65536.0 + 16 * 32768.0, 16: 8 * 65536.0 + 16 * 32768.0,
              11: 16 * 32768.0, 12: 16 * 32768.0, 13: 16 * 32768.0, 14: 8 * 65536.0}      # kinds 11 to 13: the 16 P~V instructions only
 PROBE_NAMES = {0: "INT8 32x32x32 stream", 1: "FP16 32x32x16 stream", 2: "attention mix: 8 INT8 + 16 FP16, matrix only",
                3: "softmax chunks only (24 per group)", 4: "FP16 matrix instruction + softmax chunk, one stream",
@@ -58,11 +59,13 @@ PROBE_NAMES = {0: "INT8 32x32x32 stream", 1: "FP16 32x32x16 stream", 2: "attenti
                11: "4 x (4 FP16 32x32x16 + 2 of the 4x4x4): P~V with row sums",
                12: "4 x (4 FP16 32x32x16 + 1 FP16 16x16x32)",
                13: "4 x (4 + 1 FP16 32x32x16)",
-               14: "INT8 32x32x32 stream, one accumulator (dependent chain)"}
+               14: "INT8 32x32x32 stream, one accumulator (dependent chain)",
+               15: "attention step in the kernel's order: maxima, chunks behind 16 instructions, row sums",
+               16: "kind 15 with the chunks spread over 20 instructions"}
 # matrix-pipe clocks per group (32 per 32x32 instruction) -- what a fully busy pipe needs
-PROBE_PIPE_CLOCKS = {0: 256, 1: 256, 2: 768, 4: 256, 5: 256, 6: 768, 9: 768, 11: 512, 12: 512, 13: 512, 14: 256}
+PROBE_PIPE_CLOCKS = {0: 256, 1: 256, 2: 768, 4: 256, 5: 256, 6: 768, 9: 768, 11: 512, 12: 512, 13: 512, 14: 256, 15: 768, 16: 768}
 # LDS bytes a wavefront reads per group (kinds 7 to 9)
-PROBE_LDS_BYTES = {7: 24 * 1024, 8: 24 * 1024, 9: 24 * 1024}
+PROBE_LDS_BYTES = {7: 24 * 1024, 8: 24 * 1024, 9: 24 * 1024, 15: 24 * 1024, 16: 24 * 1024}
 
 
 def run_probe(sage, torch, data, kind, waves, seconds, workgroups=1024):
@@ -104,7 +107,7 @@ def microbench(seconds: float):
     print(f"instruction-stream probes, about {seconds:g} s per launch, random operand bits; "
           f"nominal peaks: INT8 {INT8_PEAK_TOPS:.0f} TOPS, FP16 {FP16_PEAK_TFLOPS:.0f} TFLOP/s at 2.4 GHz")
     print("%-4s %-78s %5s %9s %9s %8s %10s %9s %8s" % ("kind", "probe", "waves", "ms", "TOPS", "% peak", "ticks/grp", "pipe busy", "GHz"))
-    for kind, waves in ((0, 1), (0, 2), (1, 1), (1, 2), (2, 1), (2, 2), (3, 1), (3, 2), (4, 1), (4, 2), (5, 2), (6, 1), (6, 2), (7, 1), (7, 2), (8, 1), (8, 2), (9, 1), (9, 2), (10, 1), (11, 1), (11, 2), (12, 1), (12, 2), (13, 1), (14, 1), (14, 2)):
+    for kind, waves in ((0, 1), (0, 2), (1, 1), (1, 2), (2, 1), (2, 2), (3, 1), (3, 2), (4, 1), (4, 2), (5, 2), (6, 1), (6, 2), (7, 1), (7, 2), (8, 1), (8, 2), (9, 1), (9, 2), (10, 1), (11, 1), (11, 2), (12, 1), (12, 2), (13, 1), (14, 1), (14, 2), (15, 1), (15, 2), (16, 1), (16, 2)):
         # 256 workgroups: one per compute unit, `waves` wavefronts per SIMD
         ms, tops, ticks, ghz, iters = run_probe(sage, torch, data, kind, waves, seconds, workgroups=256)
         peak = {0: INT8_PEAK_TOPS, 14: INT8_PEAK_TOPS, 1: FP16_PEAK_TFLOPS, 4: FP16_PEAK_TFLOPS, 5: FP16_PEAK_TFLOPS, 11: FP16_PEAK_TFLOPS,
@@ -476,6 +479,23 @@ def main():
         sustained = {"steps": n_sus, "seconds": ts1 - ts0, "ms_per_step": sus_ms,
                      "value": w.ops / (sus_ms * 1e-3) / 1e12, "unit": "TOPS"}
 
+    # the attention kernel's own counters (its measurement build, same arithmetic): the clock the chip holds
+    # while it runs, the clocks a wavefront spends per 64-key tile, and from them the share of the matrix
+    # pipe's clocks that carry a matrix instruction (a tile is 24 instructions of 32 clocks and 4 of 16 per
+    # wavefront at D = 128, two wavefronts share a SIMD's pipe)
+    kernel_clock = None
+    if not pv_int8 and not per_token and D == 128:
+        for _ in range(3):
+            _, clocks = sage.sage_attn_clock_debug(q_i8, q_scale, k_i8, k_scale, inputs[0][2], out, w.causal, bq, bk, stream)
+        torch.cuda.synchronize()
+        c = clocks.cpu().numpy().astype(np.float64)
+        c = c[c[:, 3] > 0]
+        kernel_clock = {"ghz": float(c[:, 0].sum() / c[:, 1].sum() * 0.1),
+                        "clocks_per_tile_and_wavefront": float(c[:, 0].sum() / c[:, 3].sum()),
+                        "matrix_pipe_busy": float(2.0 * 832.0 * c[:, 3].sum() / c[:, 0].sum()),
+                        "raises_of_the_maximum_per_wavefront": float(c[:, 2].mean()),
+                        "how": "sage_attn_clock_debug, third of three launches after the timed steps"}
+
     # what the matrix pipe sustains with this kernel's own instructions, measured now on this GPU:
     # the pure INT8 stream (the peak `frac` is quoted against, as measured) and the kernel's instruction
     # mix without anything else (the ceiling of this algorithm on this chip)
@@ -537,6 +557,7 @@ def main():
             "frac_of_measured_ceiling": attn_tops / mix_measured,
             "measured": {"int8_stream_tops": int8_measured, "int8_stream_ghz": int8_ghz,
                          "kernel_mix_stream_tops": mix_measured, "kernel_mix_stream_ghz": mix_ghz,
+                         "attention_kernel": kernel_clock,
                          "how": "sage_microbench kinds 0 and " + str(mix_kind) + ", 2 wavefronts per SIMD on every SIMD, "
                                 "about 50 ms each, run after the timed steps (see profiles/mfma_peak_microbench.txt)"},
             "traffic": None if per_token else profiled_traffic(w.name, pv_int8),

@@ -300,6 +300,26 @@ int sage_attn_qk_i32_debug(const int8_t* q_i8, const int8_t* k_i8, int32_t* s_i3
                            int B, int H, int N, int D, int block_q, int block_k, int wg_rows, void* stream);
 
 /*
+ * Measurement hook: sage_attn_fwd's kernel at D = 128 in its 256-row workgroup shape (Algorithm 1; the
+ * speed figures of Section 5 are quoted against the matrix unit's peak, which presumes a clock the
+ * chip does not hold under this load), built with two counters read at the start and the end of every
+ * wavefront.  Same arguments and the same output o_f16 as sage_attn_fwd (sm_scale is folded into
+ * q_scale there and is no argument here), and in addition
+ *   clocks  out [B*H * ceil(N/256) * 8][4] uint64, one row per wavefront, row index
+ *           ((slab * ceil(N/256) + (ceil(N/256) - 1 - query tile)) * 8 + wavefront):
+ *           [0] shader-clock ticks of the wavefront, [1] ticks of the constant 100 MHz counter over the
+ *           same span ([0] / [1] * 0.1 = the clock in GHz the chip held), [2] how often the wavefront
+ *           raised a running maximum (the rare path of the online softmax), [3] key tiles it visited.
+ *           The caller zeroes it; device memory, 8-byte aligned.
+ *   D must be 128 and block_k 64 or 128 (one scale per key block): otherwise SAGE_ERR_UNSUPPORTED.
+ * The 256-row shape is used whatever the problem size (sage_attn_fwd picks 128-row workgroups for
+ * short sequences and small launches).  Other errors as in sage_attn_fwd.
+ */
+int sage_attn_clock_debug(const int8_t* q_i8, const float* q_scale, const int8_t* k_i8, const float* k_scale,
+                          const void* v_f16, void* o_f16, uint64_t* clocks,
+                          int B, int H, int N, int D, int causal, int block_q, int block_k, void* stream);
+
+/*
  * Measurement hook: instruction-stream probes of the matrix pipe, for the roofline the attention
  * kernels are quoted against (Section 5, "Kernel Speed", compares the kernel with the peak of the
  * GPU's INT8 matrix unit; this gives the rate gfx950 sustains with the same instructions).  One
@@ -321,6 +341,12 @@ int sage_attn_qk_i32_debug(const int8_t* q_i8, const int8_t* k_i8, int32_t* s_i3
  *   kind 11 4 x (4 FP16 32x32x16 + 2 of the 4x4x4): the P~V part of a step with its row sums
  *   kind 12 4 x (4 FP16 32x32x16 + 1 FP16 16x16x32);  kind 13  4 x 5 FP16 32x32x16 (other ways to the row sums)
  *   kind 14 kind 0 with all 8 instructions accumulating into one register block (a dependent chain)
+ *   kind 15 the step in the attention kernel's own order at D = 128: 16 FP16 instructions with a 16x16x32
+ *           row-sum instruction after every fourth, then 8 INT8 ones, every operand read from LDS three
+ *           ahead; 16 three-way maxima behind the first 4 instructions, the 16 chunks behind instructions
+ *           4 .. 19 (the last 8 overwrite the scores the chunks read)
+ *   kind 16 kind 15 with the chunks spread over instructions 4 .. 23 instead (what a second set of score
+ *           registers would allow)
  *   data    in  1024 int32 of arbitrary (random) bits: the operands; 16-byte aligned
  *   out     out 4 uint64 per wavefront ([workgroups * 4 * waves_per_simd][4]): shader-clock ticks of the
  *           loop, constant-rate-counter ticks of the loop, a checksum, 0

@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     sage_attn_pv_int8_cross_fwd,
     sage_attn_pv_int8_cross_split_fwd,
     sage_attn_pv_int8_fwd,
+    sage_attn_clock_debug,
     sage_attn_qk_i32_debug,
     sage_attn_split_count,
     sage_attn_split_workspace,

@@ -12,7 +12,7 @@ _lib = None
 
 EXPORTS = ("sage_status_string", "sage_source_hash", "sage_default_sm_scale", "sage_quant_q", "sage_smooth_quant_k_workspace",
            "sage_smooth_quant_k", "sage_smooth_quant_k_noalloc", "sage_rope_quant_q", "sage_rope_smooth_quant_k",
-           "sage_attn_fwd", "sage_attn_qk_i32_debug",
+           "sage_attn_fwd", "sage_attn_qk_i32_debug", "sage_attn_clock_debug",
            "sage_quant_v_workspace", "sage_quant_v_pitch", "sage_quant_v", "sage_attn_pv_int8_fwd",
            "sage_attn_cross_fwd", "sage_attn_pv_int8_cross_fwd",
            "sage_attn_split_count", "sage_attn_split_workspace", "sage_attn_cross_split_fwd",
@@ -74,6 +74,9 @@ def load() -> ctypes.CDLL:
                                   c_int, c_int, c_int, c_int, c_int, c_float, c_int, c_int, c_void_p]
     lib.sage_attn_qk_i32_debug.restype = c_int
     lib.sage_attn_qk_i32_debug.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int, c_int, c_int, c_void_p]
+    lib.sage_attn_clock_debug.restype = c_int
+    lib.sage_attn_clock_debug.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                          c_int, c_int, c_int, c_int, c_int, c_int, c_int, c_void_p]
     lib.sage_attn_cross_fwd.restype = c_int
     lib.sage_attn_cross_fwd.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                         c_int, c_int, c_int, c_int, c_int, c_int, c_float, c_int, c_int, c_void_p]
@@ -426,6 +429,25 @@ def sage_attn_qk_i32_debug(q_i8, k_i8, s_i32=None, block_q: int = 128, block_k: 
     if st != 0:
         raise SageError(st, "sage_attn_qk_i32_debug")
     return s_i32
+
+
+def sage_attn_clock_debug(q_i8, q_scale, k_i8, k_scale, v, out=None, causal: bool = False, block_q: int = 128,
+                          block_k: int = 64, stream=None):
+    """sage_attn_fwd's kernel at D = 128 in its 256-row shape, built with counters (measurement hook) ->
+    (out, clocks): clocks [B*H*ceil(N/256)*8, 4] int64, per wavefront shader-clock ticks, 100 MHz ticks, raises
+    of the running maximum, key tiles visited."""
+    B, H, N, D = q_i8.shape
+    if out is None:
+        out = torch.empty((B, H, N, D), dtype=torch.float16, device=q_i8.device)
+    clocks = torch.zeros((B * H * ((N + 255) // 256) * 8, 4), dtype=torch.int64, device=q_i8.device)
+    st = load().sage_attn_clock_debug(_dev(q_i8, torch.int8, "q_i8"), _dev(q_scale, torch.float32, "q_scale"),
+                                      _dev(k_i8, torch.int8, "k_i8"), _dev(k_scale, torch.float32, "k_scale"),
+                                      _dev(v, torch.float16, "v"), _dev(out, torch.float16, "out"),
+                                      _dev(clocks, torch.int64, "clocks"), B, H, N, D, int(bool(causal)),
+                                      int(block_q), int(block_k), _stream(stream))
+    if st != 0:
+        raise SageError(st, "sage_attn_clock_debug")
+    return out, clocks
 
 
 def sage_microbench(kind: int, waves_per_simd: int, workgroups: int, iters: int, data, out=None, stream=None):

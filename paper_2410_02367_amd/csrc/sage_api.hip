@@ -278,7 +278,7 @@ int sage_quant_v(const void* v_f16, int8_t* v_i8t, float* v_scale, void* workspa
 int sage_microbench(int kind, int waves_per_simd, int workgroups, int iters,
                     const int32_t* data, uint64_t* out, void* stream) {
     if (!data || !out) return SAGE_ERR_NULL;
-    if (kind < 0 || kind > 14 || (waves_per_simd != 1 && waves_per_simd != 2)) return SAGE_ERR_UNSUPPORTED;
+    if (kind < 0 || kind > 16 || (waves_per_simd != 1 && waves_per_simd != 2)) return SAGE_ERR_UNSUPPORTED;
     if (kind == 5 && waves_per_simd != 2) return SAGE_ERR_UNSUPPORTED;
     if (workgroups <= 0 || workgroups > (1 << 20) || iters <= 0) return SAGE_ERR_SHAPE;
     if (!aligned(data, 16) || !aligned(out, 8)) return SAGE_ERR_ALIGN;
@@ -298,6 +298,20 @@ int sage_attn_qk_i32_debug(const int8_t* q_i8, const int8_t* k_i8, int32_t* s_i3
     // scales are not read by the dump path; pass the tensor pointers as placeholders of valid memory
     hipError_t e = sage::launch_attn(q_i8, (const float*)q_i8, k_i8, (const float*)k_i8, nullptr, nullptr, s_i32,
                                      B * H, N, N, D, 0, block_q, block_k, (hipStream_t)stream, wg_rows);
+    return e == hipSuccess ? SAGE_OK : SAGE_ERR_LAUNCH;
+}
+
+int sage_attn_clock_debug(const int8_t* q_i8, const float* q_scale, const int8_t* k_i8, const float* k_scale,
+                          const void* v_f16, void* o_f16, uint64_t* clocks,
+                          int B, int H, int N, int D, int causal, int block_q, int block_k, void* stream) {
+    if (!q_i8 || !q_scale || !k_i8 || !k_scale || !v_f16 || !o_f16 || !clocks) return SAGE_ERR_NULL;
+    if (int e = check_shape(B, H, N, D)) return e;
+    if (D != 128 || !quant_block_ok(block_q) || (block_k != 64 && block_k != 128)) return SAGE_ERR_UNSUPPORTED;
+    if (!aligned(q_i8, 16) || !aligned(k_i8, 16) || !aligned(v_f16, 16) || !aligned(o_f16, 16) ||
+        !aligned(q_scale, 4) || !aligned(k_scale, 4) || !aligned(clocks, 8))
+        return SAGE_ERR_ALIGN;
+    hipError_t e = sage::launch_attn_clocks(q_i8, q_scale, k_i8, k_scale, v_f16, o_f16, (unsigned long long*)clocks,
+                                            B * H, N, causal ? 1 : 0, block_q, block_k, (hipStream_t)stream);
     return e == hipSuccess ? SAGE_OK : SAGE_ERR_LAUNCH;
 }
 

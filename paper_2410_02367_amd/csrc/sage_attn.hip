@@ -223,14 +223,18 @@ template <class T> __device__ __forceinline__ void pin_a(T& x) { asm volatile(""
 // raw scores into t = S^ * delta_K[k] = fma(seeded score, a_k, b_k) while it takes the row maximum
 // (now a floating-point maximum), and the softmax FMA becomes t * (delta_Q log2 e) - m.  One
 // scale per QUERY token costs nothing in either variant: a lane owns one query.
-template <int D, int NW, bool CAUSAL, bool DUMP, bool KTOK>
+//
+// CLOCKS (measurement build of the same kernel): every wavefront also leaves the shader-clock and
+// constant-rate (100 MHz) counter ticks it ran for, how often it raised a running maximum and how
+// many key tiles it visited -- from which the clock the chip held and the clocks per tile follow.
+template <int D, int NW, bool CAUSAL, bool DUMP, bool KTOK, bool CLOCKS = false>
 // Workgroups of 4 wavefronts per CU that the register budget is cut for: 3 at D = 64 (168 registers
 // per lane; measured 4 % faster than 2; the per-token variant needs more), else 2.
 __global__ void __launch_bounds__(NW * 64, NW == 4 && SAGE_QS == 1 ? 2 : 1)
 sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
                  const int8_t* __restrict__ ki, const float* __restrict__ ksc,
                  const _Float16* __restrict__ vg, _Float16* __restrict__ og,
-                 int32_t* __restrict__ sdump, float* __restrict__ lse,
+                 int32_t* __restrict__ sdump, float* __restrict__ lse, unsigned long long* __restrict__ clocks,
                  int Nq, int Nkv, int shift_q, int shift_k, int tiles_q, int per_xcd, long total_tiles,
                  int BH, int n_splits, int chunk) {
     constexpr int NWAVES = NW, NTHREADS = NW * 64;
@@ -260,6 +264,9 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
     const int qt = tiles_q - 1 - (int)(gidx % tiles_q);
     const int bh = unit / n_splits, split = unit - bh * n_splits;
 
+    unsigned long long clock_t0 = 0, clock_r0 = 0;
+    int n_raised = 0;
+    if constexpr (CLOCKS) { clock_t0 = __builtin_readcyclecounter(); clock_r0 = wall_clock64(); }
     const int t = threadIdx.x, lane = t & 63;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);     // wave-uniform: keeps control flow scalar
     const int ql = lane & 31, g = lane >> 5;
@@ -871,6 +878,7 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
         asm volatile("" : "+s"(opaque));
         step_a(par);
         if (must_raise()) {
+            if constexpr (CLOCKS) ++n_raised;
             raise_maximum();
             set_bias();
         }
@@ -930,12 +938,22 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
                 }
         }
     }
+    if constexpr (CLOCKS) {
+        if (lane == 0) {
+            unsigned long long* row = clocks + ((size_t)gidx * NW + wave) * 4;
+            row[0] = __builtin_readcyclecounter() - clock_t0;
+            row[1] = wall_clock64() - clock_r0;
+            row[2] = (unsigned long long)n_raised;
+            row[3] = (unsigned long long)Tw;
+        }
+    }
 }
 
 template <int D, int NW>
 static hipError_t launch_dn(const int8_t* qq, const float* qscale, const int8_t* kq, const float* kscale,
                             const void* v, void* o, int32_t* sdump, int BH, int Nq, int N, int causal,
-                            int block_q, int block_k, const SplitPlan& sp, hipStream_t st) {
+                            int block_q, int block_k, const SplitPlan& sp, hipStream_t st,
+                            unsigned long long* clocks = nullptr) {
     constexpr int QTILE = NW * WROWS, NTHREADS = NW * 64;
     const int tiles_q = (Nq + QTILE - 1) / QTILE;
     const long total = (long)BH * sp.n_splits * tiles_q;
@@ -945,7 +963,19 @@ static hipError_t launch_dn(const int8_t* qq, const float* qscale, const int8_t*
     const _Float16* vp = (const _Float16*)v;
     _Float16* op = (_Float16*)o;
     const bool ktok = block_k == 1;
-#define SAGE_LAUNCH(C, DMP, KT) sage_attn_kernel<D, NW, C, DMP, KT><<<grid, NTHREADS, 0, st>>>(qq, qscale, kq, kscale, vp, op, sdump, sp.lse, Nq, N, shift_q, shift_k, tiles_q, per_xcd, total, BH, sp.n_splits, sp.chunk)
+#define SAGE_ARGS qq, qscale, kq, kscale, vp, op, sdump, sp.lse, clocks, Nq, N, shift_q, shift_k, tiles_q, per_xcd, total, BH, sp.n_splits, sp.chunk
+#define SAGE_LAUNCH(C, DMP, KT) sage_attn_kernel<D, NW, C, DMP, KT><<<grid, NTHREADS, 0, st>>>(SAGE_ARGS)
+    if (clocks != nullptr) {
+        // the measurement build exists for the headline shape only: D = 128, 256-row workgroups, block scales
+        if constexpr (D == 128 && NW == 8) {
+            if (sdump || ktok) return hipErrorInvalidValue;
+            if (causal) sage_attn_kernel<D, NW, true, false, false, true><<<grid, NTHREADS, 0, st>>>(SAGE_ARGS);
+            else sage_attn_kernel<D, NW, false, false, false, true><<<grid, NTHREADS, 0, st>>>(SAGE_ARGS);
+            return hipGetLastError();
+        } else {
+            return hipErrorInvalidValue;
+        }
+    }
     // per-token key scales need a few more registers than 4-wavefront workgroups at D = 128 have
     // (two workgroups per CU: 128 + 128 registers); launch_d() never asks for that combination
     constexpr bool KTOK_OK = !(D == 128 && NW == 4);
@@ -961,13 +991,15 @@ static hipError_t launch_dn(const int8_t* qq, const float* qscale, const int8_t*
     else if (causal) SAGE_LAUNCH(true, false, false);
     else SAGE_LAUNCH(false, false, false);
 #undef SAGE_LAUNCH
+#undef SAGE_ARGS
     return hipGetLastError();
 }
 
 template <int D>
 static hipError_t launch_d(const int8_t* qq, const float* qscale, const int8_t* kq, const float* kscale,
                            const void* v, void* o, int32_t* sdump, int BH, int Nq, int N, int causal,
-                           int block_q, int block_k, const SplitPlan& sp, hipStream_t st, int wg_rows = 0) {
+                           int block_q, int block_k, const SplitPlan& sp, hipStream_t st, int wg_rows = 0,
+                           unsigned long long* clocks = nullptr) {
     // 256-row workgroups (8 wavefronts sharing one set of LDS tiles) for long sequences at D = 128;
     // 128-row workgroups, two or three per CU, for D = 64, whenever the larger tile would leave CUs
     // without work (fewer than two workgroups per CU), and for short sequences, where a workgroup
@@ -980,8 +1012,9 @@ static hipError_t launch_d(const int8_t* qq, const float* qscale, const int8_t* 
     bool small = QS == 1 && (D == 64 || ((big_tiles < 2 * 256 || short_seq) && block_k != 1 && !sdump));
     // the score dump may name the workgroup shape, so that a test reaches every instantiation
     if (sdump && wg_rows != 0) small = wg_rows == 4 * WROWS;
+    if (clocks != nullptr) small = false;       // the measurement build has the 256-row shape only
     if (small) return launch_dn<D, 4>(qq, qscale, kq, kscale, v, o, sdump, BH, Nq, N, causal, block_q, block_k, sp, st);
-    return launch_dn<D, 8>(qq, qscale, kq, kscale, v, o, sdump, BH, Nq, N, causal, block_q, block_k, sp, st);
+    return launch_dn<D, 8>(qq, qscale, kq, kscale, v, o, sdump, BH, Nq, N, causal, block_q, block_k, sp, st, clocks);
 }
 
 hipError_t launch_attn(const int8_t* qq, const float* qscale, const int8_t* kq, const float* kscale,
@@ -990,6 +1023,13 @@ hipError_t launch_attn(const int8_t* qq, const float* qscale, const int8_t* kq, 
     const SplitPlan whole = {1, 0, nullptr};
     if (D == 64) return launch_d<64>(qq, qscale, kq, kscale, v, o, sdump, BH, Nq, N, causal, block_q, block_k, whole, st, wg_rows);
     return launch_d<128>(qq, qscale, kq, kscale, v, o, sdump, BH, Nq, N, causal, block_q, block_k, whole, st, wg_rows);
+}
+
+hipError_t launch_attn_clocks(const int8_t* qq, const float* qscale, const int8_t* kq, const float* kscale,
+                              const void* v, void* o, unsigned long long* clocks, int BH, int N, int causal,
+                              int block_q, int block_k, hipStream_t st) {
+    const SplitPlan whole = {1, 0, nullptr};
+    return launch_d<128>(qq, qscale, kq, kscale, v, o, nullptr, BH, N, N, causal, block_q, block_k, whole, st, 0, clocks);
 }
 
 // ---- split over the keys ------------------------------------------------------------------------

@@ -26,6 +26,13 @@ hipError_t launch_smooth_quant_k(const void* k, int8_t* kq, float* kscale, float
 hipError_t launch_attn(const int8_t* qq, const float* qscale, const int8_t* kq, const float* kscale,
                        const void* v, void* o, int32_t* sdump, int BH, int Nq, int N, int D, int causal,
                        int block_q, int block_k, hipStream_t st, int wg_rows = 0);
+// Measurement build of the same kernel (D = 128, 256-row workgroups, one scale per key block): also
+// writes, per wavefront, [shader-clock ticks, 100 MHz ticks, raises of the running maximum, key tiles
+// visited] to clocks[(workgroup * 8 + wavefront) * 4 ..], workgroup = slab * ceil(N / 256) + query tile
+// counted from the last.
+hipError_t launch_attn_clocks(const int8_t* qq, const float* qscale, const int8_t* kq, const float* kscale,
+                              const void* v, void* o, unsigned long long* clocks, int BH, int N, int causal,
+                              int block_q, int block_k, hipStream_t st);
 
 // The same with the keys of a slab cut into chunks (for few query rows): partial results per chunk in
 // `workspace` (n_splits * BH * Nq * (2 D + 4) bytes), then a merge into o.  plan_split() resolves the

@@ -100,8 +100,8 @@ template <int KIND>
 __global__ void __launch_bounds__(512) microbench_kernel(const int* __restrict__ data, unsigned long long* __restrict__ out,
                                                          int iters) {
     // 48 KB: a 64-key K^ tile (8 KB) and V tile (16 KB) of the attention kernel at D = 128, twice
-    __shared__ __attribute__((aligned(1024))) unsigned char tile[KIND >= 7 && KIND <= 9 ? 49152 : 16];
-    if constexpr (KIND >= 7 && KIND <= 9) {
+    __shared__ __attribute__((aligned(1024))) unsigned char tile[(KIND >= 7 && KIND <= 9) || KIND == 15 || KIND == 16 ? 49152 : 16];
+    if constexpr ((KIND >= 7 && KIND <= 9) || KIND == 15 || KIND == 16) {
         for (int i = threadIdx.x; i < 49152 / 4; i += blockDim.x) ((int*)tile)[i] = data[i & 1023] & 0x3BFF3BFF;
     }
     const int lane = threadIdx.x & 63;
@@ -231,6 +231,43 @@ __global__ void __launch_bounds__(512) microbench_kernel(const int* __restrict__
                 else { asm volatile("" : "+v"(mu), "+v"(mv)); mx = max(max(mx, mu), mv); asm volatile("" : "+v"(mx)); }
                 __builtin_amdgcn_sched_barrier(0);
             }
+        } else if constexpr (KIND == 15 || KIND == 16) {
+            // The attention kernel's own order at D = 128: 16 FP16 instructions (V^T operands) with a row-sum
+            // instruction after every fourth, then 8 INT8 ones (K^ operands); every operand read from LDS 3
+            // ahead; the 16 three-way maxima of the row maximum behind the first 4.  Kind 15 puts the 16
+            // softmax chunks behind instructions 4 .. 19, as the kernel must while the scores of one tile
+            // live in one set of registers (the last 8 instructions overwrite them); kind 16 spreads them
+            // over instructions 4 .. 23, which a second set of score registers would allow.
+            mb_v4i ring[4];
+            auto fetch = [&](int n) {
+                if (n >= 16) {
+                    ring[n & 3] = *(const mb_v4i*)(tile + k_operand_at(lane, (n - 16) >> 2, n & 3));
+                } else {
+                    const int at = 16384 + v_operand_at(lane, n >> 2, n & 3);
+                    mb_v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(MB_LDS(mb_v4s, tile + at));
+                    mb_v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(MB_LDS(mb_v4s, tile + at + 2048));
+                    ring[n & 3] = __builtin_bit_cast(mb_v4i, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+                }
+            };
+            if (it == 0) { fetch(0); fetch(1); fetch(2); }
+            constexpr int LAST = KIND == 15 ? 20 : 24;          // chunks behind instructions 4 .. LAST - 1
+#pragma unroll
+            for (int n = 0; n < 24; ++n) {
+                if (n >= 16) mb_i8(ci[n & 3], ring[n & 3], b8);
+                else mb_f16(cf[n & 3], __builtin_bit_cast(mb_v8h, ring[n & 3]), bf);
+                fetch((n + 3) % 24);
+                __builtin_amdgcn_sched_barrier(0);
+                if (n < 4) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) { asm volatile("" : "+v"(mu), "+v"(mv)); mx = max(max(mx, mu), mv); asm volatile("" : "+v"(mx)); }
+                } else if (n < LAST) {
+                    const int first = (n - 4) * 16 / (LAST - 4), end = (n - 3) * 16 / (LAST - 4);
+#pragma unroll
+                    for (int c = first; c < end; ++c) sp.tick(c);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                if (n < 16 && n % 4 == 3) { mb_mid(cl[(n >> 2) & 1], af, bf); __builtin_amdgcn_sched_barrier(0); }
+            }
         } else {
             // 24 matrix instructions; chunks behind 16 of them, three-way integer maxima behind the other 8
 #pragma unroll
@@ -286,6 +323,8 @@ hipError_t launch_microbench(int kind, int waves_per_simd, int workgroups, int i
         case 12: microbench_kernel<12><<<workgroups, threads, 0, st>>>(data, out, iters); break;
         case 13: microbench_kernel<13><<<workgroups, threads, 0, st>>>(data, out, iters); break;
         case 14: microbench_kernel<14><<<workgroups, threads, 0, st>>>(data, out, iters); break;
+        case 15: microbench_kernel<15><<<workgroups, threads, 0, st>>>(data, out, iters); break;
+        case 16: microbench_kernel<16><<<workgroups, threads, 0, st>>>(data, out, iters); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

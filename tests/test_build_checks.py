@@ -7,6 +7,8 @@ KERNELS = ["_ZN4sage16sage_attn_kernelILi%dELi%dELb%dELb%dELb%dEEEvPKa" % (d, nw
            for d in (64, 128) for nw in (4, 8)
            for c, dump, ktok in ((0, 1, 0), (1, 0, 0), (0, 0, 0), (1, 0, 1), (0, 0, 1))
            if not (d == 128 and nw == 4 and ktok)]
+# the two measurement builds (clock counters): D = 128, 8 wavefronts, causal / full
+KERNELS += ["_ZN4sage16sage_attn_kernelILi128ELi8ELb%dELb0ELb0ELb1EEEvPKa" % c for c in (1, 0)]
 
 
 def fake(body_of_first: str) -> str:
@@ -40,7 +42,7 @@ def test_clean_text_passes():
 
 def test_missing_kernel_is_reported():
     text = fake(CLEAN).split(KERNELS[-1])[0]
-    assert any("expected 18" in p for p in check_attention_asm(text))
+    assert any("expected 20" in p for p in check_attention_asm(text))
 
 
 def test_accumulator_copy_after_first_matrix_instruction_is_reported():

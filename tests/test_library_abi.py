@@ -82,6 +82,12 @@ def test_host_validation_rejects_bad_arguments_before_any_launch(lib):
     assert lib.sage_attn_qk_i32_debug(good, odd, good, 1, 1, 64, 64, 128, 64, 0, None) == 5
     assert lib.sage_attn_qk_i32_debug(good, good, good, 1, 1, 64, 64, 128, 32, 0, None) == 3
     assert lib.sage_attn_qk_i32_debug(good, good, good, 1, 1, 64, 64, 128, 64, 64, None) == 3
+    # the attention kernel's measurement build: D = 128 with one scale per key block only
+    assert lib.sage_attn_clock_debug(good, good, good, good, good, good, None, 1, 1, 64, 128, 0, 128, 64, None) == 1
+    assert lib.sage_attn_clock_debug(good, good, good, good, good, good, good, 1, 1, 64, 64, 0, 128, 64, None) == 3
+    assert lib.sage_attn_clock_debug(good, good, good, good, good, good, good, 1, 1, 64, 128, 0, 1, 1, None) == 3
+    assert lib.sage_attn_clock_debug(good, good, good, good, good, good, good, 0, 1, 64, 128, 0, 128, 64, None) == 2
+    assert lib.sage_attn_clock_debug(good, good, good, good, good, good, odd, 1, 1, 64, 128, 0, 128, 64, None) == 5
     # more (batch, head) slabs than the documented limit
     assert lib.sage_quant_q(good, good, good, 256, 256, 64, 64, f(0.125), 64, None) == 2
     # the fused-RoPE calls: tables required and 16-byte aligned, everything else as the unfused calls
