@@ -122,6 +122,51 @@ def microbench(seconds: float):
             "%.1f" % (100.0 * tops / peak) if tops else "-", ticks, busy, ghz, lds), flush=True)
 
 
+def clock_study(workload: str):
+    """The attention kernel (FP16 P~V, D = 128) on the workload's tensors, with the key scales multiplied by a
+    factor: what is computed per tile stays the same, the spread of the scores -- and with it the bit patterns
+    the softmax and the second product work on -- changes.  Per factor: time of the plain kernel, and from its
+    measurement build the clock the chip held, the clocks per tile and the rare-path count (table on stdout;
+    not part of the one-line benchmark contract)."""
+    import torch
+
+    import paper_2410_02367_amd as sage
+    import sage_inputs as si
+
+    w = si.WORKLOADS[workload]
+    torch.cuda.set_device(0)
+    qd, kd, vd = (torch.from_numpy(a).cuda() for a in si.full(w))
+    B, H, N, D = w.B, w.H, w.N, w.D
+    k_i8, k_scale, _ = sage.sage_smooth_quant_k(kd, w.block_k)
+    q_i8, q_scale = sage.sage_quant_q(qd, w.sm_scale, w.block_q)
+    out = torch.empty_like(qd)
+    ops = 4.0 * B * H * N * N * D
+    print(f"attention kernel on {w.name} (B={B} H={H} N={N} D={D}), key scales x factor; "
+          f"TOPS = 4 B H N^2 D (halved if causal) / time; pipe busy = 2 * 832 clocks per tile / clocks per tile and wavefront")
+    print("%-8s %-7s %8s %7s %7s %14s %10s %12s" % ("causal", "factor", "ms", "TOPS", "GHz", "clocks/tile/wf", "pipe busy", "raises/wf"))
+    for causal in (False, True):
+        for factor in (1e-9, 0.25, 1.0, 4.0, 100.0):
+            ks = (k_scale * factor).contiguous()
+            for _ in range(3):
+                sage.sage_attn_fwd(q_i8, q_scale, k_i8, ks, vd, causal, w.sm_scale, w.block_q, w.block_k, out)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(10):
+                sage.sage_attn_fwd(q_i8, q_scale, k_i8, ks, vd, causal, w.sm_scale, w.block_q, w.block_k, out)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = [e0.elapsed_time(e1) / 10]
+            for _ in range(10):      # back to back, so that the last launch sees the clock the load settles at
+                _, clocks = sage.sage_attn_clock_debug(q_i8, q_scale, k_i8, ks, vd, out, causal, w.block_q, w.block_k)
+            torch.cuda.synchronize()
+            c = clocks.cpu().numpy().astype(np.float64)
+            c = c[c[:, 3] > 0]
+            t = float(np.mean(ms))
+            print("%-8s %-7g %8.3f %7.0f %7.3f %14.0f %10.3f %12.1f" % (
+                causal, factor, t, ops / (2 if causal else 1) / (t * 1e-3) / 1e12, c[:, 0].sum() / c[:, 1].sum() * 0.1,
+                c[:, 0].sum() / c[:, 3].sum(), 2.0 * 832.0 * c[:, 3].sum() / c[:, 0].sum(), c[:, 2].mean()), flush=True)
+
+
 def cpu_baseline(w, seconds_budget=20.0, per_token=False, gpu_out_head0=None, pv_int8=False):
     """Oracle (Algorithm-1 level, as it stands) on one head of the workload: the full pre-pass of that
     head plus a spread of Q blocks, scaled to the head's block-pair count."""
@@ -332,6 +377,9 @@ def main():
                          "last Nq tokens of the workload as queries against all of its keys; comma-separated list of Nq")
     ap.add_argument("--rotate", type=int, default=1,
                     help="number of distinct input allocations used in turn (1 = every step reads the same buffers)")
+    ap.add_argument("--clock-study", action="store_true",
+                    help="table: the attention kernel's time, clock and clocks per tile on the workload's tensors with the "
+                         "key scales multiplied by several factors (the spread of the scores changes, the work does not)")
     ap.add_argument("--microbench", type=float, nargs="?", const=0.05, default=None, metavar="SECONDS",
                     help="instead of the benchmark line, print what the matrix pipe sustains with the attention "
                          "kernel's instructions (pure INT8 / FP16 streams, the attention mix, with and without the "
@@ -361,6 +409,9 @@ def main():
         sys.exit(2)
     if args.microbench is not None:
         microbench(args.microbench)
+        return
+    if args.clock_study:
+        clock_study(args.workload)
         return
     if args.sweep:
         sweep(args.scales == "token", args.pv == "int8")
