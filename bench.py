@@ -377,6 +377,9 @@ def main():
                          "last Nq tokens of the workload as queries against all of its keys; comma-separated list of Nq")
     ap.add_argument("--rotate", type=int, default=1,
                     help="number of distinct input allocations used in turn (1 = every step reads the same buffers)")
+    ap.add_argument("--prepass", choices=("separate", "fused"), default="separate",
+                    help="separate: sage_smooth_quant_k + sage_quant_q (three launches; one fewer for short sequences); "
+                         "fused: sage_quant_qk, the same work in one launch less")
     ap.add_argument("--clock-study", action="store_true",
                     help="table: the attention kernel's time, clock and clocks per tile on the workload's tensors with the "
                          "key scales multiplied by several factors (the spread of the scores changes, the work does not)")
@@ -462,6 +465,8 @@ def main():
         if args.rope:
             sage.sage_rope_smooth_quant_k(kd, rope_cos, rope_sin, bk, k_i8, k_scale, k_mean, ws, stream)
             sage.sage_rope_quant_q(qd, rope_cos, rope_sin, w.sm_scale, bq, q_i8, q_scale, stream)
+        elif args.prepass == "fused":
+            sage.sage_quant_qk(qd, kd, w.sm_scale, bq, bk, q_i8, q_scale, k_i8, k_scale, k_mean, ws, stream)
         else:
             sage.sage_smooth_quant_k(kd, bk, k_i8, k_scale, k_mean, ws, stream)
             sage.sage_quant_q(qd, w.sm_scale, bq, q_i8, q_scale, stream)

@@ -117,6 +117,22 @@ int sage_smooth_quant_k(const void* k_f16, int8_t* k_i8, float* k_scale, float* 
                         int B, int H, int N, int D, int block_k, void* stream);
 
 /*
+ * sage_quant_q and sage_smooth_quant_k of one (Q, K) pair in one launch less (Sections 3.2, 4.2, 4.6;
+ * Algorithm 1 "Quantization"): the quantization of Q depends on nothing the K side computes, so it
+ * shares a launch with the K side's first half (the column sums); for key sequences short enough for
+ * the single-launch K pre-pass, with all of it.  Two launches instead of three, one instead of two --
+ * which is most of the pre-pass's time for short sequences.  Results are those of the two separate
+ * calls, bit for bit.
+ *   q_f16 [B,H,Nq,D], k_f16 [B,H,Nkv,D]: the two lengths may differ (cross attention, decode)
+ *   q_i8, q_scale   as in sage_quant_q (for Nq);  k_i8, k_scale, k_mean as in sage_smooth_quant_k (for Nkv)
+ *   workspace       at least sage_smooth_quant_k_workspace(B, H, Nkv, D) bytes, as in sage_smooth_quant_k
+ * Arguments, limits and error codes as in the two separate calls; nothing is launched when a check fails.
+ */
+int sage_quant_qk(const void* q_f16, const void* k_f16, int8_t* q_i8, float* q_scale,
+                  int8_t* k_i8, float* k_scale, float* k_mean, void* workspace, size_t workspace_bytes,
+                  int B, int H, int Nq, int Nkv, int D, float sm_scale, int block_q, int block_k, void* stream);
+
+/*
  * sage_smooth_quant_k for callers that cannot allocate device memory or carry a workspace around:
  * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
  * kernels, same results bit for bit; the partial column sums go to a buffer that is part of the

@@ -21,6 +21,7 @@ from .binding import (  # noqa: F401
     sage_default_sm_scale,
     sage_microbench,
     sage_quant_q,
+    sage_quant_qk,
     sage_quant_v,
     sage_quant_v_pitch,
     sage_quant_v_workspace,

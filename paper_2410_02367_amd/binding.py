@@ -11,7 +11,7 @@ _LIB_PATH = os.path.join(_HERE, "libsage.so")
 _lib = None
 
 EXPORTS = ("sage_status_string", "sage_source_hash", "sage_default_sm_scale", "sage_quant_q", "sage_smooth_quant_k_workspace",
-           "sage_smooth_quant_k", "sage_smooth_quant_k_noalloc", "sage_rope_quant_q", "sage_rope_smooth_quant_k",
+           "sage_smooth_quant_k", "sage_quant_qk", "sage_smooth_quant_k_noalloc", "sage_rope_quant_q", "sage_rope_smooth_quant_k",
            "sage_attn_fwd", "sage_attn_qk_i32_debug", "sage_attn_clock_debug",
            "sage_quant_v_workspace", "sage_quant_v_pitch", "sage_quant_v", "sage_attn_pv_int8_fwd",
            "sage_attn_cross_fwd", "sage_attn_pv_int8_cross_fwd",
@@ -61,6 +61,9 @@ def load() -> ctypes.CDLL:
     lib.sage_smooth_quant_k.restype = c_int
     lib.sage_smooth_quant_k.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t,
                                         c_int, c_int, c_int, c_int, c_int, c_void_p]
+    lib.sage_quant_qk.restype = c_int
+    lib.sage_quant_qk.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t,
+                                  c_int, c_int, c_int, c_int, c_int, c_float, c_int, c_int, c_void_p]
     lib.sage_smooth_quant_k_noalloc.restype = c_int
     lib.sage_smooth_quant_k_noalloc.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int, c_void_p]
     lib.sage_rope_quant_q.restype = c_int
@@ -222,6 +225,38 @@ def sage_smooth_quant_k(k: torch.Tensor, block_k: int = 64, k_i8=None, k_scale=N
     if st != 0:
         raise SageError(st, "sage_smooth_quant_k")
     return k_i8, k_scale, k_mean
+
+
+def sage_quant_qk(q: torch.Tensor, k: torch.Tensor, sm_scale: float, block_q: int = 128, block_k: int = 64,
+                  q_i8=None, q_scale=None, k_i8=None, k_scale=None, k_mean=None, workspace=None, stream=None):
+    """sage_quant_q(q) and sage_smooth_quant_k(k) in one launch less -> (q_i8, q_scale, k_i8, k_scale, k_mean)."""
+    B, H, Nq, D = q.shape
+    Nkv = k.shape[2]
+    if k.shape[0] != B or k.shape[1] != H or k.shape[3] != D:
+        raise ValueError("sage_quant_qk: q and k differ in batch, heads or head dimension")
+    dev = q.device
+    if q_i8 is None:
+        q_i8 = torch.empty((B, H, Nq, D), dtype=torch.int8, device=dev)
+    if q_scale is None:
+        q_scale = torch.empty((B, H, _nblk(Nq, block_q)), dtype=torch.float32, device=dev)
+    if k_i8 is None:
+        k_i8 = torch.empty((B, H, Nkv, D), dtype=torch.int8, device=dev)
+    if k_scale is None:
+        k_scale = torch.empty((B, H, _nblk(Nkv, block_k)), dtype=torch.float32, device=dev)
+    if k_mean is None:
+        k_mean = torch.empty((B, H, D), dtype=torch.float32, device=dev)
+    need = sage_smooth_quant_k_workspace(B, H, Nkv, D)
+    if workspace is None:
+        workspace = torch.empty((max(need, 8) + 7) // 8, dtype=torch.int64, device=dev)
+    ws_bytes = workspace.numel() * workspace.element_size()
+    st = load().sage_quant_qk(_dev(q, torch.float16, "q"), _dev(k, torch.float16, "k"), _dev(q_i8, torch.int8, "q_i8"),
+                              _dev(q_scale, torch.float32, "q_scale"), _dev(k_i8, torch.int8, "k_i8"),
+                              _dev(k_scale, torch.float32, "k_scale"), _dev(k_mean, torch.float32, "k_mean"),
+                              workspace.data_ptr(), ws_bytes, B, H, Nq, Nkv, D, float(sm_scale), int(block_q), int(block_k),
+                              _stream(stream))
+    if st != 0:
+        raise SageError(st, "sage_quant_qk")
+    return q_i8, q_scale, k_i8, k_scale, k_mean
 
 
 NOALLOC_SCRATCH_BYTES = 4 << 20     # SAGE_NOALLOC_SCRATCH_BYTES of include/sage.h

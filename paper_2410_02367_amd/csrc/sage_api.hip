@@ -147,6 +147,25 @@ int sage_smooth_quant_k_noalloc(const void* k_f16, int8_t* k_i8, float* k_scale,
     return smooth_quant_k_impl(k_f16, nullptr, nullptr, false, k_i8, k_scale, k_mean, ws, need, B, H, N, D, block_k, stream);
 }
 
+int sage_quant_qk(const void* q_f16, const void* k_f16, int8_t* q_i8, float* q_scale,
+                  int8_t* k_i8, float* k_scale, float* k_mean, void* workspace, size_t workspace_bytes,
+                  int B, int H, int Nq, int Nkv, int D, float sm_scale, int block_q, int block_k, void* stream) {
+    if (!q_f16 || !k_f16 || !q_i8 || !q_scale || !k_i8 || !k_scale) return SAGE_ERR_NULL;      // k_mean is optional
+    if (int e = check_shape(B, H, Nq, D)) return e;
+    if (int e = check_shape(B, H, Nkv, D)) return e;
+    if (!quant_block_ok(block_q) || !quant_block_ok(block_k)) return SAGE_ERR_UNSUPPORTED;
+    if (!std::isfinite(sm_scale) || !(sm_scale > 0.0f)) return SAGE_ERR_VALUE;
+    const size_t need = sage_smooth_quant_k_workspace(B, H, Nkv, D);
+    if (need > 0 && !workspace) return SAGE_ERR_NULL;
+    if (workspace_bytes < need) return SAGE_ERR_WORKSPACE;
+    if (!aligned(q_f16, 16) || !aligned(q_i8, 16) || !aligned(q_scale, 4) || !aligned(k_f16, 16) || !aligned(k_i8, 16) ||
+        !aligned(k_scale, 4) || !aligned(k_mean, 4) || !aligned(workspace, 8))
+        return SAGE_ERR_ALIGN;
+    hipError_t e = sage::launch_quant_qk(q_f16, k_f16, q_i8, q_scale, k_i8, k_scale, k_mean, (long long*)workspace,
+                                         B * H, Nq, Nkv, D, sm_scale, block_q, block_k, (hipStream_t)stream);
+    return e == hipSuccess ? SAGE_OK : SAGE_ERR_LAUNCH;
+}
+
 int sage_rope_smooth_quant_k(const void* k_f16, const float* rope_cos, const float* rope_sin,
                              int8_t* k_i8, float* k_scale, float* k_mean,
                              void* workspace, size_t workspace_bytes,

@@ -19,6 +19,11 @@ ColsumPlan plan_colsum(int BH, int N);
 hipError_t launch_smooth_quant_k(const void* k, int8_t* kq, float* kscale, float* kmean,
                                  long long* parts, int BH, int N, int D, int block,
                                  const float* cs, const float* sn, hipStream_t st);
+// Both pre-passes of a (Q, K) pair in one launch less: the K side's first half (or, for short key
+// sequences, all of it) shares a launch with the Q quantizer.  No RoPE.  parts as above (for Nkv).
+hipError_t launch_quant_qk(const void* q, const void* k, int8_t* qq, float* qscale, int8_t* kq, float* kscale,
+                           float* kmean, long long* parts, int BH, int Nq, int Nkv, int D, float sm_scale,
+                           int block_q, int block_k, hipStream_t st);
 
 // Fused attention (MFMA-bound): Nq query rows against N keys per slab.  sdump != nullptr selects the
 // int32 score dump; for the dump, wg_rows (128 or 256) names the workgroup shape instead of leaving

@@ -59,16 +59,19 @@ __device__ __forceinline__ h8 load_row8(const _Float16* __restrict__ row, int c8
 // gives the same bits).  No atomics, nothing to clear beforehand, every word of the result written.
 // A thread owns one 16-byte column group of every RG-th row and fetches BATCH rows at a time, all loads
 // issued before the first is used (rows past the end are fetched from the last row and not added).
-template <int D, bool ROPE>
-__global__ void __launch_bounds__(256) k_colsum_kernel(const _Float16* __restrict__ k,
-                                                       long long* __restrict__ part_out, int N, int chunk,
-                                                       const float* __restrict__ cs, const float* __restrict__ sn) {
+// (The kernels of this file are written as bodies that take their workgroup coordinates -- chunk or
+// group index bx of gx, slab bh -- as arguments, so that two of them can share one launch: see
+// "One launch for two jobs" below.)
+template <int D, bool ROPE, int NT = 256>
+__device__ __forceinline__ void k_colsum_body(const _Float16* __restrict__ k,
+                                              long long* __restrict__ part_out, int N, int chunk,
+                                              const float* __restrict__ cs, const float* __restrict__ sn,
+                                              int bx, int P, int bh) {
     constexpr int VPR = D / 8;          // 16-byte vectors per token row
-    constexpr int RG = 256 / VPR;       // row groups per workgroup
+    constexpr int RG = NT / VPR;        // row groups per workgroup
     constexpr int BATCH = 8;            // rows per thread in flight
     const int t = threadIdx.x, c8 = t % VPR, rg = t / VPR;
-    const int bh = blockIdx.y, P = gridDim.x;
-    const int row_begin = blockIdx.x * chunk;
+    const int row_begin = bx * chunk;
     const int row_end = row_begin + chunk < N ? row_begin + chunk : N;
     const _Float16* base = k + ((size_t)bh * N) * D;
 
@@ -128,8 +131,14 @@ __global__ void __launch_bounds__(256) k_colsum_kernel(const _Float16* __restric
         long long s = 0;
 #pragma unroll 4
         for (int g = 0; g < RG; ++g) s += part[g][t];
-        part_out[((size_t)bh * P + blockIdx.x) * D + t] = s;
+        part_out[((size_t)bh * P + bx) * D + t] = s;
     }
+}
+template <int D, bool ROPE>
+__global__ void __launch_bounds__(256) k_colsum_kernel(const _Float16* __restrict__ k,
+                                                       long long* __restrict__ part_out, int N, int chunk,
+                                                       const float* __restrict__ cs, const float* __restrict__ sn) {
+    k_colsum_body<D, ROPE>(k, part_out, N, chunk, cs, sn, blockIdx.x, gridDim.x, blockIdx.y);
 }
 
 // mean[c] of a slab from its P partial column sums: exact integer total, one fp64 division, one
@@ -164,17 +173,18 @@ __device__ __forceinline__ float wg_max(float v, float* red) {
 // of a block are issued before the first is used (rows past the end of the block are fetched from
 // its last row and ignored).
 template <int D, int LPT, bool IS_K, bool ROPE, int NT = 256>
-__global__ void __launch_bounds__(NT) quant_block_kernel(const _Float16* __restrict__ x,
-                                                          int8_t* __restrict__ xq,
-                                                          float* __restrict__ scale,
-                                                          float* __restrict__ k_mean,
-                                                          const long long* __restrict__ parts, int P,
-                                                          int N, int block, float sm_scale,
-                                                          const float* __restrict__ cs, const float* __restrict__ sn) {
+__device__ __forceinline__ void quant_block_body(const _Float16* __restrict__ x,
+                                                 int8_t* __restrict__ xq,
+                                                 float* __restrict__ scale,
+                                                 float* __restrict__ k_mean,
+                                                 const long long* __restrict__ parts, int P,
+                                                 int N, int block, float sm_scale,
+                                                 const float* __restrict__ cs, const float* __restrict__ sn,
+                                                 int bx, int gx, int bh) {
     constexpr int VPR = D / 8;
     constexpr int RSTEP = NT / VPR;
     const int t = threadIdx.x, c8 = t % VPR, rbase = t / VPR;
-    const int bh = blockIdx.y, nblk = (N + block - 1) / block;
+    const int nblk = (N + block - 1) / block;
 
     __shared__ float s_mean[D];
     __shared__ float s_red[2][NT / 64];
@@ -192,7 +202,7 @@ __global__ void __launch_bounds__(NT) quant_block_kernel(const _Float16* __restr
         }
     };
     h8 raw[LPT], ahead[LPT];
-    int g = blockIdx.x;            // the launcher never starts more workgroups than there are blocks
+    int g = bx;                    // the launcher never starts more workgroups than there are blocks
     load_block(g, raw);            // in flight while the mean is formed
 
     float mean[8];
@@ -200,20 +210,20 @@ __global__ void __launch_bounds__(NT) quant_block_kernel(const _Float16* __restr
         if (t < D) {
             const float m = slab_mean<D>(parts, bh, P, N, t);
             s_mean[t] = m;
-            if (blockIdx.x == 0 && k_mean != nullptr) k_mean[(size_t)bh * D + t] = m;
+            if (bx == 0 && k_mean != nullptr) k_mean[(size_t)bh * D + t] = m;
         }
         __syncthreads();
 #pragma unroll
         for (int e = 0; e < 8; ++e) mean[e] = s_mean[c8 * 8 + e];
     }
 
-    for (int turn = 0; g < nblk; g += gridDim.x, turn ^= 1) {
+    for (int turn = 0; g < nblk; g += gx, turn ^= 1) {
         const int row0 = g * block;
         const int rows = (N - row0 < block) ? (N - row0) : block;
         const size_t slab = ((size_t)bh * N + row0) * D + c8 * 8;
         // the next block of this workgroup is requested before this one is reduced and stored
-        const bool more = g + (int)gridDim.x < nblk;
-        if (more) load_block(g + gridDim.x, ahead);
+        const bool more = g + gx < nblk;
+        if (more) load_block(g + gx, ahead);
         float amax = 0.0f;
 #pragma unroll
         for (int i = 0; i < LPT; ++i) {
@@ -251,6 +261,15 @@ __global__ void __launch_bounds__(NT) quant_block_kernel(const _Float16* __restr
         }
     }
 }
+template <int D, int LPT, bool IS_K, bool ROPE, int NT = 256>
+__global__ void __launch_bounds__(NT) quant_block_kernel(const _Float16* __restrict__ x, int8_t* __restrict__ xq,
+                                                          float* __restrict__ scale, float* __restrict__ k_mean,
+                                                          const long long* __restrict__ parts, int P,
+                                                          int N, int block, float sm_scale,
+                                                          const float* __restrict__ cs, const float* __restrict__ sn) {
+    quant_block_body<D, LPT, IS_K, ROPE, NT>(x, xq, scale, k_mean, parts, P, N, block, sm_scale, cs, sn,
+                                             blockIdx.x, gridDim.x, blockIdx.y);
+}
 
 // Per-token quantizer (Section 3.2): one scale per token row.  D/8 adjacent lanes own a row
 // (16 bytes each); the row's absmax is a butterfly over those lanes.  A workgroup takes groups of
@@ -259,18 +278,19 @@ __global__ void __launch_bounds__(NT) quant_block_kernel(const _Float16* __restr
 // not stored).
 constexpr int TOK_LPT = 8;
 template <int D, bool IS_K, bool ROPE>
-__global__ void __launch_bounds__(256) quant_token_kernel(const _Float16* __restrict__ x,
-                                                          int8_t* __restrict__ xq,
-                                                          float* __restrict__ scale,
-                                                          float* __restrict__ k_mean,
-                                                          const long long* __restrict__ parts, int P,
-                                                          int N, float sm_scale,
-                                                          const float* __restrict__ cs, const float* __restrict__ sn) {
+__device__ __forceinline__ void quant_token_body(const _Float16* __restrict__ x,
+                                                 int8_t* __restrict__ xq,
+                                                 float* __restrict__ scale,
+                                                 float* __restrict__ k_mean,
+                                                 const long long* __restrict__ parts, int P,
+                                                 int N, float sm_scale,
+                                                 const float* __restrict__ cs, const float* __restrict__ sn,
+                                                 int bx, int gx, int bh) {
     constexpr int VPR = D / 8;
     constexpr int RSTEP = 256 / VPR;
     constexpr int ROWS = RSTEP * TOK_LPT;
     const int t = threadIdx.x, c8 = t % VPR, rbase = t / VPR;
-    const int bh = blockIdx.y, ngrp = (N + ROWS - 1) / ROWS;
+    const int ngrp = (N + ROWS - 1) / ROWS;
 
     __shared__ float s_mean[D];
     float mean[8];
@@ -278,14 +298,14 @@ __global__ void __launch_bounds__(256) quant_token_kernel(const _Float16* __rest
         if (t < D) {
             const float m = slab_mean<D>(parts, bh, P, N, t);
             s_mean[t] = m;
-            if (blockIdx.x == 0 && k_mean != nullptr) k_mean[(size_t)bh * D + t] = m;
+            if (bx == 0 && k_mean != nullptr) k_mean[(size_t)bh * D + t] = m;
         }
         __syncthreads();
 #pragma unroll
         for (int e = 0; e < 8; ++e) mean[e] = s_mean[c8 * 8 + e];
     }
 
-    for (int grp = blockIdx.x; grp < ngrp; grp += gridDim.x) {
+    for (int grp = bx; grp < ngrp; grp += gx) {
         const int row0 = grp * ROWS;
         const _Float16* xs = x + (size_t)bh * N * D;
         h8 raw[TOK_LPT];
@@ -324,6 +344,14 @@ __global__ void __launch_bounds__(256) quant_token_kernel(const _Float16* __rest
         }
     }
 }
+template <int D, bool IS_K, bool ROPE>
+__global__ void __launch_bounds__(256) quant_token_kernel(const _Float16* __restrict__ x, int8_t* __restrict__ xq,
+                                                          float* __restrict__ scale, float* __restrict__ k_mean,
+                                                          const long long* __restrict__ parts, int P,
+                                                          int N, float sm_scale,
+                                                          const float* __restrict__ cs, const float* __restrict__ sn) {
+    quant_token_body<D, IS_K, ROPE>(x, xq, scale, k_mean, parts, P, N, sm_scale, cs, sn, blockIdx.x, gridDim.x, blockIdx.y);
+}
 
 // Short sequences (N <= SMALL_N): the whole K pre-pass of one (batch, head) slab in ONE workgroup
 // and one launch -- exact column sums, mean, then the quantization blocks one after the other
@@ -333,17 +361,16 @@ __global__ void __launch_bounds__(256) quant_token_kernel(const _Float16* __rest
 // at N = 197, slower at N = 1105), hence the low limit.
 constexpr int SMALL_N = 512;
 template <int D, bool ROPE>
-__global__ void __launch_bounds__(256) k_small_kernel(const _Float16* __restrict__ k,
-                                                      int8_t* __restrict__ kq,
-                                                      float* __restrict__ scale,
-                                                      float* __restrict__ k_mean,
-                                                      int N, int block,
-                                                      const float* __restrict__ cs, const float* __restrict__ sn) {
+__device__ __forceinline__ void k_small_body(const _Float16* __restrict__ k,
+                                             int8_t* __restrict__ kq,
+                                             float* __restrict__ scale,
+                                             float* __restrict__ k_mean,
+                                             int N, int block,
+                                             const float* __restrict__ cs, const float* __restrict__ sn, int bh) {
     constexpr int VPR = D / 8;
     constexpr int RG = 256 / VPR;
     constexpr int HALF = D / 2;
     const int t = threadIdx.x, c8 = t % VPR, rg = t / VPR;
-    const int bh = blockIdx.x;
     const _Float16* base = k + ((size_t)bh * N) * D;
 
     __shared__ long long part[RG][D];
@@ -444,6 +471,14 @@ __global__ void __launch_bounds__(256) k_small_kernel(const _Float16* __restrict
     }
 }
 
+template <int D, bool ROPE>
+__global__ void __launch_bounds__(256) k_small_kernel(const _Float16* __restrict__ k, int8_t* __restrict__ kq,
+                                                      float* __restrict__ scale, float* __restrict__ k_mean,
+                                                      int N, int block,
+                                                      const float* __restrict__ cs, const float* __restrict__ sn) {
+    k_small_body<D, ROPE>(k, kq, scale, k_mean, N, block, cs, sn, blockIdx.x);
+}
+
 // Workgroups per slab of the quantizer kernels: enough to fill the chip a few times over, few
 // enough that a workgroup of the K side walks several blocks per read of the partial sums.
 static int quant_groups(int BH, int units) {
@@ -541,6 +576,96 @@ hipError_t launch_smooth_quant_k(const void* k, int8_t* kq, float* kscale, float
                              : smooth_quant_k_d<64, false>(k, kq, kscale, kmean, parts, BH, N, block, cs, sn, st);
     return rope ? smooth_quant_k_d<128, true>(k, kq, kscale, kmean, parts, BH, N, block, cs, sn, st)
                 : smooth_quant_k_d<128, false>(k, kq, kscale, kmean, parts, BH, N, block, cs, sn, st);
+}
+
+// ---- One launch for two jobs (sage_quant_qk) -----------------------------------------------------
+// The quantization of Q (Section 4.6 + 3.2) depends on nothing the K side computes, and the K side
+// needs a grid-wide result (the mean, Section 4.2) between its two halves.  So the first launch of the
+// pair does the K side's first half AND all of Q: workgroups 0 .. n_k - 1 of a slab's row of the grid
+// run the K job, the others the Q job; the second launch is the K quantizer as it is.  For short key
+// sequences the K job is the whole K pre-pass of the slab (k_small_body) and there is no second launch.
+// Same bodies, same arithmetic, same bits as the separate calls; one launch (a few microseconds, which
+// is what short sequences are made of) less.
+template <int D, int LPT, int NT, bool SMALL_K>
+__global__ void __launch_bounds__(NT) qk_first_block_kernel(const _Float16* __restrict__ k, long long* __restrict__ parts,
+                                                             int8_t* __restrict__ kq, float* __restrict__ kscale,
+                                                             float* __restrict__ kmean, int Nkv, int chunk, int block_k, int n_k,
+                                                             const _Float16* __restrict__ q, int8_t* __restrict__ qq,
+                                                             float* __restrict__ qscale, int Nq, int block_q, float sm_scale) {
+    const int bx = blockIdx.x, bh = blockIdx.y;
+    if (bx < n_k) {
+        if constexpr (SMALL_K) k_small_body<D, false>(k, kq, kscale, kmean, Nkv, block_k, nullptr, nullptr, bh);
+        else k_colsum_body<D, false, NT>(k, parts, Nkv, chunk, nullptr, nullptr, bx, n_k, bh);
+    } else {
+        quant_block_body<D, LPT, false, false, NT>(q, qq, qscale, nullptr, nullptr, 0, Nq, block_q, sm_scale, nullptr, nullptr,
+                                                   bx - n_k, (int)gridDim.x - n_k, bh);
+    }
+}
+template <int D, bool SMALL_K>
+__global__ void __launch_bounds__(256) qk_first_token_kernel(const _Float16* __restrict__ k, long long* __restrict__ parts,
+                                                             int8_t* __restrict__ kq, float* __restrict__ kscale,
+                                                             float* __restrict__ kmean, int Nkv, int chunk, int block_k, int n_k,
+                                                             const _Float16* __restrict__ q, int8_t* __restrict__ qq,
+                                                             float* __restrict__ qscale, int Nq, float sm_scale) {
+    const int bx = blockIdx.x, bh = blockIdx.y;
+    if (bx < n_k) {
+        if constexpr (SMALL_K) k_small_body<D, false>(k, kq, kscale, kmean, Nkv, block_k, nullptr, nullptr, bh);
+        else k_colsum_body<D, false, 256>(k, parts, Nkv, chunk, nullptr, nullptr, bx, n_k, bh);
+    } else {
+        quant_token_body<D, false, false>(q, qq, qscale, nullptr, nullptr, 0, Nq, sm_scale, nullptr, nullptr,
+                                          bx - n_k, (int)gridDim.x - n_k, bh);
+    }
+}
+
+template <int D, bool SMALL_K>
+static hipError_t quant_qk_first(const void* q, const void* k, int8_t* qq, float* qscale, int8_t* kq, float* kscale,
+                                 float* kmean, long long* parts, int BH, int Nq, int Nkv, float sm_scale,
+                                 int block_q, int block_k, const ColsumPlan& cp, hipStream_t st) {
+    const _Float16* qp = (const _Float16*)q;
+    const _Float16* kp = (const _Float16*)k;
+    const int n_k = SMALL_K ? 1 : cp.parts;
+    if (block_q == 1) {
+        constexpr int ROWS = (256 / (D / 8)) * TOK_LPT;
+        const int ngrp = (Nq + ROWS - 1) / ROWS;
+        qk_first_token_kernel<D, SMALL_K><<<dim3(n_k + ngrp, BH), 256, 0, st>>>(kp, parts, kq, kscale, kmean, Nkv, cp.chunk,
+                                                                               block_k, n_k, qp, qq, qscale, Nq, sm_scale);
+        return hipGetLastError();
+    }
+    const int nblk = (Nq + block_q - 1) / block_q;
+    const dim3 grid(n_k + quant_groups(BH, nblk), BH);
+#define SAGE_QK(LPT, NT) qk_first_block_kernel<D, LPT, NT, SMALL_K><<<grid, NT, 0, st>>>(kp, parts, kq, kscale, kmean, Nkv, cp.chunk, block_k, n_k, qp, qq, qscale, Nq, block_q, sm_scale)
+    switch (block_q * D / 2048) {
+        case 1: SAGE_QK(1, 256); break;
+        case 2: SAGE_QK(2, 256); break;
+        case 4: SAGE_QK(4, 256); break;
+        case 8:
+            // (the single-workgroup K job is written for 256 threads: 8 rows per thread on the Q side there)
+            if constexpr (SMALL_K) SAGE_QK(8, 256);
+            else SAGE_QK(4, 512);
+            break;
+        default: return hipErrorInvalidValue;
+    }
+#undef SAGE_QK
+    return hipGetLastError();
+}
+
+template <int D>
+static hipError_t quant_qk_d(const void* q, const void* k, int8_t* qq, float* qscale, int8_t* kq, float* kscale,
+                             float* kmean, long long* parts, int BH, int Nq, int Nkv, float sm_scale,
+                             int block_q, int block_k, hipStream_t st) {
+    const ColsumPlan cp = plan_colsum(BH, Nkv);
+    if (Nkv <= SMALL_N)
+        return quant_qk_first<D, true>(q, k, qq, qscale, kq, kscale, kmean, parts, BH, Nq, Nkv, sm_scale, block_q, block_k, cp, st);
+    hipError_t e = quant_qk_first<D, false>(q, k, qq, qscale, kq, kscale, kmean, parts, BH, Nq, Nkv, sm_scale, block_q, block_k, cp, st);
+    if (e != hipSuccess) return e;
+    return launch_quant<D, true, false>(k, kq, kscale, kmean, parts, cp.parts, BH, Nkv, block_k, 1.0f, nullptr, nullptr, st);
+}
+
+hipError_t launch_quant_qk(const void* q, const void* k, int8_t* qq, float* qscale, int8_t* kq, float* kscale,
+                           float* kmean, long long* parts, int BH, int Nq, int Nkv, int D, float sm_scale,
+                           int block_q, int block_k, hipStream_t st) {
+    if (D == 64) return quant_qk_d<64>(q, k, qq, qscale, kq, kscale, kmean, parts, BH, Nq, Nkv, sm_scale, block_q, block_k, st);
+    return quant_qk_d<128>(q, k, qq, qscale, kq, kscale, kmean, parts, BH, Nq, Nkv, sm_scale, block_q, block_k, st);
 }
 
 }  // namespace sage

@@ -88,6 +88,15 @@ def test_host_validation_rejects_bad_arguments_before_any_launch(lib):
     assert lib.sage_attn_clock_debug(good, good, good, good, good, good, good, 1, 1, 64, 128, 0, 1, 1, None) == 3
     assert lib.sage_attn_clock_debug(good, good, good, good, good, good, good, 0, 1, 64, 128, 0, 128, 64, None) == 2
     assert lib.sage_attn_clock_debug(good, good, good, good, good, good, odd, 1, 1, 64, 128, 0, 128, 64, None) == 5
+    # both pre-passes in one call: the checks of either side
+    sz = ctypes.c_size_t
+    assert lib.sage_quant_qk(good, None, good, good, good, good, good, good, sz(1 << 20), 1, 1, 64, 64, 64, f(0.125), 64, 64, None) == 1
+    assert lib.sage_quant_qk(good, good, good, good, good, good, good, good, sz(8), 1, 1, 64, 1024, 64, f(0.125), 64, 64, None) == 4
+    assert lib.sage_quant_qk(good, good, good, good, good, good, good, good, sz(1 << 20), 1, 1, 0, 64, 64, f(0.125), 64, 64, None) == 2
+    assert lib.sage_quant_qk(good, good, good, good, good, good, good, good, sz(1 << 20), 1, 1, 64, 64, 64, f(0.125), 48, 64, None) == 3
+    assert lib.sage_quant_qk(good, good, good, good, good, good, good, good, sz(1 << 20), 1, 1, 64, 64, 64, f(0.125), 64, 48, None) == 3
+    assert lib.sage_quant_qk(good, good, good, good, good, good, good, good, sz(1 << 20), 1, 1, 64, 64, 64, f(0.0), 64, 64, None) == 7
+    assert lib.sage_quant_qk(good, odd, good, good, good, good, good, good, sz(1 << 20), 1, 1, 64, 64, 64, f(0.125), 64, 64, None) == 5
     # more (batch, head) slabs than the documented limit
     assert lib.sage_quant_q(good, good, good, 256, 256, 64, 64, f(0.125), 64, None) == 2
     # the fused-RoPE calls: tables required and 16-byte aligned, everything else as the unfused calls
