@@ -354,11 +354,12 @@ __global__ void __launch_bounds__(256) quant_token_kernel(const _Float16* __rest
 }
 
 // Short sequences (N <= SMALL_N): the whole K pre-pass of one (batch, head) slab in ONE workgroup
-// and one launch -- exact column sums, mean, then the quantization blocks one after the other
-// (the slab is re-read from cache).  The launches of a few microseconds each become one; the
-// results are the same bits (the integer sum does not depend on how it is split).  Beyond a few
-// blocks per slab the serial loop over blocks loses against the wide launches (measured: faster
-// at N = 197, slower at N = 1105), hence the low limit.
+// and one launch.  The slab is read ONCE, all loads in flight together, and stays in registers
+// (at most SMALL_N / RG rows of 16 bytes per thread): exact column sums, mean, per-block (or
+// per-token) maxima and the quantization all work on those registers -- one memory round trip, two
+// barriers.  The results are the same bits as the wide kernels' (the integer sum does not depend on
+// how it is split).  Beyond a few blocks per slab one workgroup per slab loses against the wide
+// launches (measured: faster at N = 197, slower at N = 1105), hence the low limit.
 constexpr int SMALL_N = 512;
 template <int D, bool ROPE>
 __device__ __forceinline__ void k_small_body(const _Float16* __restrict__ k,
@@ -370,32 +371,46 @@ __device__ __forceinline__ void k_small_body(const _Float16* __restrict__ k,
     constexpr int VPR = D / 8;
     constexpr int RG = 256 / VPR;
     constexpr int HALF = D / 2;
+    constexpr int MAXR = SMALL_N / RG;        // rows per thread: row rg + i * RG in register set i
+    constexpr int MAXB = SMALL_N / 32;        // blocks per slab at the smallest block size
     const int t = threadIdx.x, c8 = t % VPR, rg = t / VPR;
     const _Float16* base = k + ((size_t)bh * N) * D;
 
     __shared__ long long part[RG][D];
     __shared__ float s_mean[D];
-    __shared__ float s_red[2][4];
+    __shared__ float s_red[MAXB][4];
 
-    // ---- exact column sums: at most SMALL_N / RG = 32 rows per thread, in two int32 parts each
-    // (|integer part| <= 65504, fraction * 2^24 < 2^24: 32 of either stay far below 2^31)
-    int acc_hi[8], acc_lo[8];
+    // register sets 0 .. nset - 1 hold rows (a wave-uniform count); a row past N inside the last set is
+    // fetched from row N - 1 (no per-lane branch around a load) and left out of every sum and maximum
+    const int nset = (N + RG - 1) / RG;
+    h8 x[MAXR];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) { acc_hi[e] = 0; acc_lo[e] = 0; }
-    for (int r = rg; r < N; r += RG) {
-        const h8 x = load_row8<D, ROPE>(base + (size_t)r * D, c8, cs + (size_t)r * HALF, sn + (size_t)r * HALF);
+    for (int i = 0; i < MAXR; ++i) {
+        if (i < nset) {
+            const int r = rg + i * RG, rc = r < N ? r : N - 1;
+            x[i] = load_row8<D, ROPE>(base + (size_t)rc * D, c8, cs + (size_t)rc * HALF, sn + (size_t)rc * HALF);
+        }
+    }
+    // ---- exact column sums in fp64: multiples of 2^-24 below 2^16 in magnitude, at most 32 per thread --
+    // every partial sum fits 53 bits; then an exact conversion to a count of 2^-24 units
+    double acc_d[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const float f = (float)x[e];
-            const float hi = __builtin_truncf(f);
-            const float lo = f - hi;
-            acc_hi[e] += (int)hi;
-            acc_lo[e] += (int)(lo * 16777216.0f);
+    for (int e = 0; e < 8; ++e) acc_d[e] = 0.0;
+#pragma unroll
+    for (int i = 0; i < MAXR; ++i) {
+        if (i < nset) {
+            const double live = rg + i * RG < N ? 1.0 : 0.0;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc_d[e] += live * (double)(float)x[i][e];
         }
     }
 #pragma unroll
-    for (int e = 0; e < 8; ++e)
-        part[rg][c8 * 8 + e] = (long long)acc_hi[e] * 16777216ll + (long long)acc_lo[e];
+    for (int e = 0; e < 8; ++e) {
+        const double v = acc_d[e] * 16777216.0;          // |v| < 2^46
+        const double hi = __builtin_trunc(v * 0x1p-26);
+        const double lo = v - hi * 0x1p26;
+        part[rg][c8 * 8 + e] = (long long)(int)hi * (1ll << 26) + (long long)(int)lo;
+    }
     __syncthreads();
     if (t < D) {
         long long sum = 0;
@@ -422,51 +437,65 @@ __device__ __forceinline__ void k_small_body(const _Float16* __restrict__ k,
         }
         *(uint2*)(qbase + (size_t)r * D) = make_uint2(w[0], w[1]);
     };
+    auto row_amax = [&](const h8& raw) {
+        float a = 0.0f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) a = __builtin_fmaxf(a, __builtin_fabsf((float)raw[e] - mean[e]));
+        return a;
+    };
 
     if (block == 1) {
         // per-token scales: the VPR lanes of a row reduce among themselves
-        for (int r0 = 0; r0 < N; r0 += RG) {
-            const int r = r0 + rg;
-            h8 raw = (h8){0, 0, 0, 0, 0, 0, 0, 0};
-            if (r < N) raw = load_row8<D, ROPE>(base + (size_t)r * D, c8, cs + (size_t)r * HALF, sn + (size_t)r * HALF);
-            float amax = 0.0f;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) amax = __builtin_fmaxf(amax, __builtin_fabsf((float)raw[e] - mean[e]));
+        for (int i = 0; i < MAXR; ++i) {
+            if (i < nset) {
+                const int r = rg + i * RG;
+                float amax = row_amax(x[i]);
 #pragma unroll
-            for (int off = VPR / 2; off >= 1; off >>= 1) amax = __builtin_fmaxf(amax, __shfl_xor(amax, off, 64));
-            if (r < N) {
-                if (c8 == 0) scale[(size_t)bh * N + r] = amax / 127.0f;
-                quantize_row(raw, amax > 0.0f ? 127.0f / amax : 0.0f, r);
+                for (int off = VPR / 2; off >= 1; off >>= 1) amax = __builtin_fmaxf(amax, __shfl_xor(amax, off, 64));
+                if (r < N) {
+                    if (c8 == 0) scale[(size_t)bh * N + r] = amax / 127.0f;
+                    quantize_row(x[i], amax > 0.0f ? 127.0f / amax : 0.0f, r);
+                }
             }
         }
         return;
     }
 
-    // per-block scales: block * D = 2048 * lpt elements, lpt <= 8 rows per thread
+    // per-block scales.  block = lpt * RG rows: register sets lpt * g .. lpt * g + lpt - 1 of every thread are
+    // block g (lpt a power of two; the same for every thread).  Every thread folds its rows of a block, the
+    // wavefront reduces by shuffles and leaves its maximum in LDS; after ONE barrier every block's maximum
+    // is the largest of four words.  (A row past N holds zeros: |0 - mean| may exceed the block's true
+    // maximum, so such rows are left out.)
     const int nblk = (N + block - 1) / block;
     const int lpt = block / RG;
-    for (int g = 0; g < nblk; ++g) {
-        const int row0 = g * block;
-        const int rows = (N - row0 < block) ? (N - row0) : block;
-        h8 raw[8];
-        float amax = 0.0f;
+    const int wave = t >> 6;
+    float cur = 0.0f;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int r = rg + i * RG;
-            if (i < lpt && r < rows) {
-                raw[i] = load_row8<D, ROPE>(base + (size_t)(row0 + r) * D, c8, cs + (size_t)(row0 + r) * HALF,
-                                            sn + (size_t)(row0 + r) * HALF);
-#pragma unroll
-                for (int e = 0; e < 8; ++e) amax = __builtin_fmaxf(amax, __builtin_fabsf((float)raw[i][e] - mean[e]));
-            }
+    for (int i = 0; i < MAXR; ++i) {
+        if (i < nset) {
+            const float a = row_amax(x[i]);
+            cur = rg + i * RG < N ? __builtin_fmaxf(cur, a) : cur;
         }
-        amax = wg_max(amax, s_red[g & 1]);       // alternating buffers: one barrier per block is enough
-        if (t == 0) scale[(size_t)bh * nblk + g] = amax / 127.0f;
-        const float rcp = amax > 0.0f ? 127.0f / amax : 0.0f;
+        if (((i + 1) & (lpt - 1)) == 0 && i / lpt < nblk) {          // last register set of block i / lpt (uniform)
+            float m = cur;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int r = rg + i * RG;
-            if (i < lpt && r < rows) quantize_row(raw[i], rcp, row0 + r);
+            for (int off = 32; off >= 1; off >>= 1) m = __builtin_fmaxf(m, __shfl_xor(m, off, 64));
+            if ((t & 63) == 0) s_red[i / lpt][wave] = m;
+            cur = 0.0f;
+        }
+    }
+    __syncthreads();
+    if (t < nblk) {
+        const float amax = __builtin_fmaxf(__builtin_fmaxf(s_red[t][0], s_red[t][1]), __builtin_fmaxf(s_red[t][2], s_red[t][3]));
+        scale[(size_t)bh * nblk + t] = amax / 127.0f;
+    }
+#pragma unroll
+    for (int i = 0; i < MAXR; ++i) {
+        if (i < nset) {
+            const int r = rg + i * RG, g = i / lpt;
+            const float amax = __builtin_fmaxf(__builtin_fmaxf(s_red[g][0], s_red[g][1]), __builtin_fmaxf(s_red[g][2], s_red[g][3]));
+            if (r < N) quantize_row(x[i], amax > 0.0f ? 127.0f / amax : 0.0f, r);
         }
     }
 }
