@@ -377,9 +377,9 @@ def main():
                          "last Nq tokens of the workload as queries against all of its keys; comma-separated list of Nq")
     ap.add_argument("--rotate", type=int, default=1,
                     help="number of distinct input allocations used in turn (1 = every step reads the same buffers)")
-    ap.add_argument("--prepass", choices=("separate", "fused"), default="separate",
-                    help="separate: sage_smooth_quant_k + sage_quant_q (three launches; one fewer for short sequences); "
-                         "fused: sage_quant_qk, the same work in one launch less")
+    ap.add_argument("--prepass", choices=("separate", "fused"), default="fused",
+                    help="fused: sage_quant_qk, both pre-passes in two launches (one for short sequences); "
+                         "separate: sage_smooth_quant_k + sage_quant_q, the same work and the same bits in one launch more")
     ap.add_argument("--clock-study", action="store_true",
                     help="table: the attention kernel's time, clock and clocks per tile on the workload's tensors with the "
                          "key scales multiplied by several factors (the spread of the scores changes, the work does not)")
@@ -597,7 +597,8 @@ def main():
                                + ("; RoPE applied inside the pre-pass" if args.rope else "")
                                + ("; timed as replays of a HIP graph of one step" if args.graph else "")
                                + ("; INT8 P~V (SAGEAttn-v%s)" % ("T" if per_token else "B") if pv_int8 else "")
-                               + "; step = K pre-pass + Q pre-pass + " + ("V pre-pass + " if pv_int8 else "") + "attention"},
+                               + "; step = K pre-pass + Q pre-pass " + ("(sage_quant_qk) + " if args.prepass == "fused" and not args.rope else "(separate calls) + ")
+                               + ("V pre-pass + " if pv_int8 else "") + "attention"},
         "attn_kernel_ms": attn_ms,
         "prepass_ms": pre_ms,
         "attn_only_tops": attn_tops,

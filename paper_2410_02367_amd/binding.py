@@ -508,8 +508,7 @@ def sageattn(q, k, v, causal: bool = False, sm_scale: float | None = None, block
     D = q.shape[-1]
     if sm_scale is None:
         sm_scale = sage_default_sm_scale(D)
-    k_i8, k_scale, _ = sage_smooth_quant_k(k, block_k)
-    q_i8, q_scale = sage_quant_q(q, sm_scale, block_q)
+    q_i8, q_scale, k_i8, k_scale, _ = sage_quant_qk(q, k, sm_scale, block_q, block_k)
     same = q.shape[2] == k.shape[2]
     if pv_int8:
         v_i8t, v_scale = sage_quant_v(v)
