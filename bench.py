@@ -46,7 +46,7 @@ def profiled_traffic(workload: str, pv_int8: bool):
 # Probes of sage_microbench (include/sage.h): operations per instruction group
 PROBE_OPS = {0: 8 * 65536.0, 1: 8 * 32768.0, 2: 8 * 65536.0 + 16 * 32768.0, 4: 8 * 32768.0, 5: 8 * 32768.0,
              6: 8 * 65536.0 + 16 * 32768.0, 9: 8 * 65536.0 + 16 * 32768.0,
-             15: 8 * 65536.0 + 16 * 32768.0, 16: 8 * 65536.0 + 16 * 32768.0,
+             15: 8 * 65536.0 + 16 * 32768.0, 16: 8 * 65536.0 + 16 * 32768.0, 17: 8 * 32768.0, 18: 8 * 65536.0, 19: 8 * 65536.0 + 16 * 32768.0, 20: 2 * (8 * 65536.0 + 16 * 32768.0),
              11: 16 * 32768.0, 12: 16 * 32768.0, 13: 16 * 32768.0, 14: 8 * 65536.0}      # kinds 11 to 13: the 16 P~V instructions only
 PROBE_NAMES = {0: "INT8 32x32x32 stream", 1: "FP16 32x32x16 stream", 2: "attention mix: 8 INT8 + 16 FP16, matrix only",
                3: "softmax chunks only (24 per group)", 4: "FP16 matrix instruction + softmax chunk, one stream",
@@ -61,11 +61,15 @@ PROBE_NAMES = {0: "INT8 32x32x32 stream", 1: "FP16 32x32x16 stream", 2: "attenti
                13: "4 x (4 + 1 FP16 32x32x16)",
                14: "INT8 32x32x32 stream, one accumulator (dependent chain)",
                15: "attention step in the kernel's order: maxima, chunks behind 16 instructions, row sums",
-               16: "kind 15 with the chunks spread over 20 instructions"}
+               16: "kind 15 with the chunks spread over 20 instructions",
+               17: "FP16 16x16x32 stream (16 instructions = kind 1's operations)",
+               18: "INT8 16x16x64 stream (16 instructions = kind 0's operations)",
+               19: "kind 15 with the 16x16 instructions (every LDS operand feeds two of them)",
+               20: "kind 19 for 64 queries per wavefront (every LDS operand feeds four instructions)"}
 # matrix-pipe clocks per group (32 per 32x32 instruction) -- what a fully busy pipe needs
-PROBE_PIPE_CLOCKS = {0: 256, 1: 256, 2: 768, 4: 256, 5: 256, 6: 768, 9: 768, 11: 512, 12: 512, 13: 512, 14: 256, 15: 768, 16: 768}
+PROBE_PIPE_CLOCKS = {0: 256, 1: 256, 2: 768, 4: 256, 5: 256, 6: 768, 9: 768, 11: 512, 12: 512, 13: 512, 14: 256, 15: 768, 16: 768, 17: 256, 18: 256, 19: 768, 20: 1536}
 # LDS bytes a wavefront reads per group (kinds 7 to 9)
-PROBE_LDS_BYTES = {7: 24 * 1024, 8: 24 * 1024, 9: 24 * 1024, 15: 24 * 1024, 16: 24 * 1024}
+PROBE_LDS_BYTES = {7: 24 * 1024, 8: 24 * 1024, 9: 24 * 1024, 15: 24 * 1024, 16: 24 * 1024, 19: 24 * 1024, 20: 24 * 1024}
 
 
 def run_probe(sage, torch, data, kind, waves, seconds, workgroups=1024):
@@ -107,10 +111,10 @@ def microbench(seconds: float):
     print(f"instruction-stream probes, about {seconds:g} s per launch, random operand bits; "
           f"nominal peaks: INT8 {INT8_PEAK_TOPS:.0f} TOPS, FP16 {FP16_PEAK_TFLOPS:.0f} TFLOP/s at 2.4 GHz")
     print("%-4s %-78s %5s %9s %9s %8s %10s %9s %8s" % ("kind", "probe", "waves", "ms", "TOPS", "% peak", "ticks/grp", "pipe busy", "GHz"))
-    for kind, waves in ((0, 1), (0, 2), (1, 1), (1, 2), (2, 1), (2, 2), (3, 1), (3, 2), (4, 1), (4, 2), (5, 2), (6, 1), (6, 2), (7, 1), (7, 2), (8, 1), (8, 2), (9, 1), (9, 2), (10, 1), (11, 1), (11, 2), (12, 1), (12, 2), (13, 1), (14, 1), (14, 2), (15, 1), (15, 2), (16, 1), (16, 2)):
+    for kind, waves in ((0, 1), (0, 2), (1, 1), (1, 2), (2, 1), (2, 2), (3, 1), (3, 2), (4, 1), (4, 2), (5, 2), (6, 1), (6, 2), (7, 1), (7, 2), (8, 1), (8, 2), (9, 1), (9, 2), (10, 1), (11, 1), (11, 2), (12, 1), (12, 2), (13, 1), (14, 1), (14, 2), (15, 1), (15, 2), (16, 1), (16, 2), (17, 1), (17, 2), (18, 1), (18, 2), (19, 1), (19, 2), (20, 1), (20, 2)):
         # 256 workgroups: one per compute unit, `waves` wavefronts per SIMD
         ms, tops, ticks, ghz, iters = run_probe(sage, torch, data, kind, waves, seconds, workgroups=256)
-        peak = {0: INT8_PEAK_TOPS, 14: INT8_PEAK_TOPS, 1: FP16_PEAK_TFLOPS, 4: FP16_PEAK_TFLOPS, 5: FP16_PEAK_TFLOPS, 11: FP16_PEAK_TFLOPS,
+        peak = {0: INT8_PEAK_TOPS, 14: INT8_PEAK_TOPS, 18: INT8_PEAK_TOPS, 17: FP16_PEAK_TFLOPS, 1: FP16_PEAK_TFLOPS, 4: FP16_PEAK_TFLOPS, 5: FP16_PEAK_TFLOPS, 11: FP16_PEAK_TFLOPS,
                 12: FP16_PEAK_TFLOPS, 13: FP16_PEAK_TFLOPS}.get(kind, INT8_PEAK_TOPS)
         busy = PROBE_PIPE_CLOCKS[kind] * (1 if kind == 5 else waves) / ticks if kind in PROBE_PIPE_CLOCKS else float("nan")
         lds = ""

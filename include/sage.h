@@ -363,10 +363,16 @@ int sage_attn_clock_debug(const int8_t* q_i8, const float* q_scale, const int8_t
  *           4 .. 19 (the last 8 overwrite the scores the chunks read)
  *   kind 16 kind 15 with the chunks spread over instructions 4 .. 23 instead (what a second set of score
  *           registers would allow)
+ *   kind 17 16 FP16 16x16x32 matrix instructions (kind 1's operations in the shape with a quarter of the result
+ *           block and twice the contraction depth);  kind 18  16 INT8 16x16x64 instructions (kind 0's operations)
+ *   kind 19 kind 15 built from the 16x16 instructions: every operand read from LDS feeds two of them (two
+ *           16-query blocks), 32 FP16 + 16 INT8 + 4 row-sum instructions per step
+ *   kind 20 kind 19 for a wavefront of 64 queries: every operand feeds four 16x16 instructions, twice the
+ *           softmax work, the same LDS reads (twice kind 15's operations per group)
  *   data    in  1024 int32 of arbitrary (random) bits: the operands; 16-byte aligned
  *   out     out 4 uint64 per wavefront ([workgroups * 4 * waves_per_simd][4]): shader-clock ticks of the
  *           loop, constant-rate-counter ticks of the loop, a checksum, 0
- * Errors as everywhere; SAGE_ERR_UNSUPPORTED for an unknown kind or waves_per_simd not in {1, 2}.
+ * Errors as everywhere; SAGE_ERR_UNSUPPORTED for an unknown kind (0 .. 20 exist) or waves_per_simd not in {1, 2}.
  */
 int sage_microbench(int kind, int waves_per_simd, int workgroups, int iters,
                     const int32_t* data, uint64_t* out, void* stream);

@@ -297,7 +297,7 @@ int sage_quant_v(const void* v_f16, int8_t* v_i8t, float* v_scale, void* workspa
 int sage_microbench(int kind, int waves_per_simd, int workgroups, int iters,
                     const int32_t* data, uint64_t* out, void* stream) {
     if (!data || !out) return SAGE_ERR_NULL;
-    if (kind < 0 || kind > 16 || (waves_per_simd != 1 && waves_per_simd != 2)) return SAGE_ERR_UNSUPPORTED;
+    if (kind < 0 || kind > 20 || (waves_per_simd != 1 && waves_per_simd != 2)) return SAGE_ERR_UNSUPPORTED;
     if (kind == 5 && waves_per_simd != 2) return SAGE_ERR_UNSUPPORTED;
     if (workgroups <= 0 || workgroups > (1 << 20) || iters <= 0) return SAGE_ERR_SHAPE;
     if (!aligned(data, 16) || !aligned(out, 8)) return SAGE_ERR_ALIGN;

@@ -52,6 +52,10 @@ typedef int mb_v2i __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ void mb_small(mb_v4f& acc, const mb_v2i& a, const mb_v2i& b) {
     asm volatile("v_mfma_f32_4x4x4_16b_f16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
 }
+typedef int mb_v4i32 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void mb_mid_i8(mb_v4i32& acc, const mb_v4i& a, const mb_v4i& b) {
+    asm volatile("v_mfma_i32_16x16x64_i8 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+}
 __device__ __forceinline__ void mb_mid(mb_v4f& acc, const mb_v8h& a, const mb_v8h& b) {
     asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
 }
@@ -100,8 +104,8 @@ template <int KIND>
 __global__ void __launch_bounds__(512) microbench_kernel(const int* __restrict__ data, unsigned long long* __restrict__ out,
                                                          int iters) {
     // 48 KB: a 64-key K^ tile (8 KB) and V tile (16 KB) of the attention kernel at D = 128, twice
-    __shared__ __attribute__((aligned(1024))) unsigned char tile[(KIND >= 7 && KIND <= 9) || KIND == 15 || KIND == 16 ? 49152 : 16];
-    if constexpr ((KIND >= 7 && KIND <= 9) || KIND == 15 || KIND == 16) {
+    __shared__ __attribute__((aligned(1024))) unsigned char tile[(KIND >= 7 && KIND <= 9) || KIND == 15 || KIND == 16 || KIND == 19 || KIND == 20 ? 49152 : 16];
+    if constexpr ((KIND >= 7 && KIND <= 9) || KIND == 15 || KIND == 16 || KIND == 19 || KIND == 20) {
         for (int i = threadIdx.x; i < 49152 / 4; i += blockDim.x) ((int*)tile)[i] = data[i & 1023] & 0x3BFF3BFF;
     }
     const int lane = threadIdx.x & 63;
@@ -130,6 +134,14 @@ __global__ void __launch_bounds__(512) microbench_kernel(const int* __restrict__
     for (int n = 0; n < 3; ++n) { sp.xs[n][0] = -0.25f * (float)(lane & 7); sp.xs[n][1] = -0.125f * (float)(lane & 15); }
     sp.in0 = -0.5f - (float)(lane & 3); sp.in1 = -0.75f; sp.sc = 1.001f; sp.bias = -0.5f;
     mb_v4f cl[2] = {{0.0f, 0.0f, 0.0f, 0.0f}, {0.0f, 0.0f, 0.0f, 0.0f}};
+    mb_v4f cm[4] = {{0.0f, 0.0f, 0.0f, 0.0f}, {0.0f, 0.0f, 0.0f, 0.0f}, {0.0f, 0.0f, 0.0f, 0.0f}, {0.0f, 0.0f, 0.0f, 0.0f}};
+    mb_v4i32 cmi[4] = {{0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}};
+    mb_v4f cm2[4] = {{0.0f, 0.0f, 0.0f, 0.0f}, {0.0f, 0.0f, 0.0f, 0.0f}, {0.0f, 0.0f, 0.0f, 0.0f}, {0.0f, 0.0f, 0.0f, 0.0f}};
+    mb_v4i32 cmi2[4] = {{0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}};
+    mb_v4f cm3[4] = {{0.0f, 0.0f, 0.0f, 0.0f}, {0.0f, 0.0f, 0.0f, 0.0f}, {0.0f, 0.0f, 0.0f, 0.0f}, {0.0f, 0.0f, 0.0f, 0.0f}};
+    mb_v4f cm4[4] = {{0.0f, 0.0f, 0.0f, 0.0f}, {0.0f, 0.0f, 0.0f, 0.0f}, {0.0f, 0.0f, 0.0f, 0.0f}, {0.0f, 0.0f, 0.0f, 0.0f}};
+    mb_v4i32 cmi3[4] = {{0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}};
+    mb_v4i32 cmi4[4] = {{0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}};
     const mb_v2i one2 = {0x3C003C00, 0x3C003C00}, bl = {ah[0], ah[1]}, bl2 = {ah[2], ah[3]};
     int mx = lane, mu = lane ^ 5, mv = 63 - lane;       // operands of the three-way maxima (never matrix results)
 
@@ -171,6 +183,102 @@ __global__ void __launch_bounds__(512) microbench_kernel(const int* __restrict__
 #pragma unroll
                 for (int n = 0; n < 8; ++n) mb_f16(cf[n & 3], af, bf);
             }
+        } else if constexpr (KIND == 19) {
+            // Kind 15's step with the 16x16 instructions: every operand read from LDS feeds TWO matrix
+            // instructions (two 16-query blocks), 32 FP16 16x16x32 + 16 INT8 16x16x64 + 4 row-sum instructions
+            // per step -- the same operations, LDS reads, maxima and chunks as kind 15.
+            mb_v4i ring[4];
+            auto fetch = [&](int n) {
+                if (n >= 16) {
+                    ring[n & 3] = *(const mb_v4i*)(tile + k_operand_at(lane, (n - 16) >> 2, n & 3));
+                } else {
+                    const int at = 16384 + v_operand_at(lane, n >> 2, n & 3);
+                    mb_v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(MB_LDS(mb_v4s, tile + at));
+                    mb_v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(MB_LDS(mb_v4s, tile + at + 2048));
+                    ring[n & 3] = __builtin_bit_cast(mb_v4i, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+                }
+            };
+            if (it == 0) { fetch(0); fetch(1); fetch(2); }
+#pragma unroll
+            for (int n = 0; n < 24; ++n) {
+                if (n >= 16) {
+                    mb_mid_i8(cmi[n & 3], ring[n & 3], b8);
+                    mb_mid_i8(cmi2[n & 3], ring[n & 3], a8);
+                } else {
+                    mb_mid(cm[n & 3], __builtin_bit_cast(mb_v8h, ring[n & 3]), bf);
+                    mb_mid(cm2[n & 3], __builtin_bit_cast(mb_v8h, ring[n & 3]), af);
+                }
+                fetch((n + 3) % 24);
+                __builtin_amdgcn_sched_barrier(0);
+                if (n < 4) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) { asm volatile("" : "+v"(mu), "+v"(mv)); mx = max(max(mx, mu), mv); asm volatile("" : "+v"(mx)); }
+                } else if (n < 20) {
+                    sp.tick(n - 4);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                if (n < 16 && n % 4 == 3) { mb_mid(cl[(n >> 2) & 1], af, bf); __builtin_amdgcn_sched_barrier(0); }
+            }
+        } else if constexpr (KIND == 20) {
+            // Kind 19 for a wavefront of 64 queries: every operand read from LDS feeds FOUR 16x16 instructions,
+            // the softmax work doubles (32 chunks, 32 maxima, 8 row-sum instructions), the LDS reads stay --
+            // twice kind 15's operations per group.
+            mb_v4i ring[4];
+            auto fetch = [&](int n) {
+                if (n >= 16) {
+                    ring[n & 3] = *(const mb_v4i*)(tile + k_operand_at(lane, (n - 16) >> 2, n & 3));
+                } else {
+                    const int at = 16384 + v_operand_at(lane, n >> 2, n & 3);
+                    mb_v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(MB_LDS(mb_v4s, tile + at));
+                    mb_v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(MB_LDS(mb_v4s, tile + at + 2048));
+                    ring[n & 3] = __builtin_bit_cast(mb_v4i, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+                }
+            };
+            if (it == 0) { fetch(0); fetch(1); fetch(2); }
+#pragma unroll
+            for (int n = 0; n < 24; ++n) {
+                if (n >= 16) {
+                    mb_mid_i8(cmi[n & 3], ring[n & 3], b8);
+                    mb_mid_i8(cmi2[n & 3], ring[n & 3], a8);
+                } else {
+                    mb_mid(cm[n & 3], __builtin_bit_cast(mb_v8h, ring[n & 3]), bf);
+                    mb_mid(cm2[n & 3], __builtin_bit_cast(mb_v8h, ring[n & 3]), af);
+                }
+                fetch((n + 3) % 24);
+                __builtin_amdgcn_sched_barrier(0);
+                if (n < 4) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) { asm volatile("" : "+v"(mu), "+v"(mv)); mx = max(max(mx, mu), mv); asm volatile("" : "+v"(mx)); }
+                } else if (n < 20) {
+                    sp.tick(2 * (n - 4));
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                if (n >= 16) {
+                    mb_mid_i8(cmi3[n & 3], ring[n & 3], b8);
+                    mb_mid_i8(cmi4[n & 3], ring[n & 3], a8);
+                } else {
+                    mb_mid(cm3[n & 3], __builtin_bit_cast(mb_v8h, ring[n & 3]), bf);
+                    mb_mid(cm4[n & 3], __builtin_bit_cast(mb_v8h, ring[n & 3]), af);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                if (n < 4) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) { asm volatile("" : "+v"(mu), "+v"(mv)); mx = max(max(mx, mu), mv); asm volatile("" : "+v"(mx)); }
+                } else if (n < 20) {
+                    sp.tick(2 * (n - 4) + 1);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                if (n < 16 && n % 4 == 3) { mb_mid(cl[0], af, bf); mb_mid(cl[1], af, bf); __builtin_amdgcn_sched_barrier(0); }
+            }
+        } else if constexpr (KIND == 17) {
+            // 16 of the 16x16x32 FP16 instruction (half the result block, twice the contraction depth of the
+            // 32x32x16 one): the same 8 * 32768 operations as kind 1
+#pragma unroll
+            for (int n = 0; n < 16; ++n) mb_mid(cm[n & 3], af, bf);
+        } else if constexpr (KIND == 18) {
+            // 16 of the 16x16x64 INT8 instruction: the same 8 * 65536 operations as kind 0
+#pragma unroll
+            for (int n = 0; n < 16; ++n) mb_mid_i8(cmi[n & 3], a8, b8);
         } else if constexpr (KIND == 14) {
 #pragma unroll
             for (int n = 0; n < 8; ++n) mb_i8(ci[0], a8, b8);
@@ -286,8 +394,18 @@ __global__ void __launch_bounds__(512) microbench_kernel(const int* __restrict__
     asm volatile("s_nop 11" : "+v"(ci[0]), "+v"(ci[1]), "+v"(ci[2]), "+v"(ci[3]));
     asm volatile("s_nop 11" : "+v"(cf[0]), "+v"(cf[1]), "+v"(cf[2]), "+v"(cf[3]));
     asm volatile("s_nop 11" : "+v"(cl[0]), "+v"(cl[1]));
-    float sum = cl[0][0] + cl[1][0] + cl[0][3] + cl[1][2];
-    int isum = mx;
+    asm volatile("s_nop 11" : "+v"(cm[0]), "+v"(cm[1]), "+v"(cm[2]), "+v"(cm[3]));
+    asm volatile("s_nop 11" : "+v"(cmi[0]), "+v"(cmi[1]), "+v"(cmi[2]), "+v"(cmi[3]));
+    asm volatile("s_nop 11" : "+v"(cm2[0]), "+v"(cm2[1]), "+v"(cm2[2]), "+v"(cm2[3]));
+    asm volatile("s_nop 11" : "+v"(cmi2[0]), "+v"(cmi2[1]), "+v"(cmi2[2]), "+v"(cmi2[3]));
+    asm volatile("s_nop 11" : "+v"(cm3[0]), "+v"(cm3[1]), "+v"(cm3[2]), "+v"(cm3[3]));
+    asm volatile("s_nop 11" : "+v"(cm4[0]), "+v"(cm4[1]), "+v"(cm4[2]), "+v"(cm4[3]));
+    asm volatile("s_nop 11" : "+v"(cmi3[0]), "+v"(cmi3[1]), "+v"(cmi3[2]), "+v"(cmi3[3]));
+    asm volatile("s_nop 11" : "+v"(cmi4[0]), "+v"(cmi4[1]), "+v"(cmi4[2]), "+v"(cmi4[3]));
+    float sum = cl[0][0] + cl[1][0] + cl[0][3] + cl[1][2] + cm[0][0] + cm[1][1] + cm[2][2] + cm[3][3] + cm2[0][0] + cm2[1][1] + cm2[2][2] + cm2[3][3]
+                + cm3[0][0] + cm3[1][1] + cm3[2][2] + cm3[3][3] + cm4[0][0] + cm4[1][1] + cm4[2][2] + cm4[3][3];
+    int isum = mx ^ cmi[0][0] ^ cmi[1][1] ^ cmi[2][2] ^ cmi[3][3] ^ cmi2[0][0] ^ cmi2[1][1] ^ cmi2[2][2] ^ cmi2[3][3]
+               ^ cmi3[0][0] ^ cmi3[1][1] ^ cmi3[2][2] ^ cmi3[3][3] ^ cmi4[0][0] ^ cmi4[1][1] ^ cmi4[2][2] ^ cmi4[3][3];
 #pragma unroll
     for (int n = 0; n < 4; ++n) {
 #pragma unroll
@@ -325,6 +443,10 @@ hipError_t launch_microbench(int kind, int waves_per_simd, int workgroups, int i
         case 14: microbench_kernel<14><<<workgroups, threads, 0, st>>>(data, out, iters); break;
         case 15: microbench_kernel<15><<<workgroups, threads, 0, st>>>(data, out, iters); break;
         case 16: microbench_kernel<16><<<workgroups, threads, 0, st>>>(data, out, iters); break;
+        case 17: microbench_kernel<17><<<workgroups, threads, 0, st>>>(data, out, iters); break;
+        case 18: microbench_kernel<18><<<workgroups, threads, 0, st>>>(data, out, iters); break;
+        case 19: microbench_kernel<19><<<workgroups, threads, 0, st>>>(data, out, iters); break;
+        case 20: microbench_kernel<20><<<workgroups, threads, 0, st>>>(data, out, iters); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

@@ -33,12 +33,12 @@ def test_matrix_streams_take_32_clocks_per_instruction():
 
 
 def test_every_probe_runs_and_is_deterministic():
-    for kind in range(17):
+    for kind in range(21):
         waves = 2 if kind == 5 else 1
         a, _ = probe(kind, waves, iters=50, workgroups=16)
         b, _ = probe(kind, waves, iters=50, workgroups=16)
         assert np.array_equal(a[:, 2], b[:, 2]), f"kind {kind}: checksums differ between two runs"
         assert np.all(a[:, 0] > 0)
     with pytest.raises(sage.SageError) as e:
-        probe(17, 1, iters=10, workgroups=4)
+        probe(21, 1, iters=10, workgroups=4)
     assert e.value.status == 3
