@@ -94,6 +94,9 @@ __device__ __forceinline__ void k_colsum_body(const _Float16* __restrict__ k,
             const int r = r0 + i * RG;
             x[i] = load_row8<D, ROPE>(base + (size_t)r * D, c8, cs + (size_t)r * (D / 2), sn + (size_t)r * (D / 2));
         }
+        // every load of the batch is issued before the first is used: without this fence the compiler's
+        // scheduler sinks each load to its use -- one load in flight instead of eight, a third slower
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < BATCH; ++i)
 #pragma unroll
@@ -107,6 +110,7 @@ __device__ __forceinline__ void k_colsum_body(const _Float16* __restrict__ k,
             const int rc = r < row_end ? r : row_end - 1;
             x[i] = load_row8<D, ROPE>(base + (size_t)rc * D, c8, cs + (size_t)rc * (D / 2), sn + (size_t)rc * (D / 2));
         }
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < BATCH; ++i) {
             const double live = whole + rg + i * RG < row_end ? 1.0 : 0.0;
@@ -200,6 +204,7 @@ __device__ __forceinline__ void quant_block_body(const _Float16* __restrict__ x,
             raw[i] = load_row8<D, ROPE>(xb + (size_t)rc * D, c8, cs + (size_t)(row0 + rc) * (D / 2),
                                         sn + (size_t)(row0 + rc) * (D / 2));
         }
+        __builtin_amdgcn_sched_barrier(0);       // all loads of the block issued here, none sunk to its use
     };
     h8 raw[LPT], ahead[LPT];
     int g = bx;                    // the launcher never starts more workgroups than there are blocks
@@ -315,6 +320,7 @@ __device__ __forceinline__ void quant_token_body(const _Float16* __restrict__ x,
             const int rc = r < N ? r : N - 1;
             raw[i] = load_row8<D, ROPE>(xs + (size_t)rc * D, c8, cs + (size_t)rc * (D / 2), sn + (size_t)rc * (D / 2));
         }
+        __builtin_amdgcn_sched_barrier(0);       // all loads of the group issued here, none sunk to its use
 #pragma unroll
         for (int i = 0; i < TOK_LPT; ++i) {
             const int r = row0 + rbase + i * RSTEP;
@@ -391,6 +397,7 @@ __device__ __forceinline__ void k_small_body(const _Float16* __restrict__ k,
             x[i] = load_row8<D, ROPE>(base + (size_t)rc * D, c8, cs + (size_t)rc * HALF, sn + (size_t)rc * HALF);
         }
     }
+    __builtin_amdgcn_sched_barrier(0);           // the whole slab requested before anything is used
     // ---- exact column sums in fp64: multiples of 2^-24 below 2^16 in magnitude, at most 32 per thread --
     // every partial sum fits 53 bits; then an exact conversion to a count of 2^-24 units
     double acc_d[8];
