@@ -42,6 +42,7 @@ __global__ void __launch_bounds__(256) v_absmax_kernel(const _Float16* __restric
         const int r = row_base + i * RG;
         x[i] = *(const vh8*)(base + (size_t)(r < N ? r : N - 1) * D + c8 * 8);
     }
+    __builtin_amdgcn_sched_barrier(0);       // the fence that keeps the compiler from sinking each load to its use
 #pragma unroll
     for (int i = 0; i < RPT; ++i)
 #pragma unroll
@@ -86,7 +87,11 @@ __global__ void __launch_bounds__(256) v_quant_transpose_kernel(const _Float16* 
         const int row = tile * ROWS + 4 * g + i;
         // rows past the end: fetched from the last row, then zeroed (no load sits behind a branch)
         x[i] = *(const vh8*)(base + (size_t)(row < N ? row : N - 1) * D + c8 * 8);
-        if (row >= N) {
+    }
+    __builtin_amdgcn_sched_barrier(0);       // all four loads issued before the first is touched
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        if (tile * ROWS + 4 * g + i >= N) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) x[i][e] = (_Float16)0.0f;
         }
