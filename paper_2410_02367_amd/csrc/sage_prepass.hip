@@ -27,31 +27,47 @@ typedef _Float16 h8 __attribute__((ext_vector_type(8)));
 // would have stored, so that the fused pre-pass returns exactly what the unfused one returns.
 // cos_row / sin_row point at the D/2 fp32 table entries of the token's position.  The partner
 // chunk is a second 16-byte load from the same cache line(s).
+// The loads and the arithmetic are separate steps (fetch_row8 / finish_row8), so that a kernel can have
+// the loads of several rows in flight before it rotates the first one.
+template <bool ROPE> struct RowRaw;
+template <> struct RowRaw<false> { h8 own; };
+template <> struct RowRaw<true> { h8 own, partner; float4 c0, c1, s0, s1; };
+
 template <int D, bool ROPE>
-__device__ __forceinline__ h8 load_row8(const _Float16* __restrict__ row, int c8,
-                                        const float* __restrict__ cos_row, const float* __restrict__ sin_row) {
-    const h8 own = *(const h8*)(row + c8 * 8);
-    if constexpr (!ROPE) {
-        return own;
-    } else {
+__device__ __forceinline__ RowRaw<ROPE> fetch_row8(const _Float16* __restrict__ row, int c8,
+                                                   const float* __restrict__ cos_row, const float* __restrict__ sin_row) {
+    RowRaw<ROPE> r;
+    r.own = *(const h8*)(row + c8 * 8);
+    if constexpr (ROPE) {
         constexpr int HALF = D / 2;
         const int c = c8 * 8;
         const bool upper = c >= HALF;
         const int cp = upper ? c - HALF : c + HALF, ct = upper ? c - HALF : c;
-        const h8 partner = *(const h8*)(row + cp);
-        const float4 c0 = *(const float4*)(cos_row + ct), c1 = *(const float4*)(cos_row + ct + 4);
-        const float4 s0 = *(const float4*)(sin_row + ct), s1 = *(const float4*)(sin_row + ct + 4);
-        const float cs[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
-        const float sn[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
+        r.partner = *(const h8*)(row + cp);
+        r.c0 = *(const float4*)(cos_row + ct); r.c1 = *(const float4*)(cos_row + ct + 4);
+        r.s0 = *(const float4*)(sin_row + ct); r.s1 = *(const float4*)(sin_row + ct + 4);
+    }
+    return r;
+}
+template <int D, bool ROPE>
+__device__ __forceinline__ h8 finish_row8(const RowRaw<ROPE>& r, int c8) {
+    if constexpr (!ROPE) {
+        return r.own;
+    } else {
+        const bool upper = c8 * 8 >= D / 2;
+        const float cs[8] = {r.c0.x, r.c0.y, r.c0.z, r.c0.w, r.c1.x, r.c1.y, r.c1.z, r.c1.w};
+        const float sn[8] = {r.s0.x, r.s0.y, r.s0.z, r.s0.w, r.s1.x, r.s1.y, r.s1.z, r.s1.w};
         h8 y;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            const float oc = (float)own[e] * cs[e], ps = (float)partner[e] * sn[e];
+            const float oc = (float)r.own[e] * cs[e], ps = (float)r.partner[e] * sn[e];
             y[e] = (_Float16)(upper ? oc + ps : oc - ps);
         }
         return y;
     }
 }
+// rows in flight per thread where a kernel batches them: a fetched row is 4 registers, 24 with RoPE
+template <bool ROPE> constexpr int rows_in_flight(int plain) { return ROPE ? (plain < 4 ? plain : 4) : plain; }
 
 // Exact column sums, first level: the workgroup (chunk p, slab bh) of grid (P, BH) sums the rows
 // p * chunk .. of its slab and leaves the D sums as 64-bit integers at part[(bh * P + p) * D ..];
@@ -69,7 +85,7 @@ __device__ __forceinline__ void k_colsum_body(const _Float16* __restrict__ k,
                                               int bx, int P, int bh) {
     constexpr int VPR = D / 8;          // 16-byte vectors per token row
     constexpr int RG = NT / VPR;        // row groups per workgroup
-    constexpr int BATCH = 8;            // rows per thread in flight
+    constexpr int BATCH = rows_in_flight<ROPE>(8);      // rows per thread in flight
     const int t = threadIdx.x, c8 = t % VPR, rg = t / VPR;
     const int row_begin = bx * chunk;
     const int row_end = row_begin + chunk < N ? row_begin + chunk : N;
@@ -88,34 +104,37 @@ __device__ __forceinline__ void k_colsum_body(const _Float16* __restrict__ k,
     // at most one ragged batch whose rows past the end are fetched from the last row and not added
     const int whole = row_begin + (row_end - row_begin) / (BATCH * RG) * (BATCH * RG);
     for (int r0 = row_begin + rg; r0 < whole; r0 += BATCH * RG) {
-        h8 x[BATCH];
+        RowRaw<ROPE> xr[BATCH];
 #pragma unroll
         for (int i = 0; i < BATCH; ++i) {
             const int r = r0 + i * RG;
-            x[i] = load_row8<D, ROPE>(base + (size_t)r * D, c8, cs + (size_t)r * (D / 2), sn + (size_t)r * (D / 2));
+            xr[i] = fetch_row8<D, ROPE>(base + (size_t)r * D, c8, cs + (size_t)r * (D / 2), sn + (size_t)r * (D / 2));
         }
         // every load of the batch is issued before the first is used: without this fence the compiler's
         // scheduler sinks each load to its use -- one load in flight instead of eight, a third slower
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int i = 0; i < BATCH; ++i)
+        for (int i = 0; i < BATCH; ++i) {
+            const h8 x = finish_row8<D, ROPE>(xr[i], c8);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) acc_d[e] += (double)(float)x[i][e];
+            for (int e = 0; e < 8; ++e) acc_d[e] += (double)(float)x[e];
+        }
     }
     if (whole < row_end) {
-        h8 x[BATCH];
+        RowRaw<ROPE> xr[BATCH];
 #pragma unroll
         for (int i = 0; i < BATCH; ++i) {
             const int r = whole + rg + i * RG;
             const int rc = r < row_end ? r : row_end - 1;
-            x[i] = load_row8<D, ROPE>(base + (size_t)rc * D, c8, cs + (size_t)rc * (D / 2), sn + (size_t)rc * (D / 2));
+            xr[i] = fetch_row8<D, ROPE>(base + (size_t)rc * D, c8, cs + (size_t)rc * (D / 2), sn + (size_t)rc * (D / 2));
         }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < BATCH; ++i) {
             const double live = whole + rg + i * RG < row_end ? 1.0 : 0.0;
+            const h8 x = finish_row8<D, ROPE>(xr[i], c8);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) acc_d[e] += live * (double)(float)x[i][e];
+            for (int e = 0; e < 8; ++e) acc_d[e] += live * (double)(float)x[e];
         }
     }
     // exact conversion to a count of 2^-24 units: |v| < 2^53 is split into a 27-bit and a 26-bit part
@@ -193,7 +212,7 @@ __device__ __forceinline__ void quant_block_body(const _Float16* __restrict__ x,
     __shared__ float s_mean[D];
     __shared__ float s_red[2][NT / 64];
     // the LPT rows of block g that this thread owns (rows past the end of the block: its last row)
-    auto load_block = [&](int g, h8 (&raw)[LPT]) {
+    auto fetch_block = [&](int g, RowRaw<ROPE> (&dst)[LPT]) {
         const int row0 = g * block;
         const int rows = (N - row0 < block) ? (N - row0) : block;
         const _Float16* xb = x + ((size_t)bh * N + row0) * D;
@@ -201,14 +220,16 @@ __device__ __forceinline__ void quant_block_body(const _Float16* __restrict__ x,
         for (int i = 0; i < LPT; ++i) {
             const int r = rbase + i * RSTEP;
             const int rc = r < rows ? r : rows - 1;
-            raw[i] = load_row8<D, ROPE>(xb + (size_t)rc * D, c8, cs + (size_t)(row0 + rc) * (D / 2),
-                                        sn + (size_t)(row0 + rc) * (D / 2));
+            dst[i] = fetch_row8<D, ROPE>(xb + (size_t)rc * D, c8, cs + (size_t)(row0 + rc) * (D / 2),
+                                         sn + (size_t)(row0 + rc) * (D / 2));
         }
         __builtin_amdgcn_sched_barrier(0);       // all loads of the block issued here, none sunk to its use
     };
-    h8 raw[LPT], ahead[LPT];
+    static_assert(!ROPE || LPT <= 4, "a fetched row is 24 registers with RoPE");
+    RowRaw<ROPE> ahead[LPT];       // the loads of the block after the current one (or of the first)
+    h8 raw[LPT];                   // the current block's rows, rotated if ROPE
     int g = bx;                    // the launcher never starts more workgroups than there are blocks
-    load_block(g, raw);            // in flight while the mean is formed
+    fetch_block(g, ahead);         // in flight while the mean is formed
 
     float mean[8];
     if (IS_K) {
@@ -221,6 +242,8 @@ __device__ __forceinline__ void quant_block_body(const _Float16* __restrict__ x,
 #pragma unroll
         for (int e = 0; e < 8; ++e) mean[e] = s_mean[c8 * 8 + e];
     }
+#pragma unroll
+    for (int i = 0; i < LPT; ++i) raw[i] = finish_row8<D, ROPE>(ahead[i], c8);
 
     for (int turn = 0; g < nblk; g += gx, turn ^= 1) {
         const int row0 = g * block;
@@ -228,7 +251,7 @@ __device__ __forceinline__ void quant_block_body(const _Float16* __restrict__ x,
         const size_t slab = ((size_t)bh * N + row0) * D + c8 * 8;
         // the next block of this workgroup is requested before this one is reduced and stored
         const bool more = g + gx < nblk;
-        if (more) load_block(g + gx, ahead);
+        if (more) fetch_block(g + gx, ahead);
         float amax = 0.0f;
 #pragma unroll
         for (int i = 0; i < LPT; ++i) {
@@ -262,7 +285,7 @@ __device__ __forceinline__ void quant_block_body(const _Float16* __restrict__ x,
         }
         if (more) {
 #pragma unroll
-            for (int i = 0; i < LPT; ++i) raw[i] = ahead[i];
+            for (int i = 0; i < LPT; ++i) raw[i] = finish_row8<D, ROPE>(ahead[i], c8);
         }
     }
 }
@@ -313,22 +336,26 @@ __device__ __forceinline__ void quant_token_body(const _Float16* __restrict__ x,
     for (int grp = bx; grp < ngrp; grp += gx) {
         const int row0 = grp * ROWS;
         const _Float16* xs = x + (size_t)bh * N * D;
-        h8 raw[TOK_LPT];
+        constexpr int SUB = rows_in_flight<ROPE>(TOK_LPT);     // rows fetched together
 #pragma unroll
-        for (int i = 0; i < TOK_LPT; ++i) {
-            const int r = row0 + rbase + i * RSTEP;
+        for (int i0 = 0; i0 < TOK_LPT; i0 += SUB) {
+        RowRaw<ROPE> fetched[SUB];
+#pragma unroll
+        for (int i = 0; i < SUB; ++i) {
+            const int r = row0 + rbase + (i0 + i) * RSTEP;
             const int rc = r < N ? r : N - 1;
-            raw[i] = load_row8<D, ROPE>(xs + (size_t)rc * D, c8, cs + (size_t)rc * (D / 2), sn + (size_t)rc * (D / 2));
+            fetched[i] = fetch_row8<D, ROPE>(xs + (size_t)rc * D, c8, cs + (size_t)rc * (D / 2), sn + (size_t)rc * (D / 2));
         }
-        __builtin_amdgcn_sched_barrier(0);       // all loads of the group issued here, none sunk to its use
+        __builtin_amdgcn_sched_barrier(0);       // all loads of the batch issued here, none sunk to its use
 #pragma unroll
-        for (int i = 0; i < TOK_LPT; ++i) {
-            const int r = row0 + rbase + i * RSTEP;
+        for (int i = 0; i < SUB; ++i) {
+            const int r = row0 + rbase + (i0 + i) * RSTEP;
+            const h8 raw = finish_row8<D, ROPE>(fetched[i], c8);
             float f[8];
             float amax = 0.0f;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                f[e] = (float)raw[i][e];
+                f[e] = (float)raw[e];
                 f[e] = IS_K ? (f[e] - mean[e]) : (f[e] * sm_scale);
                 amax = __builtin_fmaxf(amax, __builtin_fabsf(f[e]));
             }
@@ -347,6 +374,7 @@ __device__ __forceinline__ void quant_token_body(const _Float16* __restrict__ x,
                 }
                 *(uint2*)(xq + ((size_t)bh * N + r) * D + c8 * 8) = make_uint2(w[0], w[1]);
             }
+        }
         }
     }
 }
@@ -390,14 +418,22 @@ __device__ __forceinline__ void k_small_body(const _Float16* __restrict__ k,
     // fetched from row N - 1 (no per-lane branch around a load) and left out of every sum and maximum
     const int nset = (N + RG - 1) / RG;
     h8 x[MAXR];
+    constexpr int SUB = rows_in_flight<ROPE>(MAXR);       // without RoPE the whole slab is requested at once
 #pragma unroll
-    for (int i = 0; i < MAXR; ++i) {
-        if (i < nset) {
-            const int r = rg + i * RG, rc = r < N ? r : N - 1;
-            x[i] = load_row8<D, ROPE>(base + (size_t)rc * D, c8, cs + (size_t)rc * HALF, sn + (size_t)rc * HALF);
+    for (int i0 = 0; i0 < MAXR; i0 += SUB) {
+        RowRaw<ROPE> fetched[SUB];
+#pragma unroll
+        for (int i = 0; i < SUB; ++i) {
+            if (i0 + i < nset) {
+                const int r = rg + (i0 + i) * RG, rc = r < N ? r : N - 1;
+                fetched[i] = fetch_row8<D, ROPE>(base + (size_t)rc * D, c8, cs + (size_t)rc * HALF, sn + (size_t)rc * HALF);
+            }
         }
+        __builtin_amdgcn_sched_barrier(0);       // requested before anything is used
+#pragma unroll
+        for (int i = 0; i < SUB; ++i)
+            if (i0 + i < nset) x[i0 + i] = finish_row8<D, ROPE>(fetched[i], c8);
     }
-    __builtin_amdgcn_sched_barrier(0);           // the whole slab requested before anything is used
     // ---- exact column sums in fp64: multiples of 2^-24 below 2^16 in magnitude, at most 32 per thread --
     // every partial sum fits 53 bits; then an exact conversion to a count of 2^-24 units
     double acc_d[8];
