@@ -545,7 +545,7 @@ def main():
     # wavefront at D = 128, two wavefronts share a SIMD's pipe)
     kernel_clock = None
     if not pv_int8 and not per_token and D == 128:
-        for _ in range(3):
+        for _ in range(10):      # back to back, so that the last launch sees the clock the load settles at
             _, clocks = sage.sage_attn_clock_debug(q_i8, q_scale, k_i8, k_scale, inputs[0][2], out, w.causal, bq, bk, stream)
         torch.cuda.synchronize()
         c = clocks.cpu().numpy().astype(np.float64)
@@ -554,7 +554,7 @@ def main():
                         "clocks_per_tile_and_wavefront": float(c[:, 0].sum() / c[:, 3].sum()),
                         "matrix_pipe_busy": float(2.0 * 832.0 * c[:, 3].sum() / c[:, 0].sum()),
                         "raises_of_the_maximum_per_wavefront": float(c[:, 2].mean()),
-                        "how": "sage_attn_clock_debug, third of three launches after the timed steps"}
+                        "how": "sage_attn_clock_debug, last of ten launches back to back after the timed steps"}
 
     # what the matrix pipe sustains with this kernel's own instructions, measured now on this GPU:
     # the pure INT8 stream (the peak `frac` is quoted against, as measured) and the kernel's instruction
