@@ -103,8 +103,21 @@ sage_attn_pv8_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qs
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
     const long gidx = (long)xcd * per_xcd + slot;
     if (slot >= per_xcd || gidx >= total_tiles) return;
-    const int unit = (int)(gidx / tiles_q);          // (slab, key chunk), chunk fastest
-    const int qt = tiles_q - 1 - (int)(gidx % tiles_q);
+    int unit = (int)(gidx / tiles_q);                // (slab, key chunk), chunk fastest
+    int qt = tiles_q - 1 - (int)(gidx % tiles_q);
+    // With a causal mask the query tiles of a slab differ in weight by up to tiles_q : 1.  When every XCD's
+    // range is a whole number of slabs it is walked tile-major instead: the heaviest query tile of each of
+    // its slabs first, the lightest ones last, so that the XCD's compute units run dry together.
+    // (Slab-major, the last slab's light tiles fill in behind the other slabs' heavy ones and the tail of the
+    // launch is as long as a heavy tile: measured 2-4 % at 16K, 12 % at 1.5K.)  Otherwise -- slab counts that
+    // do not divide by 8 -- the ranges cut through slabs, which is what balances the XCDs then, and stay as
+    // they are; so do launches without a mask, where every tile weighs the same and the slab-major order
+    // keeps one slab's K^/V in the L2 at a time.
+    if (CAUSAL && per_xcd % tiles_q == 0 && total_tiles == (long)per_xcd * 8) {
+        const int units_per_xcd = per_xcd / tiles_q;
+        unit = xcd * units_per_xcd + slot % units_per_xcd;
+        qt = tiles_q - 1 - slot / units_per_xcd;
+    }
     const int bh = SPLIT ? unit / n_splits : unit, split = SPLIT ? unit - bh * n_splits : 0;
 
     const int t = threadIdx.x, lane = t & 63;
