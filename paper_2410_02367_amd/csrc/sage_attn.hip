@@ -236,7 +236,7 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
                  const _Float16* __restrict__ vg, _Float16* __restrict__ og,
                  int32_t* __restrict__ sdump, float* __restrict__ lse, unsigned long long* __restrict__ clocks,
                  int Nq, int Nkv, int shift_q, int shift_k, int tiles_q, int per_xcd, long total_tiles,
-                 int BH, int n_splits, int chunk) {
+                 int BH, int n_splits, int chunk, int tm_group) {
     constexpr int NWAVES = NW, NTHREADS = NW * 64;
     constexpr int QTILE = NW * WROWS;   // query rows per workgroup
     constexpr int KROW = D;             // bytes per K^ row in LDS
@@ -262,18 +262,15 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
     if (slot >= per_xcd || gidx >= total_tiles) return;
     int unit = (int)(gidx / tiles_q);                // (slab, key chunk), chunk fastest
     int qt = tiles_q - 1 - (int)(gidx % tiles_q);
-    // With a causal mask the query tiles of a slab differ in weight by up to tiles_q : 1.  When every XCD's
-    // range is a whole number of slabs it is walked tile-major instead: the heaviest query tile of each of
-    // its slabs first, the lightest ones last, so that the XCD's compute units run dry together.
-    // (Slab-major, the last slab's light tiles fill in behind the other slabs' heavy ones and the tail of the
-    // launch is as long as a heavy tile: measured 2-4 % at 16K, 12 % at 1.5K.)  Otherwise -- slab counts that
-    // do not divide by 8 -- the ranges cut through slabs, which is what balances the XCDs then, and stay as
-    // they are; so do launches without a mask, where every tile weighs the same and the slab-major order
-    // keeps one slab's K^/V in the L2 at a time.
-    if (CAUSAL && per_xcd % tiles_q == 0 && total_tiles == (long)per_xcd * 8) {
-        const int units_per_xcd = per_xcd / tiles_q;
-        unit = xcd * units_per_xcd + slot % units_per_xcd;
-        qt = tiles_q - 1 - slot / units_per_xcd;
+    // With a causal mask the query tiles of a slab differ in weight by up to tiles_q : 1, and slab-major the
+    // last slab's light tiles fill in behind the other slabs' heavy ones: the tail of the launch is as long
+    // as a heavy tile.  tm_group > 0 (chosen by the launcher, see tile_major_group()): the XCD's range, a
+    // whole number of slabs, is walked in groups of tm_group slabs, tile-major inside a group -- the heaviest
+    // query tile of each of the group's slabs first, the lightest ones last.
+    if (tm_group > 0) {
+        const int gi = slot / (tm_group * tiles_q), r = slot % (tm_group * tiles_q);
+        unit = xcd * (per_xcd / tiles_q) + gi * tm_group + r % tm_group;
+        qt = tiles_q - 1 - r / tm_group;
     }
     const int bh = unit / n_splits, split = unit - bh * n_splits;
 
@@ -962,6 +959,21 @@ sage_attn_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qsc,
     }
 }
 
+// Causal launches: how many slabs (units) an XCD interleaves tile-major (0: none, slab-major as without a
+// mask).  Only when every XCD's range is a whole number of units -- otherwise the ranges cut through slabs,
+// which is what balances the XCDs then -- and only as many as keep their K^ and V (unit_bytes each) inside
+// the XCD's 4 MB L2 together: interleaving more trades the shorter tail for re-fetches from HBM (measured at
+// 16K keys, 6 MB per slab: 2.2 x the HBM traffic for 0-4 % of time, depending on the box; at 1.5K keys, where
+// 16 slabs fit, +14 % and no extra traffic).
+int tile_major_group(long total_tiles, int tiles_q, long unit_bytes) {
+    if (total_tiles % (8l * tiles_q) != 0) return 0;
+    const int units_per_xcd = (int)(total_tiles / 8 / tiles_q);
+    const long fit = (4l << 20) / (unit_bytes > 0 ? unit_bytes : 1);
+    int g = (int)(fit < units_per_xcd ? fit : units_per_xcd);
+    while (g > 1 && units_per_xcd % g != 0) --g;
+    return g > 1 ? g : 0;
+}
+
 template <int D, int NW>
 static hipError_t launch_dn(const int8_t* qq, const float* qscale, const int8_t* kq, const float* kscale,
                             const void* v, void* o, int32_t* sdump, int BH, int Nq, int N, int causal,
@@ -976,7 +988,8 @@ static hipError_t launch_dn(const int8_t* qq, const float* qscale, const int8_t*
     const _Float16* vp = (const _Float16*)v;
     _Float16* op = (_Float16*)o;
     const bool ktok = block_k == 1;
-#define SAGE_ARGS qq, qscale, kq, kscale, vp, op, sdump, sp.lse, clocks, Nq, N, shift_q, shift_k, tiles_q, per_xcd, total, BH, sp.n_splits, sp.chunk
+    const int tm_group = causal && !sdump ? tile_major_group(total, tiles_q, (long)(sp.n_splits > 1 ? sp.chunk : N) * 3 * D) : 0;
+#define SAGE_ARGS qq, qscale, kq, kscale, vp, op, sdump, sp.lse, clocks, Nq, N, shift_q, shift_k, tiles_q, per_xcd, total, BH, sp.n_splits, sp.chunk, tm_group
 #define SAGE_LAUNCH(C, DMP, KT) sage_attn_kernel<D, NW, C, DMP, KT><<<grid, NTHREADS, 0, st>>>(SAGE_ARGS)
     if (clocks != nullptr) {
         // the measurement build exists for the headline shape only: D = 128, 256-row workgroups, block scales

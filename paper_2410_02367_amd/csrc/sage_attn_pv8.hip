@@ -81,7 +81,7 @@ sage_attn_pv8_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qs
                      const int8_t* __restrict__ vt, const float* __restrict__ vsc,
                      _Float16* __restrict__ og, float* __restrict__ lse,
                      int Nq, int Nkv, int Np, int shift_q, int shift_k, int tiles_q, int per_xcd, long total_tiles,
-                     int BH, int n_splits, int chunk) {
+                     int BH, int n_splits, int chunk, int tm_group) {
     constexpr int NT = 256, QTILE = 128, KT = 64;
     constexpr int KS = D / 32, DT = D / 32;
     constexpr int KB = KT * D, VB = D * KT;            // bytes per K^ tile / V^^T tile
@@ -105,18 +105,11 @@ sage_attn_pv8_kernel(const int8_t* __restrict__ qi, const float* __restrict__ qs
     if (slot >= per_xcd || gidx >= total_tiles) return;
     int unit = (int)(gidx / tiles_q);                // (slab, key chunk), chunk fastest
     int qt = tiles_q - 1 - (int)(gidx % tiles_q);
-    // With a causal mask the query tiles of a slab differ in weight by up to tiles_q : 1.  When every XCD's
-    // range is a whole number of slabs it is walked tile-major instead: the heaviest query tile of each of
-    // its slabs first, the lightest ones last, so that the XCD's compute units run dry together.
-    // (Slab-major, the last slab's light tiles fill in behind the other slabs' heavy ones and the tail of the
-    // launch is as long as a heavy tile: measured 2-4 % at 16K, 12 % at 1.5K.)  Otherwise -- slab counts that
-    // do not divide by 8 -- the ranges cut through slabs, which is what balances the XCDs then, and stay as
-    // they are; so do launches without a mask, where every tile weighs the same and the slab-major order
-    // keeps one slab's K^/V in the L2 at a time.
-    if (CAUSAL && per_xcd % tiles_q == 0 && total_tiles == (long)per_xcd * 8) {
-        const int units_per_xcd = per_xcd / tiles_q;
-        unit = xcd * units_per_xcd + slot % units_per_xcd;
-        qt = tiles_q - 1 - slot / units_per_xcd;
+    // causal launches: groups of tm_group slabs walked tile-major, heaviest query tiles first (see sage_attn.hip)
+    if (tm_group > 0) {
+        const int gi = slot / (tm_group * tiles_q), r = slot % (tm_group * tiles_q);
+        unit = xcd * (per_xcd / tiles_q) + gi * tm_group + r % tm_group;
+        qt = tiles_q - 1 - r / tm_group;
     }
     const int bh = SPLIT ? unit / n_splits : unit, split = SPLIT ? unit - bh * n_splits : 0;
 
@@ -428,9 +421,10 @@ static hipError_t launch_pv8_d(const int8_t* qq, const float* qscale, const int8
     const long total = (long)BH * sp.n_splits * tiles_q;
     const int per_xcd = (int)((total + 7) / 8);
     const dim3 grid((unsigned)(per_xcd * 8)), block(256);
+    const int tm_group = causal ? tile_major_group(total, tiles_q, (long)(sp.n_splits > 1 ? sp.chunk : N) * 2 * D) : 0;
 #define SAGE_PV8_S(C, K, S) sage_attn_pv8_kernel<D, C, K, S><<<grid, block, 0, st>>>( \
         qq, qscale, kq, kscale, vt, vscale, (_Float16*)o, sp.lse, Nq, N, Np, shift_q, shift_k, tiles_q, per_xcd, total, \
-        BH, sp.n_splits, sp.chunk)
+        BH, sp.n_splits, sp.chunk, tm_group)
 #define SAGE_PV8(C, K) do { if (sp.n_splits > 1) SAGE_PV8_S(C, K, true); else SAGE_PV8_S(C, K, false); } while (0)
     if (causal) { if (ktok) SAGE_PV8(true, true); else SAGE_PV8(true, false); }
     else        { if (ktok) SAGE_PV8(false, true); else SAGE_PV8(false, false); }

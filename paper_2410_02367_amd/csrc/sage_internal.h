@@ -48,6 +48,8 @@ struct SplitPlan {
     int chunk;
     float* lse;
 };
+// slabs an XCD interleaves tile-major in a causal launch (0: none); see sage_attn.hip
+int tile_major_group(long total_tiles, int tiles_q, long unit_bytes);
 SplitPlan plan_split(int BH, int Nq, int N, int causal, int requested);
 hipError_t launch_attn_split(const int8_t* qq, const float* qscale, const int8_t* kq, const float* kscale,
                              const void* v, void* o, void* workspace, int BH, int Nq, int N, int D, int causal,
